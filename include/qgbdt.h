@@ -1,0 +1,201 @@
+/*
+ * qgbdt.h -- C ABI of the MI355X (gfx950) library for the hot path of quantized
+ * GBDT training (arxiv 2207.09682): gradient quantization with stochastic
+ * rounding, integer histogram construction in packed (gradient | hessian) bins,
+ * sibling subtraction, best-split search, stable row partition, leaf refit and
+ * the leaf-wise growth of one tree.
+ *
+ * Conventions
+ *  - Every pointer marked "dev" is device memory owned by the caller (the Python
+ *    binding hands in torch tensors); the library never frees or keeps it beyond
+ *    the call's enqueued work.  Pointers marked "host" are host memory.
+ *  - All work is enqueued on the context's HIP stream and is asynchronous; no
+ *    entry point synchronises unless it says so.
+ *  - Every function returns 0 (QGBDT_OK) or a negative QGBDT_E_* code;
+ *    qgbdt_last_error() gives a message.  No exception crosses the boundary.
+ *  - Layouts
+ *      bins   uint8 [n_rows][n_features], row-major, values in [0, n_bins)
+ *      gh     int16 [n_rows]: quantized gradient (signed) in the high byte,
+ *             quantized hessian (unsigned) in the low byte
+ *      hist   int64 [n_features][n_bins]: one packed word per bin, sum of g~ in
+ *             the upper 32 bits (signed), sum of h~ in the lower 32 bits
+ *             (unsigned) -- the packing of Sec. 6.2 at 32|32 width
+ *      rows   int32 row ids; a leaf is a contiguous slice [begin, begin+count)
+ *             of an index array, ascending inside the slice
+ */
+#ifndef QGBDT_H
+#define QGBDT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QGBDT_API __attribute__((visibility("default")))
+
+#define QGBDT_OK 0
+#define QGBDT_E_INVALID_ARG (-1)
+#define QGBDT_E_UNSUPPORTED (-2)
+#define QGBDT_E_OVERFLOW_RISK (-3)
+#define QGBDT_E_HIP (-4)
+#define QGBDT_E_ALLOC (-5)
+
+#define QGBDT_ROUND_STOCHASTIC 0 /* SR of Sec. 4.2 */
+#define QGBDT_ROUND_NEAREST 1    /* RN of Sec. 4.2 (half rounds up) */
+
+typedef struct qgbdt_ctx qgbdt_ctx;
+
+/* Problem shape a context is created for. */
+typedef struct {
+    int64_t n_rows;     /* N, 1 .. 2^31-1 */
+    int32_t n_features; /* J of Algorithm 1 */
+    int32_t n_bins;     /* bins per feature, 2 .. 256 */
+    int32_t bin_bytes;  /* 1 (uint8 bins) */
+    int32_t max_leaves; /* largest num_leaves grow_tree will be asked for */
+} qgbdt_shape;
+
+/* Training parameters of one tree. */
+typedef struct {
+    int32_t bits_g;           /* B for gradients, 2..8 (Sec. 4.1) */
+    int32_t bits_h;           /* B for hessians, 2..8 */
+    int32_t rounding;         /* QGBDT_ROUND_* */
+    int32_t num_leaves;       /* leaf budget of leaf-wise growth */
+    int32_t min_data_in_leaf; /* minimum (hessian-share estimated) rows per child */
+    int32_t acc_width;        /* local accumulator fields: 0 auto, 16 or 32 bits (Sec. 6.1, 7.4.3) */
+    uint64_t seed;            /* key of the counter-based RNG */
+    double min_sum_hessian;   /* minimum H~ * delta_h per child */
+} qgbdt_params;
+
+/* Totals of one leaf, input of the split search. */
+typedef struct {
+    int64_t n_rows;
+    int64_t sum_g; /* G~_s */
+    int64_t sum_h; /* H~_s */
+} qgbdt_leafstat;
+
+/* Best split of one leaf; feature = -1 (gain 0) when no candidate is valid. */
+typedef struct {
+    double gain; /* eq. (gain) of Sec. 4.1, fp64 */
+    int32_t feature;
+    int32_t bin; /* rows with bin <= this go left */
+    int64_t left_g, left_h, right_g, right_h;
+    int64_t left_count; /* hessian-share estimate, rounded half up */
+} qgbdt_split;
+
+/* Output of grow_tree: device arrays, all caller-allocated.
+ * split_* are in split order (entry k is the k-th split), leaf_* by leaf id. */
+typedef struct {
+    int32_t* n_leaves;        /* dev[1] */
+    int32_t* split_leaf;      /* dev[max_leaves-1] id of the leaf that was split */
+    int32_t* split_feature;   /* dev[max_leaves-1] */
+    int32_t* split_bin;       /* dev[max_leaves-1] */
+    double* split_gain;       /* dev[max_leaves-1] */
+    int64_t* split_stats;     /* dev[(max_leaves-1)*4] left_g, left_h, right_g, right_h */
+    int64_t* split_n_left;    /* dev[max_leaves-1] true number of rows sent left */
+    int64_t* leaf_begin;      /* dev[max_leaves] slice of row_idx_out */
+    int64_t* leaf_count;      /* dev[max_leaves] */
+    int64_t* leaf_sum_g;      /* dev[max_leaves] G~ of the leaf */
+    int64_t* leaf_sum_h;      /* dev[max_leaves] H~ of the leaf */
+    double* leaf_value;       /* dev[max_leaves] refit with FP gradients, eq. (leaf) */
+    double* leaf_value_quant; /* dev[max_leaves] -G~ delta_g / (H~ delta_h), Sec. 4.2 */
+    float* delta;             /* dev[2] delta_g, delta_h */
+    int64_t* hist_units;      /* dev[1] sum over histogram builds of rows*features accumulated */
+} qgbdt_tree;
+
+/* ---- lifecycle ---------------------------------------------------------- */
+
+/* Creates a context for `shape` on the current device and allocates its workspace
+ * (row-index double buffer, quantized gradients, one histogram per leaf, small
+ * descriptors).  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
+QGBDT_API int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream);
+/* Frees the workspace and the context.  Synchronises the stream first. */
+QGBDT_API int qgbdt_destroy(qgbdt_ctx* ctx);
+/* Changes the stream later calls enqueue on. */
+QGBDT_API int qgbdt_set_stream(qgbdt_ctx* ctx, void* stream);
+/* Message of the last error on this context (or of a failed create when ctx is NULL). */
+QGBDT_API const char* qgbdt_last_error(const qgbdt_ctx* ctx);
+/* Bytes of device workspace the context holds (host out). */
+QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
+
+/* ---- steps of the path ---------------------------------------------------- */
+
+/* Sec. 4.1 (interval lengths, eq. (scale)) and Sec. 4.2 (SR / RN).
+ * delta_g = max|g| / (2^(bits_g-1)-1), delta_h = max h / (2^bits_h-2) over all n rows,
+ * then g~ = Round(g/delta_g) in [-(2^(bits_g-1)-1), ..], h~ = Round(h/delta_h) in
+ * [0, 2^bits_h-2], fp32 arithmetic.  Stochastic rounding draws its uniform numbers
+ * from Philox-4x32-10 keyed by `seed` with counter (row, iteration): output word 0
+ * rounds g, word 1 rounds h, top 24 bits each.  g, h: dev float[n]; gh_out: dev
+ * int16[n]; delta_out: dev float[2].  n <= shape.n_rows. */
+QGBDT_API int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n,
+                             int32_t bits_g, int32_t bits_h, uint64_t seed, uint32_t iteration,
+                             int32_t rounding, int16_t* gh_out, float* delta_out);
+
+/* Algorithm 1 with quantized gradients (Sec. 4.1), accumulated in workgroup-local
+ * packed low-width bins and merged into the total histogram (Sec. 6.1, 6.2).
+ * Rows are row_idx[begin .. begin+count) (dev int32) or, when row_idx is NULL,
+ * begin .. begin+count.  bits_g/bits_h bound |g~|, h~ and set how many rows a local
+ * 16|16 accumulator may take before it is merged (Sec. 7.4.3); acc_width 0 picks the
+ * width, 16 / 32 force it.  hist_out: dev int64[n_features*n_bins], overwritten.
+ * QGBDT_E_OVERFLOW_RISK if count rows could overflow a 32-bit field. */
+QGBDT_API int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh,
+                           const int32_t* row_idx, int64_t begin, int64_t count, int32_t bits_g,
+                           int32_t bits_h, int32_t acc_width, int64_t* hist_out);
+
+/* sibling = parent - child, bin by bin on the packed words (exact: a child's sums
+ * never exceed its parent's).  All dev int64[n_features*n_bins]; sibling_out may
+ * alias parent. */
+QGBDT_API int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child,
+                              int64_t* sibling_out);
+
+/* Best split of each of n_hists leaves: thresholds of every feature enumerated
+ * (Sec. 3), integer prefix sums, fp64 gain of eq. (gain) (Sec. 4.1).  A candidate
+ * needs H~ > 0 on both sides, both estimated row counts >= min_data_in_leaf and both
+ * H~ delta_h >= min_sum_hessian; the strictly largest gain > 0 wins, ties go to the
+ * lowest feature, then the lowest bin.  hist: dev int64[n_hists][F][nb]; stats: dev
+ * [n_hists]; delta: dev float[2]; out: dev [n_hists]. */
+QGBDT_API int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists,
+                           const qgbdt_leafstat* stats, const float* delta,
+                           int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out);
+
+/* Stable partition of the slice row_idx[begin..begin+count) (the set I_s of
+ * Algorithm 1): rows with bins[row][feature] <= bin first, both sides keeping their
+ * order.  row_idx: dev int32, reordered in place; n_left_out: dev int64[1]. */
+QGBDT_API int qgbdt_partition_rows(qgbdt_ctx* ctx, const void* bins, int32_t* row_idx, int64_t begin,
+                         int64_t count, int32_t feature, int32_t bin, int64_t* n_left_out);
+
+/* Leaf values from the original FP gradients (eq. (leaf) of Sec. 3, refit of
+ * Sec. 4.2): value[l] = -sum g / sum h over row_idx[leaf_begin[l] .. +leaf_count[l]),
+ * fp64 sums; 0 when sum h <= 0.  leaf_begin, leaf_count: dev int64[n_leaves];
+ * value_out: dev double[n_leaves]. */
+QGBDT_API int qgbdt_refit_leaves(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
+                       const int64_t* leaf_begin, const int64_t* leaf_count, int32_t n_leaves,
+                       double* value_out);
+
+/* One tree, leaf-wise (Sec. 3, Sec. 7): quantize (g,h), build the root histogram,
+ * then repeatedly split the open leaf with the largest gain (ties: lowest id); the
+ * left child keeps the parent's id, the right child takes the next id; the child
+ * with fewer rows (tie: left) is built from its rows, its sibling by subtraction;
+ * stops at num_leaves or when no gain > 0 is left; leaf values are refit at the end.
+ * The whole tree is enqueued without any host synchronisation.  bins: dev; g, h: dev
+ * float[n_rows]; row_idx_out: dev int32[n_rows], leaf-ordered rows. */
+QGBDT_API int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const float* h,
+                    const qgbdt_params* params, uint32_t iteration, const qgbdt_tree* tree_out,
+                    int32_t* row_idx_out);
+
+/* ---- measurement ---------------------------------------------------------- */
+
+/* When on, every histogram-kernel launch is bracketed by HIP events on the
+ * context's stream. */
+QGBDT_API int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on);
+/* Synchronises the stream, returns the summed histogram-kernel time (ms), the
+ * number of launches and their summed algorithmic bytes since the last call, and
+ * resets the counters (host out pointers). */
+QGBDT_API int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches,
+                       double* hist_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGBDT_H */

@@ -172,6 +172,8 @@ def partition_rows(bins, row_idx, begin: int, count: int, feature: int, bin: int
     bins, bb = _bins(bins)
     F = bins.shape[1]
     out = np.array(row_idx, dtype=np.int32, copy=True)
+    if begin < 0 or count < 0 or begin + count > out.size:
+        raise ValueError("slice outside row_idx")
     nl = C.c_int64(0)
     _chk(lib().qgbdt_ref_partition_rows(_p(bins), bb, F, _p(out), C.c_int64(begin),
                                         C.c_int64(count), feature, bin, C.byref(nl)),

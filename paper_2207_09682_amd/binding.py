@@ -1,0 +1,274 @@
+"""Thin ctypes binding over libqgbdt.so (see include/qgbdt.h).
+
+Argument marshalling only: every step runs in the library's HIP kernels.  torch
+is used for device memory and the current stream.  There is no CPU path: the
+import of the library and every call fail loudly when the HIP library or a GPU
+is missing.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libqgbdt.so")
+
+ROUND_STOCHASTIC = 0
+ROUND_NEAREST = 1
+
+EXPORTS = [
+    "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
+    "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
+    "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
+    "qgbdt_set_profiling", "qgbdt_read_profile",
+]
+
+
+class Shape(C.Structure):
+    _fields_ = [("n_rows", C.c_int64), ("n_features", C.c_int32), ("n_bins", C.c_int32),
+                ("bin_bytes", C.c_int32), ("max_leaves", C.c_int32)]
+
+
+class Params(C.Structure):
+    _fields_ = [("bits_g", C.c_int32), ("bits_h", C.c_int32), ("rounding", C.c_int32),
+                ("num_leaves", C.c_int32), ("min_data_in_leaf", C.c_int32), ("acc_width", C.c_int32),
+                ("seed", C.c_uint64), ("min_sum_hessian", C.c_double)]
+
+
+class TreePtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "n_leaves", "split_leaf", "split_feature", "split_bin", "split_gain", "split_stats",
+        "split_n_left", "leaf_begin", "leaf_count", "leaf_sum_g", "leaf_sum_h", "leaf_value",
+        "leaf_value_quant", "delta", "hist_units")]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2207_09682_amd.build` "
+                               "(there is no CPU fallback)")
+        lib = C.CDLL(LIB_PATH)
+        lib.qgbdt_last_error.restype = C.c_char_p
+        lib.qgbdt_last_error.argtypes = [C.c_void_p]
+        lib.qgbdt_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Shape), C.c_void_p]
+        lib.qgbdt_destroy.argtypes = [C.c_void_p]
+        lib.qgbdt_set_stream.argtypes = [C.c_void_p, C.c_void_p]
+        lib.qgbdt_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+        lib.qgbdt_quantize_gradients.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                                 C.c_uint64, C.c_uint32, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.qgbdt_build_histograms.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                               C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        lib.qgbdt_subtract_histograms.argtypes = [C.c_void_p] * 4
+        lib.qgbdt_find_best_splits.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                               C.c_double, C.c_void_p]
+        lib.qgbdt_partition_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32,
+                                             C.c_int32, C.c_void_p]
+        lib.qgbdt_refit_leaves.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int32, C.c_void_p]
+        lib.qgbdt_grow_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_uint32,
+                                        C.POINTER(TreePtrs), C.c_void_p]
+        lib.qgbdt_set_profiling.argtypes = [C.c_void_p, C.c_int32]
+        lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        _lib = lib
+    return _lib
+
+
+class QgbdtError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"qgbdt error {code}: {msg}")
+        self.code = code
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+@dataclass
+class Tree:
+    """Device tensors written by grow_tree (see qgbdt_tree in include/qgbdt.h)."""
+    n_leaves: torch.Tensor
+    split_leaf: torch.Tensor
+    split_feature: torch.Tensor
+    split_bin: torch.Tensor
+    split_gain: torch.Tensor
+    split_stats: torch.Tensor
+    split_n_left: torch.Tensor
+    leaf_begin: torch.Tensor
+    leaf_count: torch.Tensor
+    leaf_sum_g: torch.Tensor
+    leaf_sum_h: torch.Tensor
+    leaf_value: torch.Tensor
+    leaf_value_quant: torch.Tensor
+    delta: torch.Tensor
+    hist_units: torch.Tensor
+    row_idx: torch.Tensor
+
+    def ptrs(self) -> TreePtrs:
+        p = TreePtrs()
+        for name, _ in TreePtrs._fields_:
+            setattr(p, name, getattr(self, name).data_ptr())
+        return p
+
+
+class Context:
+    """One qgbdt context: a problem shape, its device workspace and a stream."""
+
+    def __init__(self, n_rows: int, n_features: int, n_bins: int, max_leaves: int = 255, bin_bytes: int = 1,
+                 device: str | torch.device = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the qgbdt library runs on MI355X only (no CPU path)")
+        self.lib = load_library()
+        self.device = torch.device(device)
+        self.shape = Shape(n_rows, n_features, n_bins, bin_bytes, max_leaves)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            rc = self.lib.qgbdt_create(C.byref(self._h), C.byref(self.shape), C.c_void_p(stream))
+        if rc != 0:
+            raise QgbdtError(rc, self.lib.qgbdt_last_error(None).decode())
+
+    # -- helpers ---------------------------------------------------------------
+    def _chk(self, rc: int):
+        if rc != 0:
+            raise QgbdtError(rc, self.lib.qgbdt_last_error(self._h).decode())
+
+    def _sync_stream(self):
+        self.lib.qgbdt_set_stream(self._h, C.c_void_p(torch.cuda.current_stream(self.device).cuda_stream))
+
+    def close(self):
+        if self._h:
+            self.lib.qgbdt_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def workspace_bytes(self) -> int:
+        n = C.c_size_t(0)
+        self._chk(self.lib.qgbdt_workspace_bytes(self._h, C.byref(n)))
+        return n.value
+
+    # -- steps -------------------------------------------------------------------
+    def quantize_gradients(self, g, h, bits_g, bits_h, seed, iteration, rounding=ROUND_STOCHASTIC, gh_out=None,
+                           delta_out=None):
+        self._sync_stream()
+        n = g.numel()
+        gh = gh_out if gh_out is not None else torch.empty(n, dtype=torch.int16, device=self.device)
+        delta = delta_out if delta_out is not None else torch.empty(2, dtype=torch.float32, device=self.device)
+        self._chk(self.lib.qgbdt_quantize_gradients(self._h, _dev(g, torch.float32, "g"), _dev(h, torch.float32, "h"),
+                                                    n, bits_g, bits_h, seed, iteration, rounding,
+                                                    _dev(gh, torch.int16, "gh_out"), _dev(delta, torch.float32, "delta_out")))
+        return gh, delta
+
+    def build_histograms(self, bins, gh, row_idx=None, begin=0, count=None, bits_g=3, bits_h=3, acc_width=0,
+                         hist_out=None):
+        self._sync_stream()
+        if count is None:
+            count = (row_idx.numel() if row_idx is not None else bins.shape[0]) - begin
+        W = self.shape.n_features * self.shape.n_bins
+        hist = hist_out if hist_out is not None else torch.empty(W, dtype=torch.int64, device=self.device)
+        self._chk(self.lib.qgbdt_build_histograms(
+            self._h, _dev(bins, torch.uint8, "bins"), _dev(gh, torch.int16, "gh"),
+            _dev(row_idx, torch.int32, "row_idx") if row_idx is not None else None, begin, count, bits_g, bits_h,
+            acc_width, _dev(hist, torch.int64, "hist_out")))
+        return hist
+
+    def subtract_histograms(self, parent, child, out=None):
+        self._sync_stream()
+        out = out if out is not None else torch.empty_like(parent)
+        self._chk(self.lib.qgbdt_subtract_histograms(self._h, _dev(parent, torch.int64, "parent"),
+                                                     _dev(child, torch.int64, "child"), _dev(out, torch.int64, "out")))
+        return out
+
+    def find_best_splits(self, hist, stats, delta, min_data_in_leaf=20, min_sum_hessian=0.0):
+        """hist: int64 [n, F*nb]; stats: int64 [n, 3] (n_rows, sum_g, sum_h).
+        Returns a uint8 tensor [n, 56] holding qgbdt_split records (see unpack_splits)."""
+        self._sync_stream()
+        n = stats.shape[0]
+        out = torch.empty((n, 56), dtype=torch.uint8, device=self.device)
+        self._chk(self.lib.qgbdt_find_best_splits(self._h, _dev(hist, torch.int64, "hist"), n,
+                                                  _dev(stats, torch.int64, "stats"), _dev(delta, torch.float32, "delta"),
+                                                  min_data_in_leaf, min_sum_hessian, out.data_ptr()))
+        return out
+
+    def partition_rows(self, bins, row_idx, begin, count, feature, bin):
+        self._sync_stream()
+        n_left = torch.empty(1, dtype=torch.int64, device=self.device)
+        self._chk(self.lib.qgbdt_partition_rows(self._h, _dev(bins, torch.uint8, "bins"),
+                                                _dev(row_idx, torch.int32, "row_idx"), begin, count, feature, bin,
+                                                n_left.data_ptr()))
+        return n_left
+
+    def refit_leaves(self, g, h, row_idx, leaf_begin, leaf_count):
+        self._sync_stream()
+        n = leaf_begin.numel()
+        out = torch.empty(n, dtype=torch.float64, device=self.device)
+        self._chk(self.lib.qgbdt_refit_leaves(self._h, _dev(g, torch.float32, "g"), _dev(h, torch.float32, "h"),
+                                              _dev(row_idx, torch.int32, "row_idx"),
+                                              _dev(leaf_begin, torch.int64, "leaf_begin"),
+                                              _dev(leaf_count, torch.int64, "leaf_count"), n, out.data_ptr()))
+        return out
+
+    def new_tree(self) -> Tree:
+        L = self.shape.max_leaves
+        S = max(L - 1, 1)
+        d = self.device
+        z = lambda n, dt: torch.zeros(n, dtype=dt, device=d)
+        return Tree(z(1, torch.int32), z(S, torch.int32), z(S, torch.int32), z(S, torch.int32), z(S, torch.float64),
+                    z(S * 4, torch.int64), z(S, torch.int64), z(L, torch.int64), z(L, torch.int64), z(L, torch.int64),
+                    z(L, torch.int64), z(L, torch.float64), z(L, torch.float64), z(2, torch.float32),
+                    z(1, torch.int64), z(self.shape.n_rows, torch.int32))
+
+    def grow_tree(self, bins, g, h, bits_g, bits_h, seed, iteration, num_leaves, min_data_in_leaf=20,
+                  min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0, tree: Tree | None = None) -> Tree:
+        self._sync_stream()
+        tree = tree if tree is not None else self.new_tree()
+        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
+        tp = tree.ptrs()
+        self._chk(self.lib.qgbdt_grow_tree(self._h, _dev(bins, torch.uint8, "bins"), _dev(g, torch.float32, "g"),
+                                           _dev(h, torch.float32, "h"), C.byref(p), iteration, C.byref(tp),
+                                           _dev(tree.row_idx, torch.int32, "row_idx")))
+        return tree
+
+    # -- measurement -------------------------------------------------------------
+    def set_profiling(self, on: bool):
+        self._chk(self.lib.qgbdt_set_profiling(self._h, 1 if on else 0))
+
+    def read_profile(self):
+        ms = C.c_double(0); n = C.c_int64(0); b = C.c_double(0)
+        self._chk(self.lib.qgbdt_read_profile(self._h, C.byref(ms), C.byref(n), C.byref(b)))
+        return ms.value, n.value, b.value
+
+
+def unpack_splits(raw: torch.Tensor):
+    """Decodes qgbdt_split records (uint8 [n, 56]) into a list of dicts (host)."""
+    import struct
+    out = []
+    for rec in raw.cpu().numpy():
+        gain, feature, bin_, lg, lh, rg, rh, lc = struct.unpack("<diiqqqqq", rec.tobytes())
+        out.append(dict(gain=gain, feature=feature, bin=bin_, GL=lg, HL=lh, GR=rg, HR=rh, cnt_left=lc))
+    return out
+
+
+def unpack_hist(hist: torch.Tensor, n_features: int, n_bins: int):
+    """Packed int64 words -> (G int64 [F, nb], H int64 [F, nb]) on the host."""
+    w = hist.cpu().view(n_features, n_bins)
+    return (w >> 32).numpy(), (w & 0xFFFFFFFF).numpy()

@@ -1,0 +1,293 @@
+// C-ABI entry points of libqgbdt: argument checks, context and workspace
+// management, and the stand-alone forms of the steps (the kernels themselves live
+// next to their launchers).
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "split_device.h"
+
+static char g_create_error[512] = "";
+
+namespace qgbdt {
+
+int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx ? ctx->err : g_create_error, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+__global__ void set_hist_work_kernel(HistWork* w, int64_t begin, int64_t count, int use_idx) {
+    if (threadIdx.x == 0) { w->begin = begin; w->count = count; w->use_idx = use_idx; w->buf = 0; w->slot = 0; }
+}
+
+// sum of h~ and |g~| over a row set (only used when the a-priori bound cannot rule out overflow)
+__global__ __launch_bounds__(256) void gh_totals_kernel(const int16_t* __restrict__ gh, const int32_t* __restrict__ idx,
+                                                        int64_t begin, int64_t count, int64_t* totals) {
+    int64_t sh = 0, sa = 0;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < count; p += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = idx ? (int64_t)idx[begin + p] : begin + p;
+        const int v = gh[i];
+        sh += v & 0xff;
+        sa += abs(v >> 8);
+    }
+    for (int o = 32; o > 0; o >>= 1) { sh += __shfl_xor(sh, o); sa += __shfl_xor(sa, o); }
+    if ((threadIdx.x & 63) == 0) {
+        atomicAdd((unsigned long long*)&totals[1], (unsigned long long)sh);
+        atomicAdd((unsigned long long*)&totals[2], (unsigned long long)sa);
+    }
+}
+__global__ void zero3_kernel(int64_t* t) {
+    if (threadIdx.x < 3) t[threadIdx.x] = 0;
+}
+
+template <typename T>
+static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
+    const size_t bytes = (n ? n : 1) * sizeof(T);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
+    if (e != hipSuccess) return set_error(ctx, QGBDT_E_ALLOC, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    ctx->ws_bytes += bytes;
+    return QGBDT_OK;
+}
+
+static void free_all(qgbdt_ctx* c) {
+    void* ptrs[] = {c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->absmax, c->qtotals,
+                    c->delta, c->leaves, c->step, c->cand, c->hwork, c->pwork, c->scan_items, c->tmp_stats,
+                    c->refit_partial, c->tmp_i64};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    if (c->ev) {
+        for (int i = 0; i < c->ev_cap; ++i)
+            if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+        delete[] c->ev;
+    }
+}
+
+static int check_bits(qgbdt_ctx* ctx, int bits_g, int bits_h) {
+    if (bits_g < 2 || bits_g > 8 || bits_h < 2 || bits_h > 8)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "bits_g=%d, bits_h=%d outside 2..8", bits_g, bits_h);
+    return QGBDT_OK;
+}
+
+}  // namespace qgbdt
+
+using namespace qgbdt;
+
+extern "C" {
+
+int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
+    if (!out || !shape) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
+    *out = nullptr;
+    if (shape->n_rows < 1 || shape->n_rows > 2147483647LL || shape->n_features < 1 || shape->n_bins < 2 ||
+        shape->n_bins > 256 || shape->max_leaves < 1)
+        return set_error(nullptr, QGBDT_E_INVALID_ARG, "shape out of range (rows %lld, features %d, bins %d, leaves %d)",
+                         (long long)shape->n_rows, shape->n_features, shape->n_bins, shape->max_leaves);
+    if (shape->bin_bytes != 1)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "bin_bytes=%d: only uint8 bins are built", shape->bin_bytes);
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+        return set_error(nullptr, QGBDT_E_HIP, "no HIP device: this library has no CPU path");
+    qgbdt_ctx* c = new (std::nothrow) qgbdt_ctx();
+    if (!c) return set_error(nullptr, QGBDT_E_ALLOC, "out of host memory");
+    memset(c, 0, sizeof(*c));
+    c->shape = *shape;
+    c->stream = (hipStream_t)stream;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return set_error(nullptr, QGBDT_E_HIP, "hipGetDevice failed"); }
+    const int64_t N = shape->n_rows;
+    const int64_t W = (int64_t)shape->n_features * shape->n_bins;
+    const int L = shape->max_leaves;
+    int rc = QGBDT_OK;
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (L + 1)));
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->flags, (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->part_counts, (size_t)PART_GROUPS);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->absmax, 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals, 4);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->delta, 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->leaves, (size_t)L + 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->step, 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->cand, (size_t)2 * shape->n_features);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hwork, 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->pwork, 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, reinterpret_cast<ScanItem**>(&c->scan_items), 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_stats, 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->refit_partial, (size_t)L * REFIT_PARTS * 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_i64, 8);
+    if (rc == QGBDT_OK && hipMemset(c->step, 0, sizeof(StepState)) != hipSuccess)
+        rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
+    if (rc != QGBDT_OK) {
+        snprintf(g_create_error, sizeof(g_create_error), "%s", c->err);
+        free_all(c);
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return QGBDT_OK;
+}
+
+int qgbdt_destroy(qgbdt_ctx* ctx) {
+    if (!ctx) return QGBDT_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    free_all(ctx);
+    delete ctx;
+    return QGBDT_OK;
+}
+
+int qgbdt_set_stream(qgbdt_ctx* ctx, void* stream) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    ctx->stream = (hipStream_t)stream;
+    return QGBDT_OK;
+}
+
+const char* qgbdt_last_error(const qgbdt_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes) {
+    if (!ctx || !bytes) return QGBDT_E_INVALID_ARG;
+    *bytes = ctx->ws_bytes;
+    return QGBDT_OK;
+}
+
+int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int32_t bits_g,
+                             int32_t bits_h, uint64_t seed, uint32_t iteration, int32_t rounding, int16_t* gh_out,
+                             float* delta_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!g || !h || !gh_out || !delta_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
+    if (rounding != QGBDT_ROUND_STOCHASTIC && rounding != QGBDT_ROUND_NEAREST)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "rounding=%d", rounding);
+    int rc = check_bits(ctx, bits_g, bits_h);
+    if (rc != QGBDT_OK) return rc;
+    return launch_quantize(ctx, g, h, n, bits_g, bits_h, seed, iteration, rounding, gh_out, delta_out, nullptr);
+}
+
+int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, const int32_t* row_idx,
+                           int64_t begin, int64_t count, int32_t bits_g, int32_t bits_h, int32_t acc_width,
+                           int64_t* hist_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!bins || !gh || !hist_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (begin < 0 || count < 0 || begin + count > ctx->shape.n_rows)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "slice [%lld, +%lld) outside 0..n_rows", (long long)begin, (long long)count);
+    if (acc_width != 0 && acc_width != 16 && acc_width != 32)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "acc_width=%d (0, 16 or 32)", acc_width);
+    if (((uintptr_t)bins & 3) != 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "bins must be 4-byte aligned");
+    int rc = check_bits(ctx, bits_g, bits_h);
+    if (rc != QGBDT_OK) return rc;
+    const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
+    if (count > max_rows_for_width(bits_g, bits_h, 32)) {
+        // the a-priori bound fails: use the exact totals of these rows (synchronises)
+        int64_t tot[3];
+        hipLaunchKernelGGL(zero3_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->tmp_i64);
+        hipLaunchKernelGGL(gh_totals_kernel, dim3(1024), dim3(256), 0, ctx->stream, gh, row_idx, begin, count,
+                           ctx->tmp_i64);
+        QG_HIP(ctx, hipMemcpyAsync(tot, ctx->tmp_i64, sizeof(tot), hipMemcpyDeviceToHost, ctx->stream));
+        QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (tot[1] > 0xffffffffLL || tot[2] > 0x7fffffffLL)
+            return set_error(ctx, QGBDT_E_OVERFLOW_RISK, "sums of %lld rows do not fit 32|32 packed bins", (long long)count);
+    }
+    rc = launch_fill_zero(ctx, hist_out, W);
+    if (rc != QGBDT_OK) return rc;
+    if (count == 0) return QGBDT_OK;
+    const HistPlan plan = make_hist_plan(ctx->shape, bits_g, bits_h, acc_width);
+    hipLaunchKernelGGL(set_hist_work_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->hwork, begin, count,
+                       row_idx ? 1 : 0);
+    return launch_hist(ctx, plan, (const uint8_t*)bins, gh, row_idx, row_idx, ctx->hwork, hist_out, count, ctx->step);
+}
+
+int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* sibling_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!parent || !child || !sibling_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    return launch_subtract(ctx, parent, child, sibling_out, (int64_t)ctx->shape.n_features * ctx->shape.n_bins);
+}
+
+int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists, const qgbdt_leafstat* stats,
+                           const float* delta, int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!hist || !stats || !delta || !out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n_hists < 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "n_hists=%d", n_hists);
+    return run_find_best_splits(ctx, hist, n_hists, stats, delta, min_data_in_leaf, min_sum_hessian, out);
+}
+
+int qgbdt_partition_rows(qgbdt_ctx* ctx, const void* bins, int32_t* row_idx, int64_t begin, int64_t count,
+                         int32_t feature, int32_t bin, int64_t* n_left_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!bins || !row_idx || !n_left_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (begin < 0 || count < 0 || begin + count > ctx->shape.n_rows)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "slice [%lld, +%lld) outside 0..n_rows", (long long)begin, (long long)count);
+    if (feature < 0 || feature >= ctx->shape.n_features)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "feature=%d", feature);
+    return run_partition_rows(ctx, (const uint8_t*)bins, row_idx, begin, count, feature, bin, n_left_out);
+}
+
+int qgbdt_refit_leaves(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
+                       const int64_t* leaf_begin, const int64_t* leaf_count, int32_t n_leaves, double* value_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!g || !h || !row_idx || !leaf_begin || !leaf_count || !value_out)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n_leaves < 0 || n_leaves > ctx->shape.max_leaves)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "n_leaves=%d outside 0..max_leaves", n_leaves);
+    return launch_refit(ctx, g, h, row_idx, leaf_begin, leaf_count, n_leaves, nullptr, value_out);
+}
+
+int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const float* h, const qgbdt_params* p,
+                    uint32_t iteration, const qgbdt_tree* t, int32_t* row_idx_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!bins || !g || !h || !p || !t || !row_idx_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (!t->n_leaves || !t->split_leaf || !t->split_feature || !t->split_bin || !t->split_gain || !t->split_stats ||
+        !t->split_n_left || !t->leaf_begin || !t->leaf_count || !t->leaf_sum_g || !t->leaf_sum_h || !t->leaf_value ||
+        !t->leaf_value_quant || !t->delta || !t->hist_units)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer in qgbdt_tree");
+    if (p->num_leaves < 1 || p->num_leaves > ctx->shape.max_leaves)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "num_leaves=%d outside 1..max_leaves", p->num_leaves);
+    if (p->rounding != QGBDT_ROUND_STOCHASTIC && p->rounding != QGBDT_ROUND_NEAREST)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "rounding=%d", p->rounding);
+    if (p->acc_width != 0 && p->acc_width != 16 && p->acc_width != 32)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "acc_width=%d (0, 16 or 32)", p->acc_width);
+    if (((uintptr_t)bins & 3) != 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "bins must be 4-byte aligned");
+    int rc = check_bits(ctx, p->bits_g, p->bits_h);
+    if (rc != QGBDT_OK) return rc;
+    return run_grow_tree(ctx, (const uint8_t*)bins, g, h, p, iteration, t, row_idx_out);
+}
+
+int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (on && !ctx->ev) {
+        ctx->ev_cap = 16384;
+        ctx->ev = new (std::nothrow) hipEvent_t[ctx->ev_cap];
+        if (!ctx->ev) { ctx->ev_cap = 0; return set_error(ctx, QGBDT_E_ALLOC, "out of host memory"); }
+        memset(ctx->ev, 0, sizeof(hipEvent_t) * ctx->ev_cap);
+        for (int i = 0; i < ctx->ev_cap; ++i) QG_HIP(ctx, hipEventCreate(&ctx->ev[i]));
+    }
+    ctx->profiling = on ? 1 : 0;
+    return QGBDT_OK;
+}
+
+int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches, double* hist_bytes) {
+    if (!ctx || !hist_ms || !hist_launches || !hist_bytes) return QGBDT_E_INVALID_ARG;
+    QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double ms = 0.0;
+    for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float t = 0.0f;
+        QG_HIP(ctx, hipEventElapsedTime(&t, ctx->ev[i], ctx->ev[i + 1]));
+        ms += t;
+    }
+    StepState st;
+    QG_HIP(ctx, hipMemcpy(&st, ctx->step, sizeof(st), hipMemcpyDeviceToHost));
+    const double F = ctx->shape.n_features, nb = ctx->shape.n_bins;
+    // algorithmic bytes: a bin row and a packed (g~,h~) per row, a row id when gathered, one histogram per launch
+    *hist_bytes = (double)st.prof_rows_contig * (F + 2.0) + (double)st.prof_rows_idx * (F + 2.0 + 4.0) +
+                  (double)st.prof_launches * F * nb * 8.0;
+    *hist_ms = ms;
+    *hist_launches = st.prof_launches;
+    ctx->ev_used = 0;
+    ctx->prof_launches = 0;
+    st.prof_rows_contig = 0; st.prof_rows_idx = 0; st.prof_launches = 0;
+    QG_HIP(ctx, hipMemcpy(ctx->step, &st, sizeof(st), hipMemcpyHostToDevice));
+    return QGBDT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,155 @@
+// Stable row partition of a leaf's index slice (the set I_s of Algorithm 1) by
+// bins[row][feature] <= bin.  Two passes over a fixed grid: per-workgroup counts
+// of left-going rows (flags kept as bytes), then an order-preserving scatter into
+// the other index buffer with offsets from the counts.  No inter-workgroup waits.
+#include "common.h"
+
+namespace qgbdt {
+
+__device__ __forceinline__ int64_t segment_len(int64_t count, int groups) {
+    int64_t seg = (count + groups - 1) / groups;
+    return (seg + 255) / 256 * 256;
+}
+
+__global__ void fill_i64_kernel(int64_t* p, int64_t v) {
+    if (threadIdx.x == 0) *p = v;
+}
+
+__global__ void set_part_work_kernel(PartWork* w, int64_t begin, int64_t count, int feature, int bin) {
+    if (threadIdx.x == 0) {
+        w->begin = begin; w->count = count; w->feature = feature; w->bin = bin; w->src_buf = 0; w->zero_slot = -1;
+    }
+}
+
+__global__ __launch_bounds__(256) void part_count_kernel(const uint8_t* __restrict__ bins, int F,
+                                                         const int32_t* __restrict__ buf0,
+                                                         const int32_t* __restrict__ buf1,
+                                                         const PartWork* __restrict__ work,
+                                                         uint8_t* __restrict__ flags, int64_t* __restrict__ counts,
+                                                         int64_t* hist_base, int64_t hist_words) {
+    const PartWork wk = *work;
+    if (wk.count <= 0) {
+        if (threadIdx.x == 0) counts[blockIdx.x] = 0;
+        return;
+    }
+    if (wk.zero_slot >= 0) {  // clear the histogram the smaller child will be accumulated into
+        int64_t* z = hist_base + (int64_t)wk.zero_slot * hist_words;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < hist_words;
+             i += (int64_t)gridDim.x * blockDim.x)
+            z[i] = 0;
+    }
+    const int32_t* src = wk.src_buf ? buf1 : buf0;
+    const int64_t seg = segment_len(wk.count, gridDim.x);
+    const int64_t sbegin = (int64_t)blockIdx.x * seg;
+    const int64_t send = min(wk.count, sbegin + seg);
+    int cnt = 0;
+    for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
+        const int64_t row = src[wk.begin + p];
+        const int fl = bins[row * F + wk.feature] <= wk.bin;
+        flags[wk.begin + p] = (uint8_t)fl;
+        cnt += fl;
+    }
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    __shared__ int sc[4];
+    if ((threadIdx.x & 63) == 0) sc[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) counts[blockIdx.x] = (int64_t)sc[0] + sc[1] + sc[2] + sc[3];
+}
+
+__global__ __launch_bounds__(256) void part_scatter_kernel(const int32_t* __restrict__ buf0r,
+                                                           const int32_t* __restrict__ buf1r, int32_t* buf0w,
+                                                           int32_t* buf1w, const PartWork* __restrict__ work,
+                                                           const uint8_t* __restrict__ flags,
+                                                           const int64_t* __restrict__ counts, int64_t* n_left_out) {
+    const PartWork wk = *work;
+    if (wk.count <= 0) return;
+    const int32_t* src = wk.src_buf ? buf1r : buf0r;
+    int32_t* dst = wk.src_buf ? buf0w : buf1w;
+    // left rows before this segment, and in total
+    int64_t before = 0, total = 0;
+    for (int b = threadIdx.x; b < (int)gridDim.x; b += blockDim.x) {
+        const int64_t c = counts[b];
+        total += c;
+        if (b < (int)blockIdx.x) before += c;
+    }
+    for (int o = 32; o > 0; o >>= 1) { before += __shfl_xor(before, o); total += __shfl_xor(total, o); }
+    __shared__ int64_t sb[4], st[4];
+    __shared__ int wl[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sb[wave] = before; st[wave] = total; }
+    __syncthreads();
+    before = sb[0] + sb[1] + sb[2] + sb[3];
+    total = st[0] + st[1] + st[2] + st[3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_left_out = total;
+
+    const int64_t seg = segment_len(wk.count, gridDim.x);
+    const int64_t sbegin = (int64_t)blockIdx.x * seg;
+    const int64_t send = min(wk.count, sbegin + seg);
+    int64_t lpos = wk.begin + before;                      // next left slot
+    int64_t rpos = wk.begin + total + (sbegin - before);   // next right slot
+    for (int64_t t0 = sbegin; t0 < send; t0 += 256) {
+        const int64_t p = t0 + threadIdx.x;
+        const bool on = p < send;
+        int fl = 0;
+        int32_t v = 0;
+        if (on) { fl = flags[wk.begin + p]; v = src[wk.begin + p]; }
+        const unsigned long long m = __ballot(on && fl);
+        const int rank = __popcll(m & ((1ull << lane) - 1ull));
+        __syncthreads();
+        if (lane == 0) wl[wave] = __popcll(m);
+        __syncthreads();
+        int lw = 0, ltile = 0;
+        for (int k = 0; k < 4; ++k) { if (k < wave) lw += wl[k]; ltile += wl[k]; }
+        const int pos_in_tile = wave * 64 + lane;  // order inside the tile
+        if (on) {
+            if (fl) dst[lpos + lw + rank] = v;
+            else dst[rpos + (pos_in_tile - (lw + rank))] = v;
+        }
+        const int tile_n = (int)min((int64_t)256, send - t0);
+        lpos += ltile;
+        rpos += tile_n - ltile;
+    }
+}
+
+__global__ void copy_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int64_t begin,
+                                int64_t count) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+        dst[begin + i] = src[begin + i];
+}
+
+int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, int32_t* buf1, const PartWork* work,
+                          int64_t* n_left_out, int64_t max_count) {
+    const int F = ctx->shape.n_features;
+    int64_t g = (max_count + 2047) / 2048;
+    if (g > PART_GROUPS) g = PART_GROUPS;
+    if (g < 1) g = 1;
+    const int64_t W = (int64_t)F * ctx->shape.n_bins;
+    hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, bins, F, buf0, buf1, work,
+                       ctx->flags, ctx->part_counts, ctx->hist_pool, W);
+    hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, buf0, buf1, buf0, buf1,
+                       work, ctx->flags, ctx->part_counts, n_left_out);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+// Stand-alone call: row_idx is reordered in place (through the context's spare buffer).
+int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,
+                       int feature, int bin, int64_t* n_left_out) {
+    hipLaunchKernelGGL(set_part_work_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->pwork, begin, count, feature,
+                       bin);
+    if (count == 0) {
+        hipLaunchKernelGGL(fill_i64_kernel, dim3(1), dim3(64), 0, ctx->stream, n_left_out, (int64_t)0);
+        QG_HIP(ctx, hipGetLastError());
+        return QGBDT_OK;
+    }
+    int rc = launch_partition_work(ctx, bins, row_idx, ctx->idx[0], ctx->pwork, n_left_out, count);
+    if (rc != QGBDT_OK) return rc;
+    int blocks = (int)((count + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], row_idx, begin, count);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+}  // namespace qgbdt

@@ -1,0 +1,74 @@
+// Device helpers of the split search shared by the stand-alone entry point and
+// the tree-growing kernels.
+#pragma once
+#include "common.h"
+
+namespace qgbdt {
+
+// One histogram to scan: where it lives, whether it is first formed as
+// parent - child (sibling subtraction), and the totals of its leaf.
+struct ScanItem {
+    int32_t slot;        // histogram index relative to the base pointer
+    int32_t sub_parent;  // >= 0: hist[slot] = hist[sub_parent] - hist[sub_child] first
+    int32_t sub_child;
+    int32_t valid;       // 0: skip
+    qgbdt_leafstat stat;
+};
+
+__device__ __forceinline__ int64_t packed_g(int64_t w) { return w >> 32; }
+__device__ __forceinline__ int64_t packed_h(int64_t w) { return w & 0xffffffffLL; }
+
+// (G*dg)^2 / (2*H*dh), fp64, this operation order (Sec. 4.1 eq. (gain)); the
+// translation unit is compiled without FMA contraction.
+__device__ __forceinline__ double half_loss(int64_t G, int64_t H, double dg, double dh) {
+    const double a = (double)G * dg;
+    const double num = a * a;
+    const double den = 2.0 * ((double)H * dh);
+    return num / den;
+}
+
+// Left row count from the hessian share, rounded half up, exact integers.
+__device__ __forceinline__ int64_t count_estimate(int64_t HL, int64_t Hs, int64_t n) {
+    return (2 * HL * n + Hs) / (2 * Hs);
+}
+
+// Reduces the per-feature candidates of one leaf to its best split: largest gain,
+// ties to the lowest feature.  Must be called by all threads of a workgroup of
+// `nthreads` (multiple of 64, <= 1024); the result is valid in thread 0.
+__device__ inline void reduce_features(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
+                                       int tid, int nthreads) {
+    double bg = 0.0;
+    int bf = -1;
+    for (int f = tid; f < F; f += nthreads) {
+        const FeatCand c = cand[f];
+        if (c.bin >= 0 && (c.gain > bg)) { bg = c.gain; bf = f; }  // ascending f: strict > keeps the lowest
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const double og = __shfl_xor(bg, o);
+        const int of = __shfl_xor(bf, o);
+        if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) { bg = og; bf = of; }
+    }
+    __shared__ double sg[16];
+    __shared__ int sf[16];
+    const int w = tid >> 6;
+    if ((tid & 63) == 0) { sg[w] = bg; sf[w] = bf; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < (nthreads >> 6); ++k)
+            if (sf[k] >= 0 && (bf < 0 || sg[k] > bg || (sg[k] == bg && sf[k] < bf))) { bg = sg[k]; bf = sf[k]; }
+        qgbdt_split s;
+        s.gain = 0.0; s.feature = -1; s.bin = -1;
+        s.left_g = s.left_h = s.right_g = s.right_h = s.left_count = 0;
+        if (bf >= 0) {
+            const FeatCand c = cand[bf];
+            s.gain = c.gain; s.feature = bf; s.bin = c.bin;
+            s.left_g = packed_g(c.left); s.left_h = packed_h(c.left);
+            s.right_g = st.sum_g - s.left_g; s.right_h = st.sum_h - s.left_h;
+            s.left_count = count_estimate(s.left_h, st.sum_h, st.n_rows);
+        }
+        *out = s;
+    }
+    __syncthreads();
+}
+
+}  // namespace qgbdt
