@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-GBDT hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: quantize
+(g, h), root histogram, then for every split partition -> histogram of the smaller
+child -> sibling subtraction -> split scan, and the final leaf refit, i.e. one call
+of grow_tree.  The (g, h) of step i are those of boosting iteration i of a real
+boosting run on the synthetic data (computed before the timed region and kept in
+HBM), so the timed trees are exactly the trees of that run.
+
+Prints ONE JSON line.  `value` = rows*features accumulated into histograms per
+second of whole-step time.  `roofline` is the histogram kernel (all its launches in
+the timed region, timed with HIP events on the library's stream).  `cpu_baseline`
+times the CPU oracle on the same inputs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="index into workloads.CONFIGS (default: 10.5M x 28)")
+    ap.add_argument("--rows", type=int, default=0, help="override the row count (testing only)")
+    ap.add_argument("--bits", type=int, default=3)
+    ap.add_argument("--acc-width", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--root-reps", type=int, default=20)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import workloads
+    from paper_2207_09682_amd import Context
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = workloads.CONFIGS[args.config]
+    bits_g = args.bits if cfg.loss == "logistic" else cfg.bits_g
+    bits_h = args.bits if cfg.loss == "logistic" else cfg.bits_h
+    N = args.rows or cfg.n_rows
+    t0 = time.time()
+    wl = workloads.make_workload(cfg, n_rows=N, device=dev)
+    N = wl.n_rows
+    F, nb, L = cfg.n_features, cfg.n_bins, cfg.num_leaves
+    bins = wl.bins.contiguous()
+    ctx = Context(N, F, nb, max_leaves=L)
+    K, W = args.steps, args.warmup
+    sys.stderr.write(f"[bench] workload {cfg.name}: {N} x {F}, {nb} bins, generated in {time.time() - t0:.1f}s\n")
+
+    # ---- set-up (untimed): a real boosting run that records (g, h) of every iteration --------
+    score = torch.zeros(N, device=dev)
+    gs, hs = [], []
+    tree = ctx.new_tree()
+    for it in range(W + K):
+        g, h = workloads.gradients(wl, score)
+        gs.append(g); hs.append(h)
+        ctx.grow_tree(bins, g, h, bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
+        order = torch.argsort(tree.leaf_begin[: int(tree.n_leaves.item())])
+        cnt = tree.leaf_count[order]
+        leaf_at_pos = torch.repeat_interleave(order, cnt)
+        upd = (cfg.learning_rate * tree.leaf_value[leaf_at_pos]).float()
+        score.index_add_(0, tree.row_idx.long(), upd)
+    torch.cuda.synchronize()
+
+    # ---- timed region: W warm-up steps, then exactly K steps ---------------------------------
+    units = torch.zeros(1, dtype=torch.int64, device=dev)
+    for it in range(W):
+        ctx.grow_tree(bins, gs[it], hs[it], bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf,
+                      acc_width=args.acc_width, tree=tree)
+    torch.cuda.synchronize()
+    ctx.set_profiling(True)
+    ctx.read_profile()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for it in range(W, W + K):
+        ctx.grow_tree(bins, gs[it], hs[it], bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf,
+                      acc_width=args.acc_width, tree=tree)
+        units += tree.hist_units
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    hist_ms, hist_launches, hist_bytes = ctx.read_profile()
+    ctx.set_profiling(False)
+    total_units = int(units.item())
+    n_leaves_last = int(tree.n_leaves.item())
+
+    # ---- root pass alone (contiguous rows): the kernel at its full-size launch -----------------
+    gh, _ = ctx.quantize_gradients(gs[W], hs[W], bits_g, bits_h, cfg.seed, W)
+    hist = torch.empty(F * nb, dtype=torch.int64, device=dev)
+    for _ in range(3):
+        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    torch.cuda.synchronize()
+    ctx.set_profiling(True)
+    ctx.read_profile()
+    for _ in range(args.root_reps):
+        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    root_ms, root_n, root_bytes = ctx.read_profile()
+    ctx.set_profiling(False)
+    root_avg_ms = root_ms / max(root_n, 1)
+    root_gbs = root_bytes / max(root_n, 1) / (root_avg_ms * 1e-3) / 1e9 if root_avg_ms > 0 else 0.0
+
+    # ---- CPU oracle on the same inputs -----------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        bins_h = bins.cpu().numpy()
+        g_h = gs[W].cpu().numpy(); h_h = hs[W].cpu().numpy()
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        gq, hq, _ = oracle.quantize_gradients(g_h, h_h, bits_g, bits_h, cfg.seed, W)
+        c0 = time.perf_counter()
+        reps = 0
+        while True:
+            oracle.build_histograms(bins_h, nb, gq, hq)
+            reps += 1
+            if time.perf_counter() - c0 > 12.0 or reps >= 20:
+                break
+        c_el = time.perf_counter() - c0
+        cpu = {"value": reps * N * F / c_el, "unit": "rows*features/s", "cores": threads, "kind": "oracle",
+               "sample": f"{reps} root-pass histogram builds of the oracle (all {N} rows x {F} features, "
+                         f"{bits_g}-bit), {c_el:.1f} s"}
+
+    achieved = (hist_bytes / hist_launches) / (hist_ms / hist_launches * 1e-3) / 1e9 if hist_launches and hist_ms > 0 else 0.0
+    out = {
+        "metric": "histogram build rows*features/s over whole trees (quantize+hist+subtract+scan+partition+refit), "
+                  f"{bits_g}-bit gradients",
+        "value": total_units / elapsed,
+        "unit": "rows*features/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3,
+        "s_per_tree": elapsed / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {N} rows x {F} features, {nb} bins (uint8), {cfg.loss} loss, "
+                               f"{bits_g}-bit g / {bits_h}-bit h, {L} leaves/tree, leaf-wise",
+                   "acc_width": args.acc_width or "auto", "leaves_last_tree": n_leaves_last,
+                   "hist_units_per_tree": total_units / K},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "hist_kernel (all launches of the timed trees)",
+                     "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
+                     "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1)},
+        "root_pass": {"avg_launch_us": root_avg_ms * 1e3, "achieved_GBps": root_gbs, "frac": root_gbs / HBM_PEAK_GBS,
+                      "rows_x_features_per_s": N * F / (root_avg_ms * 1e-3) if root_avg_ms > 0 else 0.0,
+                      "reps": root_n},
+        "hist_time_share": hist_ms / (elapsed * 1e3),
+        "cpu_baseline": cpu,
+        "paper_context": "paper: V100, Higgs 10.5M x 28, 3-bit: 4.74 s histogram time / 500 trees = 9.5 ms per tree "
+                         "(another machine; context, not the target)",
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
