@@ -17,8 +17,9 @@
  *      bins   uint8 [n_rows][n_features], row-major, values in [0, n_bins)
  *      gh     int16 [n_rows]: quantized gradient (signed) in the high byte,
  *             quantized hessian (unsigned) in the low byte
- *      hist   int64 [n_features][n_bins]: one packed word per bin, sum of g~ in
- *             the upper 32 bits (signed), sum of h~ in the lower 32 bits
+ *      hist   int64 [n_bins][n_features] (bin-major: the order in which the kernels
+ *             merge their local copies): one packed word per (bin, feature), sum of
+ *             g~ in the upper 32 bits (signed), sum of h~ in the lower 32 bits
  *             (unsigned) -- the packing of Sec. 6.2 at 32|32 width
  *      rows   int32 row ids; a leaf is a contiguous slice [begin, begin+count)
  *             of an index array, ascending inside the slice
@@ -137,14 +138,14 @@ QGBDT_API int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const flo
  * Rows are row_idx[begin .. begin+count) (dev int32) or, when row_idx is NULL,
  * begin .. begin+count.  bits_g/bits_h bound |g~|, h~ and set how many rows a local
  * 16|16 accumulator may take before it is merged (Sec. 7.4.3); acc_width 0 picks the
- * width, 16 / 32 force it.  hist_out: dev int64[n_features*n_bins], overwritten.
+ * width, 16 / 32 force it.  hist_out: dev int64[n_bins][n_features], overwritten.
  * QGBDT_E_OVERFLOW_RISK if count rows could overflow a 32-bit field. */
 QGBDT_API int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh,
                            const int32_t* row_idx, int64_t begin, int64_t count, int32_t bits_g,
                            int32_t bits_h, int32_t acc_width, int64_t* hist_out);
 
 /* sibling = parent - child, bin by bin on the packed words (exact: a child's sums
- * never exceed its parent's).  All dev int64[n_features*n_bins]; sibling_out may
+ * never exceed its parent's).  All dev int64[n_bins][n_features]; sibling_out may
  * alias parent. */
 QGBDT_API int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child,
                               int64_t* sibling_out);
@@ -153,7 +154,7 @@ QGBDT_API int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, c
  * (Sec. 3), integer prefix sums, fp64 gain of eq. (gain) (Sec. 4.1).  A candidate
  * needs H~ > 0 on both sides, both estimated row counts >= min_data_in_leaf and both
  * H~ delta_h >= min_sum_hessian; the strictly largest gain > 0 wins, ties go to the
- * lowest feature, then the lowest bin.  hist: dev int64[n_hists][F][nb]; stats: dev
+ * lowest feature, then the lowest bin.  hist: dev int64[n_hists][nb][F]; stats: dev
  * [n_hists]; delta: dev float[2]; out: dev [n_hists]. */
 QGBDT_API int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists,
                            const qgbdt_leafstat* stats, const float* delta,

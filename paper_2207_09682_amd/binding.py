@@ -199,7 +199,7 @@ class Context:
         return out
 
     def find_best_splits(self, hist, stats, delta, min_data_in_leaf=20, min_sum_hessian=0.0):
-        """hist: int64 [n, F*nb]; stats: int64 [n, 3] (n_rows, sum_g, sum_h).
+        """hist: int64 [n, nb*F] (bin-major); stats: int64 [n, 3] (n_rows, sum_g, sum_h).
         Returns a uint8 tensor [n, 56] holding qgbdt_split records (see unpack_splits)."""
         self._sync_stream()
         n = stats.shape[0]
@@ -269,6 +269,6 @@ def unpack_splits(raw: torch.Tensor):
 
 
 def unpack_hist(hist: torch.Tensor, n_features: int, n_bins: int):
-    """Packed int64 words -> (G int64 [F, nb], H int64 [F, nb]) on the host."""
-    w = hist.cpu().view(n_features, n_bins)
+    """Packed int64 words [nb, F] -> (G int64 [F, nb], H int64 [F, nb]) on the host."""
+    w = hist.cpu().view(n_bins, n_features).t().contiguous()
     return (w >> 32).numpy(), (w & 0xFFFFFFFF).numpy()

@@ -20,10 +20,6 @@ int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...) {
     return code;
 }
 
-__global__ void set_hist_work_kernel(HistWork* w, int64_t begin, int64_t count, int use_idx) {
-    if (threadIdx.x == 0) { w->begin = begin; w->count = count; w->use_idx = use_idx; w->buf = 0; w->slot = 0; }
-}
-
 // sum of h~ and |g~| over a row set (only used when the a-priori bound cannot rule out overflow)
 __global__ __launch_bounds__(256) void gh_totals_kernel(const int16_t* __restrict__ gh, const int32_t* __restrict__ idx,
                                                         int64_t begin, int64_t count, int64_t* totals) {
@@ -54,11 +50,13 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 }
 
 static void free_all(qgbdt_ctx* c) {
-    void* ptrs[] = {c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->absmax, c->qtotals,
-                    c->delta, c->leaves, c->step, c->cand, c->hwork, c->pwork, c->scan_items, c->tmp_stats,
-                    c->refit_partial, c->tmp_i64};
+    void* ptrs[] = {c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->absmax, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
+                    c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
+                    c->tmp_i64};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (c->host_state) (void)hipHostFree(c->host_state);
     if (c->ev) {
         for (int i = 0; i < c->ev_cap; ++i)
             if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
@@ -99,27 +97,41 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     const int64_t N = shape->n_rows;
     const int64_t W = (int64_t)shape->n_features * shape->n_bins;
     const int L = shape->max_leaves;
+    c->batch_max = L;
+    c->max_expand = 2 * L;
+    c->max_nodes = 2 * c->max_expand + 1;
+    c->max_seg = (int)(N / PART_SEG) + c->batch_max + 2;
+    c->rounds_hint = 10;
     int rc = QGBDT_OK;
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (L + 1)));
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (c->max_expand + 1)));
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->flags, (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->part_counts, (size_t)PART_GROUPS);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_counts, (size_t)c->max_seg);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_prefix, (size_t)c->max_seg + 1);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->absmax, 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals, 4);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->delta, 2);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->leaves, (size_t)L + 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->nodes, (size_t)c->max_nodes);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->step, 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->cand, (size_t)2 * shape->n_features);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hwork, 1);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->batch, (size_t)c->batch_max);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->cand, (size_t)2 * c->batch_max * shape->n_features);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_entries, (size_t)c->batch_max);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_counts, 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->pwork, 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, reinterpret_cast<ScanItem**>(&c->scan_items), 2);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_stats, 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->scan_items, (size_t)2 * c->batch_max);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->scan_counters, (size_t)2 * c->batch_max);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->leaf_node, (size_t)L);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->refit_partial, (size_t)L * REFIT_PARTS * 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_i64, 8);
     if (rc == QGBDT_OK && hipMemset(c->step, 0, sizeof(StepState)) != hipSuccess)
         rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
+    if (rc == QGBDT_OK && hipMemset(c->scan_counters, 0, sizeof(int32_t) * 2 * c->batch_max) != hipSuccess)
+        rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
+    if (rc == QGBDT_OK && hipHostMalloc(reinterpret_cast<void**>(&c->host_state), sizeof(StepState), hipHostMallocDefault) != hipSuccess)
+        rc = set_error(c, QGBDT_E_ALLOC, "hipHostMalloc failed");
     if (rc != QGBDT_OK) {
         snprintf(g_create_error, sizeof(g_create_error), "%s", c->err);
         free_all(c);
@@ -193,9 +205,12 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     if (rc != QGBDT_OK) return rc;
     if (count == 0) return QGBDT_OK;
     const HistPlan plan = make_hist_plan(ctx->shape, bits_g, bits_h, acc_width);
-    hipLaunchKernelGGL(set_hist_work_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->hwork, begin, count,
-                       row_idx ? 1 : 0);
-    return launch_hist(ctx, plan, (const uint8_t*)bins, gh, row_idx, row_idx, ctx->hwork, hist_out, count, ctx->step);
+    rc = launch_set_hist_table(ctx, plan, begin, count);
+    if (rc != QGBDT_OK) return rc;
+    return launch_hist(ctx, plan, (const uint8_t*)bins, gh, row_idx, row_idx, row_idx != nullptr,
+                       (((uintptr_t)bins + (uint64_t)begin * ctx->shape.n_features) & 15) == 0, ctx->hist_entries,
+                       ctx->hist_counts, hist_out, (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group,
+                       ctx->step);
 }
 
 int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* sibling_out) {
@@ -278,14 +293,13 @@ int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches, 
     StepState st;
     QG_HIP(ctx, hipMemcpy(&st, ctx->step, sizeof(st), hipMemcpyDeviceToHost));
     const double F = ctx->shape.n_features, nb = ctx->shape.n_bins;
-    // algorithmic bytes: a bin row and a packed (g~,h~) per row, a row id when gathered, one histogram per launch
+    // algorithmic bytes: a bin row and a packed (g~,h~) per row, a row id when gathered, one histogram per build
     *hist_bytes = (double)st.prof_rows_contig * (F + 2.0) + (double)st.prof_rows_idx * (F + 2.0 + 4.0) +
-                  (double)st.prof_launches * F * nb * 8.0;
+                  (double)st.prof_builds * F * nb * 8.0;
     *hist_ms = ms;
     *hist_launches = st.prof_launches;
     ctx->ev_used = 0;
-    ctx->prof_launches = 0;
-    st.prof_rows_contig = 0; st.prof_rows_idx = 0; st.prof_launches = 0;
+    st.prof_rows_contig = 0; st.prof_rows_idx = 0; st.prof_launches = 0; st.prof_builds = 0;
     QG_HIP(ctx, hipMemcpy(ctx->step, &st, sizeof(st), hipMemcpyHostToDevice));
     return QGBDT_OK;
 }

@@ -12,33 +12,43 @@ namespace qgbdt {
 
 // ---- device-side bookkeeping of one tree -----------------------------------
 
-// Per-leaf record kept on the device while a tree grows.
-struct LeafState {
+// A node of the tree being grown.  Nodes are created in pairs when their parent is
+// expanded (partitioned, histograms built, best split searched); a node becomes an
+// open leaf when its parent's split is committed in best-first order.
+struct Node {
     int64_t begin, count;  // slice of the index buffer `buf`
     int64_t sum_g, sum_h;  // quantized totals
+    int64_t n_left;        // rows sent left by this node's split (valid once expanded)
     int32_t buf;           // which of the two index buffers holds the slice
     int32_t slot;          // histogram slot in the pool
-    qgbdt_split best;      // best split of this leaf (feature < 0: none)
+    int32_t state;         // 0 waiting for its parent's commit, 1 open leaf, 2 internal (split committed)
+    int32_t expanded;      // children exist (their rows, histograms and best splits are known)
+    int32_t child;         // left child id (right = child + 1), -1 if none
+    int32_t leaf_id;       // valid once the node is an open leaf
+    qgbdt_split best;      // best split of this node (feature < 0: none)
 };
 
-// Work of the current split step; written by one kernel, read by the next ones.
+// State of the growth of one tree.
 struct StepState {
     int32_t done;        // 1: tree finished, later kernels return at once
-    int32_t n_leaves;    // leaves so far
-    int32_t leaf;        // leaf being split (left child keeps this id)
-    int32_t new_leaf;    // id of the right child
-    int32_t feature, bin;
-    int32_t src_buf;     // index buffer holding the parent's slice
-    int32_t small_is_left;
-    int64_t begin, count;  // parent's slice
-    int64_t n_left;        // true left count (after partition)
-    int32_t parent_slot, new_slot;
-    int32_t pending;       // 1: pend_leaf[] still need their per-feature candidates reduced
-    int32_t pend_leaf[2];  // leaves whose candidates sit in the candidate buffer (-1: none)
-    int32_t pad;
-    int64_t hist_units;    // sum of rows*features accumulated by histogram builds
+    int32_t n_nodes, n_leaves, n_commits, n_expanded, n_slots;
+    int32_t n_batch;     // nodes expanded in the current round
+    int32_t rounds;
+    int32_t n_part_items;  // row segments of the current round's partitions
+    int32_t n_scan_items;  // histograms to scan in the current round
+    int32_t pad[2];
+    int64_t hist_units;    // rows*features of the histogram builds the sequential algorithm performs
     int64_t prof_rows_contig, prof_rows_idx;  // rows seen by histogram launches
     int64_t prof_launches;                    // histogram launches that had rows
+    int64_t prof_builds;                      // histogram builds served by those launches
+};
+
+// One node expanded in the current round.
+struct BatchEntry {
+    int32_t node;
+    int32_t seg_start;  // first partition segment of this node
+    int32_t n_seg;
+    int32_t new_slot;   // histogram slot of the child that is built from its rows
 };
 
 // Candidate of one (leaf, feature) pair produced by the scan kernel.
@@ -49,21 +59,22 @@ struct FeatCand {
     int32_t pad;
 };
 
-// Work descriptor of one row partition.
+// One histogram build: a row slice accumulated into one slot, cut into `groups` row groups
+// that are the work items [item_start, item_start + groups) of the launch.
+struct HistEntry {
+    int64_t begin, count;
+    int32_t buf;   // index buffer (gathered builds)
+    int32_t slot;  // histogram slot relative to the base pointer
+    int32_t item_start;
+    int32_t groups;
+};
+
+// Work descriptor of one stand-alone row partition.
 struct PartWork {
     int64_t begin, count;
     int32_t feature, bin;
     int32_t src_buf;    // which index buffer holds the slice; the result goes to the other one
-    int32_t zero_slot;  // >= 0: histogram slot cleared on the way (grow_tree)
-};
-
-// Work descriptor of one histogram build.
-struct HistWork {
-    int64_t begin, count;
-    int32_t use_idx;  // rows come from an index buffer
-    int32_t buf;      // which index buffer (grow_tree) -- 0 for the standalone call
-    int32_t slot;     // histogram slot (grow_tree)
-    int32_t pad;
+    int32_t zero_slot;  // unused by the stand-alone call
 };
 
 struct HistPlan {
@@ -78,7 +89,12 @@ struct HistPlan {
     int32_t max_groups;  // workgroups along the row axis
     int32_t min_rows_per_group;
     int32_t acc_width;   // 16: packed 16|16 words in LDS, 32: packed 32|32 words
+    int32_t flat_lanes;  // > 0: contiguous slices may use the flat 16-byte-load kernel with this many lanes
+    int32_t flat_rows;   // rows per wavefront iteration of that kernel
+    int32_t flat_unroll;
 };
+
+struct ScanItem;
 
 }  // namespace qgbdt
 
@@ -87,29 +103,40 @@ struct qgbdt_ctx {
     hipStream_t stream;
     int device;
     size_t ws_bytes;
+    // sizes derived from the shape
+    int batch_max;   // most nodes expanded per round
+    int max_expand;  // most expansions per tree (sequential ones plus speculative ones)
+    int max_nodes;
+    int max_seg;
+    int rounds_hint;
     // workspace
     int32_t* idx[2];       // [N] each
     int16_t* gh;           // [N]
-    int64_t* hist_pool;    // [max_leaves][F*nb]
+    int64_t* hist_pool;    // [max_expand + 1][nb*F]
     uint8_t* flags;        // [N] partition flags
-    int64_t* part_counts;  // [PART_GROUPS]
+    int64_t* part_counts;  // [PART_GROUPS] (stand-alone partition)
+    int32_t* seg_counts;   // [max_seg] left rows per partition segment
+    int32_t* seg_prefix;   // [max_seg + 1]
     uint32_t* absmax;      // [2] float bits
     int64_t* qtotals;      // [3] sum g~, sum h~, sum |g~|
     float* delta;          // [2]
-    qgbdt::LeafState* leaves;  // [max_leaves]
-    qgbdt::StepState* step;    // [1]
-    qgbdt::FeatCand* cand;     // [2][F]
-    qgbdt::HistWork* hwork;    // [1]
-    qgbdt::PartWork* pwork;    // [1]
-    void* scan_items;          // ScanItem[2]
-    qgbdt_leafstat* tmp_stats; // [2]
-    double* refit_partial;     // [max_leaves][REFIT_PARTS][2]
-    int64_t* tmp_i64;          // [8]
+    qgbdt::Node* nodes;          // [max_nodes]
+    qgbdt::StepState* step;      // [1]
+    qgbdt::BatchEntry* batch;    // [batch_max]
+    qgbdt::FeatCand* cand;       // [2*batch_max][F]
+    qgbdt::HistEntry* hist_entries;  // [batch_max]
+    int32_t* hist_counts;        // [2] entries, items
+    qgbdt::PartWork* pwork;      // [1]
+    qgbdt::ScanItem* scan_items; // [2*batch_max]
+    int32_t* scan_counters;      // [2*batch_max]
+    int32_t* leaf_node;          // [max_leaves]
+    double* refit_partial;       // [max_leaves][REFIT_PARTS][2]
+    int64_t* tmp_i64;            // [8]
+    qgbdt::StepState* host_state;  // pinned host copy
     // profiling
     int profiling;
     hipEvent_t* ev;
     int ev_cap, ev_used;
-    int64_t prof_launches;
     char err[512];
 };
 
@@ -117,6 +144,7 @@ namespace qgbdt {
 
 constexpr int PART_GROUPS = 512;
 constexpr int REFIT_PARTS = 32;
+constexpr int PART_SEG = 2048;  // rows per partition segment of the batched partition
 
 int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...);
 
@@ -134,20 +162,22 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
                     int64_t* totals_out);
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh,
-                const int32_t* idx0, const int32_t* idx1, const HistWork* work, int64_t* hist_base,
-                int64_t max_count, StepState* step);
+int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh, const int32_t* idx0,
+                const int32_t* idx1, bool use_idx, bool flat_aligned, const HistEntry* entries,
+                const int32_t* table_counts, int64_t* hist_base, int64_t grid_items, StepState* step);
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);
-struct ScanItem;
-int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, int n_items, const float* delta,
-                      int min_data, double min_sum_hess, FeatCand* cand);
+int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
+                      const float* delta, int min_data, double min_sum_hess);
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
                          const float* delta, int min_data, double min_sum_hess, qgbdt_split* out);
 int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, int32_t* buf1, const PartWork* work,
                           int64_t* n_left_out, int64_t max_count);
 int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,
                        int feature, int bin, int64_t* n_left_out);
+int launch_batch_partition_count(qgbdt_ctx* ctx, const uint8_t* bins);
+int launch_batch_partition_scatter(qgbdt_ctx* ctx);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);

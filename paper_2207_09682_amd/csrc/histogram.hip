@@ -3,18 +3,24 @@
 // histogram by 64-bit integer atomics (hierarchical buffers of Sec. 6.1, packed
 // gradient|hessian words of Sec. 6.2, width rule of Sec. 7.4.3).
 //
-// Bound by HBM: per row one F-byte bin row, one 2-byte packed (g~,h~) and, for a
-// non-root leaf, one 4-byte row id are read once; the only other traffic is the
-// merge of F*n_bins packed words per workgroup chunk.
+// Bound by HBM traffic on one side -- per row one F-byte bin row, one 2-byte packed
+// (g~,h~) and, for a gathered leaf, one 4-byte row id are read once -- and by the
+// LDS atomic rate on the other: one 64-lane ds_add takes about 5.7 clocks per CU
+// whatever the (<= 4-way) bank conflicts, i.e. ~7e12 bin updates/s on the chip,
+// the same order as the ~6e12 bin bytes/s that HBM streams.
 //
-// Mapping.  The bin matrix is row-major.  A wavefront covers `rows_per_it`
-// consecutive rows per iteration: lane -> (row r, dword q of the row's feature
-// tile), so a wavefront reads rows_per_it * ft contiguous (or row-gathered) bytes
-// with one dword load per lane, and the lane's (r, q) never change.  Each dword
-// holds four features; the four LDS atomics of a lane are issued in an order
-// rotated by (r + q/8), and the local histogram is laid out [bin][feature] with a
-// row pitch that is a multiple of 32 words for narrow tiles, so that in one
-// atomic instruction lanes of different features fall into different LDS banks.
+// Work decomposition.  A launch serves a table of histogram builds (one per leaf);
+// every build is cut into row groups and the (build, group) pairs are the work
+// items the workgroups loop over.  A workgroup accumulates a group chunk by chunk
+// (a chunk is as many rows as a 16|16 packed accumulator can take) and merges each
+// chunk into the build's [bin][feature] histogram.
+//
+// Local histogram layout: [bin][feature] with a pitch of 32 words for narrow tiles,
+// so the LDS bank is the feature; the order in which a lane issues the atomics of
+// the four features of a dword is rotated per row so that lanes of one instruction
+// spread over the features.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace qgbdt {
@@ -40,7 +46,8 @@ struct Acc;
 template <>
 struct Acc<16> {
     using word = uint32_t;
-    static __device__ __forceinline__ word expand(int ghv) { return (word)((ghv >> 8) * 65536 + (ghv & 0xff)); }
+    // (g~ << 16) + h~ = t*255 + ghv with t = ghv minus its low byte (one AND, one multiply-add)
+    static __device__ __forceinline__ word expand(int ghv) { return (word)(__mul24(ghv & ~0xff, 255) + ghv); }
     static __device__ __forceinline__ void add(word* p, word v) { atomicAdd(p, v); }
     static __device__ __forceinline__ int64_t widen(word v) {
         const int64_t G = (int32_t)v >> 16;
@@ -58,145 +65,331 @@ struct Acc<32> {
     static __device__ __forceinline__ int64_t widen(word v) { return (int64_t)v; }
 };
 
+// Work item -> (table entry, row group).
+__device__ __forceinline__ int find_entry(const HistEntry* __restrict__ entries, int n_entries, int item) {
+    int lo = 0, hi = n_entries - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (entries[mid].item_start <= item) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ void count_profile(const HistEntry* __restrict__ entries, int n_entries, bool idx,
+                                              StepState* step) {
+    int64_t rows = 0;
+    for (int e = 0; e < n_entries; ++e) rows += entries[e].count;
+    if (idx) step->prof_rows_idx += rows; else step->prof_rows_contig += rows;
+    step->prof_launches += 1;
+    step->prof_builds += n_entries;
+}
+
+// Merge of the local bins into the total histogram and reset of the local bins.
+// Both are [bin][feature], so LDS is walked linearly (no bank conflicts) and the
+// atomics of a wavefront fall into consecutive words.
 template <int W>
-__global__ __launch_bounds__(256) void hist_kernel(const uint8_t* __restrict__ bins, const int16_t* __restrict__ gh,
-                                                   const int32_t* __restrict__ idx0,
-                                                   const int32_t* __restrict__ idx1,
-                                                   const HistWork* __restrict__ work, int64_t* hist_base, int F,
-                                                   int nb, HistPlan plan, StepState* step) {
+__device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_words, int ftp, int ft, int f0, int F,
+                                            int64_t* hist) {
+    for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
+        const int b = w / ftp, f = w - b * ftp;
+        const typename Acc<W>::word v = lds[w];
+        if (v != 0 && f < ft) {
+            lds[w] = 0;
+            atomicAdd(reinterpret_cast<unsigned long long*>(hist + (int64_t)b * F + f0 + f),
+                      (unsigned long long)Acc<W>::widen(v));
+        }
+    }
+}
+
+// Fast path (feature count a multiple of 4), any row set.  lane -> (row r of the
+// iteration, dword q of the row's feature tile); U row-iterations (U*rows_per_it
+// <= 64 rows) form one block of a wavefront.  All loads of a block are issued before
+// its first LDS atomic and the loads of the wavefront's next block are already in
+// flight while the atomics of the current one are issued.  Rows beyond the end and
+// lanes without work are not branched around: they read a valid row and add zero.
+//
+// Instruction budget: the four SIMDs of a CU issue one VALU instruction per clock
+// between them and the LDS takes one 64-lane atomic per ~5.7 clocks, so a bin may
+// cost ~5 VALU instructions: one bit-field extract and one 24-bit multiply-add
+// into the byte address of its LDS word, plus its share of the per-row work.
+template <int W, bool IDX, int U>
+__global__ __launch_bounds__(1024) void hist_kernel(const uint8_t* __restrict__ bins, const int16_t* __restrict__ gh,
+                                                    const int32_t* __restrict__ idx0,
+                                                    const int32_t* __restrict__ idx1,
+                                                    const HistEntry* __restrict__ entries,
+                                                    const int32_t* __restrict__ table_counts, int64_t* hist_base,
+                                                    int F, int nb, HistPlan plan, StepState* step) {
     using word = typename Acc<W>::word;
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
 
-    const HistWork wk = *work;
-    if (wk.count <= 0) return;
-    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        step->hist_units += wk.count * (int64_t)F;
-        if (wk.use_idx) step->prof_rows_idx += wk.count; else step->prof_rows_contig += wk.count;
-        step->prof_launches += 1;
-    }
-    int64_t rows_per_group = (wk.count + gridDim.x - 1) / gridDim.x;
-    if (rows_per_group < plan.min_rows_per_group) rows_per_group = plan.min_rows_per_group;
-    const int64_t gbegin = (int64_t)blockIdx.x * rows_per_group;
-    if (gbegin >= wk.count) return;
-    const int64_t gend = min(wk.count, gbegin + rows_per_group);
+    const int n_entries = table_counts[0], n_items = table_counts[1];
+    if ((int)blockIdx.x >= n_items) return;
+    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) count_profile(entries, n_entries, IDX, step);
 
     const int f0 = blockIdx.y * plan.ft;
     const int ft = min(plan.ft, F - f0);
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
-    int64_t* hist = hist_base + (int64_t)wk.slot * F * nb;
-    const int32_t* idx = wk.use_idx ? (wk.buf ? idx1 : idx0) : nullptr;
-
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
-    const int q = lane % plan.dpr, r = lane / plan.dpr;
-    const bool lane_on = (r < plan.rows_per_it) && (4 * q < ft);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const int rpi = plan.rows_per_it;
+    int q = lane % plan.dpr, r = lane / plan.dpr;
+    const bool lane_on = (r < rpi) && (4 * q < ft);
+    if (!lane_on) { q = 0; r = 0; }
     const int rot = (q >> 3) + r;
-    int sh[4], fl[4];
+    uint32_t sh[4], fl4[4];  // bit offset of the k-th bin in the dword, byte offset of its feature column in LDS
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int c = (k + rot) & 3;
         sh[k] = 8 * c;
-        fl[k] = 4 * q + c;
+        fl4[k] = (uint32_t)(4 * q + c) * (uint32_t)sizeof(word);
     }
-    const int64_t row_stride = (int64_t)n_waves * plan.rows_per_it;
-    const uint8_t* col = bins + f0 + 4 * q;
+    const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);  // LDS bytes per bin row
+    const int S = U * rpi;                                          // rows per block of one wavefront
+    const uint8_t* colbase = bins + f0 + 4 * q;
 
-    for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
-        const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
-        __syncthreads();
-        if (lane_on) {
-            for (int64_t p0 = cbegin + (int64_t)wave * plan.rows_per_it + r; p0 < cend; p0 += 4 * row_stride) {
-                uint32_t d[4];
-                int gv[4];
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
+        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
+        if (gbegin >= en.count) continue;
+        const int64_t gend = min(en.count, gbegin + rows_per_group);
+        int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        const int32_t* idx = IDX ? ((en.buf ? idx1 : idx0) + en.begin) : nullptr;
+
+        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
+            const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
+            const int crow = (int)(cend - cbegin);
+            __syncthreads();
+            const int32_t* ib = IDX ? idx + cbegin : nullptr;
+            const int64_t row_base = IDX ? 0 : en.begin + cbegin;
+            if (wave * S < crow) {
+                // three stages in flight per wavefront: row ids of block n+2, bin dwords and packed
+                // gradients of block n+1, LDS atomics of block n
+                int64_t rown[U];
+                uint32_t d[U], dn[U];
+                int gv[U], gn[U];
+                {
+                    int64_t rows[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int64_t p = p0 + u * row_stride;
-                    d[u] = 0; gv[u] = 0;
-                    if (p < cend) {
-                        const int64_t i = idx ? (int64_t)idx[wk.begin + p] : wk.begin + p;
-                        d[u] = *reinterpret_cast<const uint32_t*>(col + i * F);
-                        gv[u] = gh[i];
+                    for (int u = 0; u < U; ++u) {
+                        const int p = min(wave * S + u * rpi + r, crow - 1);
+                        rows[u] = IDX ? (int64_t)ib[p] : row_base + p;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        d[u] = *reinterpret_cast<const uint32_t*>(colbase + rows[u] * F);
+                        gv[u] = gh[rows[u]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int p = min((wave + n_waves) * S + u * rpi + r, crow - 1);
+                        rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
                     }
                 }
+                for (int ro = wave * S; ro < crow; ro += n_waves * S) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (p0 + u * row_stride < cend) {
-                        const word v = Acc<W>::expand(gv[u]);
+                    for (int u = 0; u < U; ++u) {
+                        dn[u] = *reinterpret_cast<const uint32_t*>(colbase + rown[u] * F);
+                        gn[u] = gh[rown[u]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {  // row ids two blocks ahead (clamped when past the end)
+                        const int p = min(ro + 2 * n_waves * S + u * rpi + r, crow - 1);
+                        rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const bool ok = lane_on && (ro + u * rpi + r < crow);
+                        const word v = Acc<W>::expand(ok ? gv[u] : 0);
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
-                            const uint32_t b = (d[u] >> sh[k]) & 0xffu;
-                            Acc<W>::add(&lds[b * ftp + fl[k]], v);
+                            const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
+                            Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
                         }
                     }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) { d[u] = dn[u]; gv[u] = gn[u]; }
                 }
             }
+            __syncthreads();
+            merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist);
         }
-        __syncthreads();
-        // merge the local bins into the total histogram and clear them
-        const int n_words = ft * nb;
-        for (int w = threadIdx.x; w < n_words; w += blockDim.x) {
-            const int f = w / nb, b = w - f * nb;
-            const word v = lds[b * ftp + f];
-            if (v != 0) {
-                lds[b * ftp + f] = 0;
-                atomicAdd(reinterpret_cast<unsigned long long*>(hist + (int64_t)(f0 + f) * nb + b),
-                          (unsigned long long)Acc<W>::widen(v));
+    }
+}
+
+// Contiguous rows with the whole row in one tile (16 <= F <= 64, F % 4 == 0, slice
+// start 16-byte aligned): the rows of a chunk are one flat byte stream, read with
+// 16-byte loads.  L lanes (16*L a multiple of F) cover RPI = 16*L/F whole rows per
+// iteration, so a lane's four dwords keep their (row, feature) position for the
+// whole kernel; they lie in at most two consecutive rows.  Blocks of U iterations
+// are software-pipelined like in hist_kernel.
+template <int W, int U>
+__global__ __launch_bounds__(1024) void hist_flat_kernel(const uint8_t* __restrict__ bins,
+                                                         const int16_t* __restrict__ gh,
+                                                         const HistEntry* __restrict__ entries,
+                                                         const int32_t* __restrict__ table_counts,
+                                                         int64_t* hist_base, int F, int nb, HistPlan plan,
+                                                         StepState* step) {
+    using word = typename Acc<W>::word;
+    extern __shared__ unsigned char lds_raw[];
+    word* lds = reinterpret_cast<word*>(lds_raw);
+
+    const int n_entries = table_counts[0], n_items = table_counts[1];
+    if ((int)blockIdx.x >= n_items) return;
+    if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, false, step);
+
+    const int RPI = plan.flat_rows, L = plan.flat_lanes;
+    const int BR = U * RPI;  // rows of one block of U iterations
+    const int ftp = plan.ftp;
+    const int lds_words = nb * ftp;
+    for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+
+    const int lane0 = threadIdx.x & 63;
+    const bool lane_on = lane0 < L;
+    const int lane = lane_on ? lane0 : 0;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);
+    // position of the lane's four dwords inside one iteration
+    const int period = F / ((F % 16 == 0) ? 16 : (F % 8 == 0) ? 8 : 4);  // lanes after which the column repeats
+    const int rot = lane / period;
+    uint32_t sh[4], fl4[4][4];
+    const int rA = (16 * lane) / F, rB = (16 * lane + 12) / F;
+    bool useB[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int fo = 16 * lane + 4 * i;
+        const int row = fo / F, col = fo - row * F;
+        useB[i] = row != rA;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = (k + rot) & 3;
+            if (i == 0) sh[k] = 8 * c;
+            fl4[i][k] = (uint32_t)(col + c) * (uint32_t)sizeof(word);
+        }
+    }
+    const int chunk = plan.chunk_rows / BR * BR > 0 ? plan.chunk_rows / BR * BR : BR;
+    const int dpr = F / 4;
+
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
+        rows_per_group = (rows_per_group + BR - 1) / BR * BR;  // keeps every group start 16-byte aligned
+        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
+        if (gbegin >= en.count) continue;
+        const int64_t gend = min(en.count, gbegin + rows_per_group);
+        int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+
+        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += chunk) {
+            const int64_t cend = min(gend, cbegin + (int64_t)chunk);
+            const int crow = (int)(cend - cbegin);
+            __syncthreads();
+            const uint8_t* cb = bins + (en.begin + cbegin) * (int64_t)F;
+            const int16_t* gb = gh + (en.begin + cbegin);
+            const int n_blocks = crow / BR;
+            if (wave < n_blocks) {
+                uint4 d[U], dn[U];
+                int ga[U], gbv[U], gan[U], gbn[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int row0 = (wave * U + u) * RPI;
+                    d[u] = *reinterpret_cast<const uint4*>(cb + (size_t)row0 * (size_t)F + 16 * lane);
+                    ga[u] = gb[row0 + rA];
+                    gbv[u] = gb[row0 + rB];
+                }
+                for (int jb = wave; jb < n_blocks; jb += n_waves) {
+                    const int jn = min(jb + n_waves, n_blocks - 1);  // the last prefetch re-reads the last block
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int row0 = (jn * U + u) * RPI;  // uniform
+                        dn[u] = *reinterpret_cast<const uint4*>(cb + (size_t)row0 * (size_t)F + 16 * lane);
+                        gan[u] = gb[row0 + rA];
+                        gbn[u] = gb[row0 + rB];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const word va = Acc<W>::expand(lane_on ? ga[u] : 0);
+                        const word vb = Acc<W>::expand(lane_on ? gbv[u] : 0);
+                        const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const word v = useB[i] ? vb : va;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
+                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[i][k])), v);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) { d[u] = dn[u]; ga[u] = gan[u]; gbv[u] = gbn[u]; }
+                }
             }
+            // rows left over after the last whole block: one dword per thread and step
+            const int tail0 = n_blocks * BR;
+            for (int e = threadIdx.x; e < (crow - tail0) * dpr; e += blockDim.x) {
+                const int row = tail0 + e / dpr, q = e % dpr;
+                const uint32_t dwd = *reinterpret_cast<const uint32_t*>(cb + (size_t)row * (size_t)F + 4 * q);
+                const word v = Acc<W>::expand(gb[row]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t b = (dwd >> (8 * k)) & 0xffu;
+                    Acc<W>::add(&lds[b * ftp + 4 * q + k], v);
+                }
+            }
+            __syncthreads();
+            merge_local<W>(lds, lds_words, ftp, F, 0, F, hist);
         }
     }
 }
 
 // Any feature count (no alignment assumption): one byte load per (row, feature).
 template <int W>
-__global__ __launch_bounds__(256) void hist_generic_kernel(const uint8_t* __restrict__ bins,
-                                                           const int16_t* __restrict__ gh,
-                                                           const int32_t* __restrict__ idx0,
-                                                           const int32_t* __restrict__ idx1,
-                                                           const HistWork* __restrict__ work, int64_t* hist_base,
-                                                           int F, int nb, HistPlan plan, StepState* step) {
+__global__ __launch_bounds__(1024) void hist_generic_kernel(const uint8_t* __restrict__ bins,
+                                                            const int16_t* __restrict__ gh,
+                                                            const int32_t* __restrict__ idx0,
+                                                            const int32_t* __restrict__ idx1, int use_idx,
+                                                            const HistEntry* __restrict__ entries,
+                                                            const int32_t* __restrict__ table_counts,
+                                                            int64_t* hist_base, int F, int nb, HistPlan plan,
+                                                            StepState* step) {
     using word = typename Acc<W>::word;
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
-    const HistWork wk = *work;
-    if (wk.count <= 0) return;
-    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        step->hist_units += wk.count * (int64_t)F;
-        if (wk.use_idx) step->prof_rows_idx += wk.count; else step->prof_rows_contig += wk.count;
-        step->prof_launches += 1;
-    }
-    int64_t rows_per_group = (wk.count + gridDim.x - 1) / gridDim.x;
-    if (rows_per_group < plan.min_rows_per_group) rows_per_group = plan.min_rows_per_group;
-    const int64_t gbegin = (int64_t)blockIdx.x * rows_per_group;
-    if (gbegin >= wk.count) return;
-    const int64_t gend = min(wk.count, gbegin + rows_per_group);
+    const int n_entries = table_counts[0], n_items = table_counts[1];
+    if ((int)blockIdx.x >= n_items) return;
+    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        count_profile(entries, n_entries, use_idx != 0, step);
     const int f0 = blockIdx.y * plan.ft;
     const int ft = min(plan.ft, F - f0);
-    const int n_words = ft * nb;
-    int64_t* hist = hist_base + (int64_t)wk.slot * F * nb;
-    const int32_t* idx = wk.use_idx ? (wk.buf ? idx1 : idx0) : nullptr;
-    for (int w = threadIdx.x; w < n_words; w += blockDim.x) lds[w] = 0;
-    for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
-        const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
-        __syncthreads();
-        const int64_t n_el = (cend - cbegin) * ft;
-        for (int64_t e = threadIdx.x; e < n_el; e += blockDim.x) {
-            const int64_t p = cbegin + e / ft;
-            const int f = (int)(e % ft);
-            const int64_t i = idx ? (int64_t)idx[wk.begin + p] : wk.begin + p;
-            const uint32_t b = bins[i * F + f0 + f];
-            Acc<W>::add(&lds[f * nb + b], Acc<W>::expand(gh[i]));
-        }
-        __syncthreads();
-        for (int w = threadIdx.x; w < n_words; w += blockDim.x) {
-            const word v = lds[w];
-            if (v != 0) {
-                lds[w] = 0;
-                atomicAdd(reinterpret_cast<unsigned long long*>(hist + (int64_t)f0 * nb + w),
-                          (unsigned long long)Acc<W>::widen(v));
+    const int lds_words = ft * nb;
+    for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
+        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
+        if (gbegin >= en.count) continue;
+        const int64_t gend = min(en.count, gbegin + rows_per_group);
+        int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        const int32_t* idx = use_idx ? ((en.buf ? idx1 : idx0) + en.begin) : nullptr;
+        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
+            const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
+            __syncthreads();
+            const int64_t n_el = (cend - cbegin) * ft;
+            for (int64_t e = threadIdx.x; e < n_el; e += blockDim.x) {
+                const int64_t p = cbegin + e / ft;
+                const int f = (int)(e % ft);
+                const int64_t i = idx ? (int64_t)idx[p] : en.begin + p;
+                const uint32_t b = bins[i * F + f0 + f];
+                Acc<W>::add(&lds[b * ft + f], Acc<W>::expand(gh[i]));
             }
+            __syncthreads();
+            merge_local<W>(lds, lds_words, ft, ft, f0, F, hist);
         }
     }
 }
@@ -219,7 +412,6 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (w == 0) w = (n16 >= 1024) ? 16 : 32;  // a 16|16 chunk must amortise its merge
     const int wbytes = (w == 16) ? 4 : 8;
     const int lds_budget = 64 * 1024;
-    p.threads = 256;
     const bool fast = (F % 4 == 0);
     if (fast) {
         // candidates in order of preference: the whole row when it is narrow, then wide tiles
@@ -259,21 +451,58 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.chunk_rows = (int32_t)((lim > 0x40000000LL) ? 0x40000000LL : lim);
     if (p.chunk_rows < 1) p.chunk_rows = 1;
     p.min_rows_per_group = 2048;
+    p.threads = 512;
     int per_cu = (160 * 1024) / (p.lds_bytes > 0 ? p.lds_bytes : 1);
-    if (per_cu > 8) per_cu = 8;
+    const int by_waves = 32 / (p.threads / 64);  // 32 wavefronts per CU
+    if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
     int groups = (256 * per_cu) / p.n_tiles;
     if (groups < 1) groups = 1;
     p.max_groups = groups;
     p.acc_width = w;
+    p.flat_lanes = 0; p.flat_rows = 0;
+    if (fast && p.n_tiles == 1 && F >= 16 && F <= 64) {
+        for (int l = 64; l >= 32; --l)
+            if ((16 * l) % F == 0) { p.flat_lanes = l; p.flat_rows = 16 * l / F; break; }
+    }
+    p.flat_unroll = 2;
+    if (const char* e = getenv("QGBDT_NOFLAT")) { if (atoi(e)) p.flat_lanes = 0; }
+    if (const char* e = getenv("QGBDT_FLAT_U")) p.flat_unroll = atoi(e);
+    if (const char* e = getenv("QGBDT_MAX_GROUPS")) p.max_groups = atoi(e);
+    if (const char* e = getenv("QGBDT_MIN_ROWS")) p.min_rows_per_group = atoi(e);
+    if (const char* e = getenv("QGBDT_THREADS")) p.threads = atoi(e);
     return p;
 }
 
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh,
-                const int32_t* idx0, const int32_t* idx1, const HistWork* work, int64_t* hist_base,
-                int64_t max_count, StepState* step) {
+// One entry table for a stand-alone build.
+__global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64_t begin, int64_t count, int min_rows,
+                                      int max_groups) {
+    if (threadIdx.x == 0) {
+        int64_t g = (count + min_rows - 1) / min_rows;
+        if (g > max_groups) g = max_groups;
+        if (g < 1) g = 1;
+        HistEntry e;
+        e.begin = begin; e.count = count; e.buf = 0; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
+        entries[0] = e;
+        counts[0] = 1;
+        counts[1] = count > 0 ? (int32_t)g : 0;
+    }
+}
+
+int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count) {
+    hipLaunchKernelGGL(set_hist_table_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->hist_entries, ctx->hist_counts,
+                       begin, count, plan.min_rows_per_group, plan.max_groups);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+// Launches the kernel variant for (plan, row source).  `grid_items` is the host's upper bound on
+// the number of work items; workgroups beyond the table's item count return at once.
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh, const int32_t* idx0,
+                const int32_t* idx1, bool use_idx, bool flat_aligned, const HistEntry* entries,
+                const int32_t* table_counts, int64_t* hist_base, int64_t grid_items, StepState* step) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
-    int64_t groups = (max_count + plan.min_rows_per_group - 1) / plan.min_rows_per_group;
+    int64_t groups = grid_items;
     if (groups > plan.max_groups) groups = plan.max_groups;
     if (groups < 1) groups = 1;
     dim3 grid((unsigned)groups, (unsigned)plan.n_tiles), block(plan.threads);
@@ -283,26 +512,51 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const
         e0 = ctx->ev[ctx->ev_used++]; e1 = ctx->ev[ctx->ev_used++];
         QG_HIP(ctx, hipEventRecord(e0, ctx->stream));
     }
-    if (plan.acc_width == 16) {
-        if (fast)
-            hipLaunchKernelGGL(hist_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1, work,
-                               hist_base, F, nb, plan, step);
-        else
-            hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0,
-                               idx1, work, hist_base, F, nb, plan, step);
+    const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_aligned;
+    if (flat) {
+#define QG_LAUNCH_FLAT(W_, U_)                                                                                   \
+    hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, bins, gh, entries, \
+                       table_counts, hist_base, F, nb, plan, step)
+        if (plan.acc_width == 16) {
+            if (plan.flat_unroll >= 4) QG_LAUNCH_FLAT(16, 4);
+            else if (plan.flat_unroll >= 2) QG_LAUNCH_FLAT(16, 2);
+            else QG_LAUNCH_FLAT(16, 1);
+        } else {
+            if (plan.flat_unroll >= 4) QG_LAUNCH_FLAT(32, 4);
+            else if (plan.flat_unroll >= 2) QG_LAUNCH_FLAT(32, 2);
+            else QG_LAUNCH_FLAT(32, 1);
+        }
+#undef QG_LAUNCH_FLAT
+    } else if (fast) {
+        const int cap = 64 / plan.rows_per_it;
+        const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
+#define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                              \
+    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1, \
+                       entries, table_counts, hist_base, F, nb, plan, step)
+#define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
+    switch (U) {                                                                        \
+        case 8: QG_LAUNCH_HIST(W_, IDX_, 8); break;                                     \
+        case 7: QG_LAUNCH_HIST(W_, IDX_, 7); break;                                     \
+        case 4: QG_LAUNCH_HIST(W_, IDX_, 4); break;                                     \
+        case 2: QG_LAUNCH_HIST(W_, IDX_, 2); break;                                     \
+        default: QG_LAUNCH_HIST(W_, IDX_, 1); break;                                    \
+    }
+        if (plan.acc_width == 16) {
+            if (use_idx) { QG_LAUNCH_HIST_U(16, true) } else { QG_LAUNCH_HIST_U(16, false) }
+        } else {
+            if (use_idx) { QG_LAUNCH_HIST_U(32, true) } else { QG_LAUNCH_HIST_U(32, false) }
+        }
+#undef QG_LAUNCH_HIST_U
+#undef QG_LAUNCH_HIST
+    } else if (plan.acc_width == 16) {
+        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1,
+                           use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     } else {
-        if (fast)
-            hipLaunchKernelGGL(hist_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1, work,
-                               hist_base, F, nb, plan, step);
-        else
-            hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0,
-                               idx1, work, hist_base, F, nb, plan, step);
+        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1,
+                           use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     }
     QG_HIP(ctx, hipGetLastError());
-    if (e1) {
-        QG_HIP(ctx, hipEventRecord(e1, ctx->stream));
-        ctx->prof_launches += 1;
-    }
+    if (e1) QG_HIP(ctx, hipEventRecord(e1, ctx->stream));
     return QGBDT_OK;
 }
 

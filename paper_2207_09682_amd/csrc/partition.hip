@@ -152,4 +152,134 @@ int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, in
     return QGBDT_OK;
 }
 
+
+// ---- batched partition of the nodes expanded in one round of grow_tree ---------------
+//
+// Work items are row segments of PART_SEG rows; segment -> (batch entry, segment of that
+// node) by binary search over the entries' first-segment numbers.
+
+__device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, int n_batch, int item) {
+    int lo = 0, hi = n_batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (batch[mid].seg_start <= item) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Left-going rows per segment (flags kept as bytes); on the way the histogram slots
+// that this round's builds accumulate into are cleared.
+__global__ __launch_bounds__(256) void batch_part_count_kernel(const uint8_t* __restrict__ bins, int F,
+                                                               const int32_t* __restrict__ buf0,
+                                                               const int32_t* __restrict__ buf1,
+                                                               const StepState* __restrict__ step,
+                                                               const BatchEntry* __restrict__ batch,
+                                                               const Node* __restrict__ nodes,
+                                                               uint8_t* __restrict__ flags,
+                                                               int32_t* __restrict__ seg_counts, int64_t* hist_base,
+                                                               int64_t hist_words) {
+    if (step->done) return;
+    const int n_items = step->n_part_items, n_batch = step->n_batch;
+    if (n_batch <= 0) return;
+    {
+        int64_t* z = hist_base + (int64_t)batch[0].new_slot * hist_words;  // the new slots are consecutive
+        const int64_t nz = (int64_t)n_batch * hist_words;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nz; i += (int64_t)gridDim.x * blockDim.x)
+            z[i] = 0;
+    }
+    __shared__ int sc[4];
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const BatchEntry be = batch[find_batch(batch, n_batch, item)];
+        const Node nd = nodes[be.node];
+        const int32_t* src = (nd.buf ? buf1 : buf0) + nd.begin;
+        const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
+        const int64_t send = min(nd.count, sbegin + PART_SEG);
+        const int feature = nd.best.feature, bin = nd.best.bin;
+        int cnt = 0;
+        for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
+            const int64_t row = src[p];
+            const int fl = bins[row * F + feature] <= bin;
+            flags[nd.begin + p] = (uint8_t)fl;
+            cnt += fl;
+        }
+        for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) sc[threadIdx.x >> 6] = cnt;
+        __syncthreads();
+        if (threadIdx.x == 0) seg_counts[item] = sc[0] + sc[1] + sc[2] + sc[3];
+    }
+}
+
+// Order-preserving scatter of every segment into the other index buffer; seg_prefix is the
+// exclusive prefix of seg_counts over all segments of the round.
+__global__ __launch_bounds__(256) void batch_part_scatter_kernel(const int32_t* __restrict__ buf0r,
+                                                                 const int32_t* __restrict__ buf1r, int32_t* buf0w,
+                                                                 int32_t* buf1w, const StepState* __restrict__ step,
+                                                                 const BatchEntry* __restrict__ batch,
+                                                                 const Node* __restrict__ nodes,
+                                                                 const uint8_t* __restrict__ flags,
+                                                                 const int32_t* __restrict__ seg_prefix) {
+    if (step->done) return;
+    const int n_items = step->n_part_items, n_batch = step->n_batch;
+    __shared__ int wl[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const BatchEntry be = batch[find_batch(batch, n_batch, item)];
+        const Node nd = nodes[be.node];
+        const int32_t* src = (nd.buf ? buf1r : buf0r) + nd.begin;
+        int32_t* dst = (nd.buf ? buf0w : buf1w) + nd.begin;
+        const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
+        const int64_t send = min(nd.count, sbegin + PART_SEG);
+        const int64_t before = seg_prefix[item] - seg_prefix[be.seg_start];  // left rows in earlier segments
+        int64_t lpos = before;                          // next left slot (relative to the node's slice)
+        int64_t rpos = nd.n_left + (sbegin - before);   // next right slot
+        for (int64_t t0 = sbegin; t0 < send; t0 += 256) {
+            const int64_t p = t0 + threadIdx.x;
+            const bool on = p < send;
+            int fl = 0;
+            int32_t v = 0;
+            if (on) { fl = flags[nd.begin + p]; v = src[p]; }
+            const unsigned long long m = __ballot(on && fl);
+            const int rank = __popcll(m & ((1ull << lane) - 1ull));
+            __syncthreads();
+            if (lane == 0) wl[wave] = __popcll(m);
+            __syncthreads();
+            int lw = 0, ltile = 0;
+            for (int k = 0; k < 4; ++k) { if (k < wave) lw += wl[k]; ltile += wl[k]; }
+            const int pos_in_tile = wave * 64 + lane;
+            if (on) {
+                if (fl) dst[lpos + lw + rank] = v;
+                else dst[rpos + (pos_in_tile - (lw + rank))] = v;
+            }
+            const int tile_n = (int)min((int64_t)256, send - t0);
+            lpos += ltile;
+            rpos += tile_n - ltile;
+        }
+    }
+}
+
+static int batch_part_grid(const qgbdt_ctx* ctx) {
+    int64_t g = ctx->max_seg;
+    if (g > 2048) g = 2048;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+int launch_batch_partition_count(qgbdt_ctx* ctx, const uint8_t* bins) {
+    const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
+    hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, bins,
+                       ctx->shape.n_features, ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                       ctx->seg_counts, ctx->hist_pool, W);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+int launch_batch_partition_scatter(qgbdt_ctx* ctx) {
+    hipLaunchKernelGGL(batch_part_scatter_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, ctx->idx[0],
+                       ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                       ctx->seg_prefix);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
 }  // namespace qgbdt

@@ -22,120 +22,136 @@ int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child,
     return QGBDT_OK;
 }
 
-__global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n, ScanItem* items) {
+__global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n, ScanItem* items, qgbdt_split* out,
+                                             int32_t* n_items, int32_t* counters) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
         ScanItem it;
-        it.slot = i; it.sub_parent = -1; it.sub_child = -1; it.valid = 1; it.stat = stats[i];
+        it.slot = i; it.sub_parent = -1; it.sub_child = -1; it.valid = 1; it.stat = stats[i]; it.out = out + i;
         items[i] = it;
+        counters[i] = 0;
     }
+    if (i == 0) *n_items = n;
 }
 
 // One workgroup per (feature, histogram): thread b owns bin b.  Workgroup-wide
 // inclusive scan of the packed words (fields cannot overflow: every prefix is
-// bounded by the leaf totals), then each thread evaluates its threshold.
-__global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items, int F,
-                                                   int nb, const float* __restrict__ delta, int64_t min_data,
-                                                   double min_sum_hess, FeatCand* cand_base) {
-    const ScanItem it = items[blockIdx.y];
-    if (!it.valid) return;
+// bounded by the leaf totals), then each thread evaluates its threshold.  The
+// workgroup that finishes a histogram's last feature reduces its per-feature
+// candidates to the histogram's best split (counter + fences, no waiting).
+__global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
+                                                   const int32_t* __restrict__ n_items_ptr, int F, int nb,
+                                                   const float* __restrict__ delta, int64_t min_data,
+                                                   double min_sum_hess, FeatCand* cand_base, int32_t* counters) {
+    const int n_items = *n_items_ptr;
     const int f = blockIdx.x, b = threadIdx.x;
-    const int64_t W = (int64_t)F * nb;
-    int64_t* hist = hist_base + it.slot * W + (int64_t)f * nb;
-    int64_t word = 0;
-    if (b < nb) {
-        if (it.sub_parent >= 0) {
-            word = hist_base[it.sub_parent * W + (int64_t)f * nb + b] - hist_base[it.sub_child * W + (int64_t)f * nb + b];
-            hist[b] = word;
-        } else {
-            word = hist[b];
-        }
-    }
-    // inclusive scan
-    int64_t pre = word;
     const int lane = b & 63, wave = b >> 6;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int64_t v = __shfl_up(pre, o);
-        if (lane >= o) pre += v;
-    }
-    __shared__ int64_t wtot[4];
-    if (lane == 63) wtot[wave] = pre;
-    __syncthreads();
-    for (int k = 0; k < wave; ++k) pre += wtot[k];
-
+    const int64_t W = (int64_t)F * nb;
+    const int64_t at = (int64_t)b * F + f;  // histograms are [bin][feature]
     const double dg = (double)delta[0], dh = (double)delta[1];
-    const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
-    double gain = 0.0;
-    int bin = -1;
-    if (b + 1 < nb && Hs > 0) {
-        const int64_t GL = packed_g(pre), HL = packed_h(pre);
-        const int64_t GR = Gs - GL, HR = Hs - HL;
-        if (HL > 0 && HR > 0) {
-            const int64_t cl = count_estimate(HL, Hs, n), cr = n - cl;
-            if (cl >= min_data && cr >= min_data && !((double)HL * dh < min_sum_hess) &&
-                !((double)HR * dh < min_sum_hess)) {
-                const double parent = half_loss(Gs, Hs, dg, dh);
-                const double gn = half_loss(GL, HL, dg, dh) + half_loss(GR, HR, dg, dh) - parent;
-                if (gn > 0.0) { gain = gn; bin = b; }
-            }
-        }
-    }
-    int64_t left = pre;
-    // arg-max: largest gain, ties to the lowest bin
-    for (int o = 32; o > 0; o >>= 1) {
-        const double og = __shfl_xor(gain, o);
-        const int ob = __shfl_xor(bin, o);
-        const int64_t ol = __shfl_xor(left, o);
-        if (ob >= 0 && (bin < 0 || og > gain || (og == gain && ob < bin))) { gain = og; bin = ob; left = ol; }
-    }
+    __shared__ int64_t wtot[4];
     __shared__ double sg[4];
     __shared__ int sb[4];
     __shared__ int64_t sl[4];
-    if (lane == 0) { sg[wave] = gain; sb[wave] = bin; sl[wave] = left; }
-    __syncthreads();
-    if (b == 0) {
-        for (int k = 1; k < (int)(blockDim.x >> 6); ++k)
-            if (sb[k] >= 0 && (bin < 0 || sg[k] > gain || (sg[k] == gain && sb[k] < bin))) {
-                gain = sg[k]; bin = sb[k]; left = sl[k];
+    __shared__ int s_last;
+    for (int item = blockIdx.y; item < n_items; item += gridDim.y) {
+        const ScanItem it = items[item];
+        if (!it.valid) continue;
+        int64_t word = 0;
+        if (b < nb) {
+            if (it.sub_parent >= 0) {
+                word = hist_base[it.sub_parent * W + at] - hist_base[it.sub_child * W + at];
+                hist_base[it.slot * W + at] = word;
+            } else {
+                word = hist_base[it.slot * W + at];
             }
-        FeatCand c;
-        c.gain = gain; c.left = left; c.bin = bin; c.pad = 0;
-        cand_base[(int64_t)blockIdx.y * F + f] = c;
+        }
+        // inclusive scan
+        int64_t pre = word;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t v = __shfl_up(pre, o);
+            if (lane >= o) pre += v;
+        }
+        if (lane == 63) wtot[wave] = pre;
+        __syncthreads();
+        for (int k = 0; k < wave; ++k) pre += wtot[k];
+
+        const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
+        double gain = 0.0;
+        int bin = -1;
+        if (b + 1 < nb && Hs > 0) {
+            const int64_t GL = packed_g(pre), HL = packed_h(pre);
+            const int64_t GR = Gs - GL, HR = Hs - HL;
+            if (HL > 0 && HR > 0) {
+                const int64_t cl = count_estimate(HL, Hs, n), cr = n - cl;
+                if (cl >= min_data && cr >= min_data && !((double)HL * dh < min_sum_hess) &&
+                    !((double)HR * dh < min_sum_hess)) {
+                    const double parent = half_loss(Gs, Hs, dg, dh);
+                    const double gn = half_loss(GL, HL, dg, dh) + half_loss(GR, HR, dg, dh) - parent;
+                    if (gn > 0.0) { gain = gn; bin = b; }
+                }
+            }
+        }
+        int64_t left = pre;
+        // arg-max: largest gain, ties to the lowest bin
+        for (int o = 32; o > 0; o >>= 1) {
+            const double og = __shfl_xor(gain, o);
+            const int ob = __shfl_xor(bin, o);
+            const int64_t ol = __shfl_xor(left, o);
+            if (ob >= 0 && (bin < 0 || og > gain || (og == gain && ob < bin))) { gain = og; bin = ob; left = ol; }
+        }
+        if (lane == 0) { sg[wave] = gain; sb[wave] = bin; sl[wave] = left; }
+        __syncthreads();
+        if (b == 0) {
+            for (int k = 1; k < (int)(blockDim.x >> 6); ++k)
+                if (sb[k] >= 0 && (bin < 0 || sg[k] > gain || (sg[k] == gain && sb[k] < bin))) {
+                    gain = sg[k]; bin = sb[k]; left = sl[k];
+                }
+            FeatCand c;
+            c.gain = gain; c.left = left; c.bin = bin; c.pad = 0;
+            cand_base[(int64_t)item * F + f] = c;
+            __threadfence();  // the candidate is visible before the count
+            s_last = (atomicAdd(&counters[item], 1) == F - 1) ? 1 : 0;
+        }
+        __syncthreads();
+        if (s_last) {
+            __threadfence();  // the other workgroups' candidates are visible after the count
+            reduce_features(cand_base + (int64_t)item * F, F, it.stat, it.out, b, blockDim.x);
+            if (b == 0) counters[item] = 0;
+        }
+        __syncthreads();
     }
 }
 
-__global__ __launch_bounds__(256) void reduce_cand_kernel(const FeatCand* __restrict__ cand, int F,
-                                                          const ScanItem* __restrict__ items, qgbdt_split* out) {
-    const ScanItem it = items[blockIdx.x];
-    reduce_features(cand + (int64_t)blockIdx.x * F, F, it.stat, &out[blockIdx.x], threadIdx.x, blockDim.x);
-}
-
-int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, int n_items, const float* delta,
-                      int min_data, double min_sum_hess, FeatCand* cand) {
+int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
+                      const float* delta, int min_data, double min_sum_hess) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int threads = 64;
     while (threads < nb) threads <<= 1;
-    hipLaunchKernelGGL(scan_kernel, dim3(F, n_items), dim3(threads), 0, ctx->stream, hist_base, items, F, nb, delta,
-                       (int64_t)min_data, min_sum_hess, cand);
+    int gy = 4096 / F;
+    if (gy < 2) gy = 2;
+    if (gy > max_items) gy = max_items;
+    if (gy < 1) gy = 1;
+    hipLaunchKernelGGL(scan_kernel, dim3(F, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb, delta,
+                       (int64_t)min_data, min_sum_hess, ctx->cand, ctx->scan_counters);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
-// Stand-alone search over n_hists contiguous histograms; processes them in
-// batches of the context's candidate buffer.
+// Stand-alone search over n_hists contiguous histograms, in batches of the context's item table.
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
                          const float* delta, int min_data, double min_sum_hess, qgbdt_split* out) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     const int64_t W = (int64_t)F * nb;
-    ScanItem* items = reinterpret_cast<ScanItem*>(ctx->scan_items);
-    for (int h0 = 0; h0 < n_hists; h0 += 2) {
-        const int n = (n_hists - h0 < 2) ? (n_hists - h0) : 2;
-        hipLaunchKernelGGL(scan_items_from_stats_kernel, dim3(1), dim3(64), 0, ctx->stream, stats + h0, n, items);
-        int rc = launch_scan_items(ctx, const_cast<int64_t*>(hist) + h0 * W, items, n, delta, min_data, min_sum_hess,
-                                   ctx->cand);
+    const int cap = 2 * ctx->batch_max;
+    int32_t* n_items = reinterpret_cast<int32_t*>(ctx->tmp_i64);
+    for (int h0 = 0; h0 < n_hists; h0 += cap) {
+        const int n = (n_hists - h0 < cap) ? (n_hists - h0) : cap;
+        hipLaunchKernelGGL(scan_items_from_stats_kernel, dim3((n + 63) / 64), dim3(64), 0, ctx->stream, stats + h0, n,
+                           ctx->scan_items, out + h0, n_items, ctx->scan_counters);
+        int rc = launch_scan_items(ctx, const_cast<int64_t*>(hist) + h0 * W, ctx->scan_items, n_items, n, delta,
+                                   min_data, min_sum_hess);
         if (rc != QGBDT_OK) return rc;
-        hipLaunchKernelGGL(reduce_cand_kernel, dim3(n), dim3(256), 0, ctx->stream, ctx->cand, F, items, out + h0);
-        QG_HIP(ctx, hipGetLastError());
     }
     return QGBDT_OK;
 }

@@ -6,13 +6,15 @@
 namespace qgbdt {
 
 // One histogram to scan: where it lives, whether it is first formed as
-// parent - child (sibling subtraction), and the totals of its leaf.
+// parent - child (sibling subtraction), the totals of its leaf and where the
+// best split goes.
 struct ScanItem {
     int32_t slot;        // histogram index relative to the base pointer
     int32_t sub_parent;  // >= 0: hist[slot] = hist[sub_parent] - hist[sub_child] first
     int32_t sub_child;
     int32_t valid;       // 0: skip
     qgbdt_leafstat stat;
+    qgbdt_split* out;
 };
 
 __device__ __forceinline__ int64_t packed_g(int64_t w) { return w >> 32; }
@@ -34,7 +36,7 @@ __device__ __forceinline__ int64_t count_estimate(int64_t HL, int64_t Hs, int64_
 
 // Reduces the per-feature candidates of one leaf to its best split: largest gain,
 // ties to the lowest feature.  Must be called by all threads of a workgroup of
-// `nthreads` (multiple of 64, <= 1024); the result is valid in thread 0.
+// `nthreads` (multiple of 64, <= 1024); thread 0 writes the result.
 __device__ inline void reduce_features(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
                                        int tid, int nthreads) {
     double bg = 0.0;

@@ -1,8 +1,25 @@
 // Leaf-wise growth of one tree (greedy splitting of Sec. 3, best-first order of
-// Sec. 7) driven entirely from the device: the host enqueues a fixed sequence of
-// kernels per split and never reads anything back; split decisions, leaf
-// bookkeeping and the arguments of the next kernels live in device memory.  Once
-// the tree is finished the remaining kernels of the sequence return at once.
+// Sec. 7), driven from the device.
+//
+// Best-first growth is sequential by definition: split the open leaf with the
+// largest gain, look at its children, repeat.  Its result, however, only depends on
+// the gains, so it can be reproduced exactly from a tree that was expanded in a
+// different order.  The tree is therefore grown in rounds.  Each round
+//   1. replays the best-first order over what is known (commit phase): the open leaf
+//      with the largest gain is committed as the next split if it has already been
+//      expanded, and its children become open leaves; the replay stops at the first
+//      leaf that has not been expanded;
+//   2. expands that leaf and, speculatively, the other open leaves with the largest
+//      gains (as many as the leaf budget still allows): one batched partition, one
+//      batched histogram build for the smaller children, one batched subtraction and
+//      split search for all children.
+// A speculative expansion that the replay never reaches is simply not part of the
+// tree: its node stays a leaf and its row slice is untouched, because children are
+// always written to the other index buffer.  Split numbers and leaf ids are assigned
+// at commit time, so the result equals the sequential one bit for bit.
+//
+// The host enqueues whole rounds without reading anything back; after the expected
+// number of rounds it reads one status word to learn whether more are needed.
 #include "split_device.h"
 
 namespace qgbdt {
@@ -12,140 +29,275 @@ struct TreeOut {
     int32_t max_leaves;
 };
 
-__global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, StepState* step, LeafState* leaves,
-                                                        const int64_t* qtotals, HistWork* hwork, PartWork* pwork,
-                                                        ScanItem* items, int64_t* hist0, int64_t hist_words) {
+__device__ __forceinline__ void clear_split(qgbdt_split& s) {
+    s.gain = 0.0; s.feature = -1; s.bin = -1;
+    s.left_g = s.left_h = s.right_g = s.right_h = s.left_count = 0;
+}
+
+__device__ __forceinline__ int hist_groups(int64_t count, int min_rows, int max_groups) {
+    int64_t g = (count + min_rows - 1) / min_rows;
+    if (g > max_groups) g = max_groups;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+__global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, int F, StepState* step, Node* nodes,
+                                                        const int64_t* qtotals, HistEntry* hist_entries,
+                                                        int32_t* hist_counts, ScanItem* items, int32_t* scan_counters,
+                                                        int64_t* hist0, int64_t hist_words, int min_rows,
+                                                        int max_groups) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = t; i < N; i += stride) idx0[i] = (int32_t)i;
     for (int64_t i = t; i < hist_words; i += stride) hist0[i] = 0;
     if (t == 0) {
-        step->done = 0; step->n_leaves = 1; step->leaf = 0; step->new_leaf = 1;
-        step->pending = 1; step->pend_leaf[0] = 0; step->pend_leaf[1] = -1;
-        step->hist_units = 0; step->n_left = 0;
-        LeafState r;
-        r.begin = 0; r.count = N; r.sum_g = qtotals[0]; r.sum_h = qtotals[1]; r.buf = 0; r.slot = 0;
-        r.best.gain = 0.0; r.best.feature = -1; r.best.bin = -1;
-        r.best.left_g = r.best.left_h = r.best.right_g = r.best.right_h = r.best.left_count = 0;
-        leaves[0] = r;
-        hwork->begin = 0; hwork->count = N; hwork->use_idx = 0; hwork->buf = 0; hwork->slot = 0;
-        pwork->count = 0; pwork->zero_slot = -1;
-        items[0].slot = 0; items[0].sub_parent = -1; items[0].sub_child = -1; items[0].valid = 1;
-        items[0].stat.n_rows = N; items[0].stat.sum_g = r.sum_g; items[0].stat.sum_h = r.sum_h;
-        items[1].valid = 0;
+        step->done = 0; step->n_nodes = 1; step->n_leaves = 1; step->n_commits = 0; step->n_expanded = 0;
+        step->n_slots = 1; step->n_batch = 0; step->rounds = 0; step->n_part_items = 0; step->n_scan_items = 1;
+        step->hist_units = N * (int64_t)F;
+        Node r;
+        r.begin = 0; r.count = N; r.sum_g = qtotals[0]; r.sum_h = qtotals[1]; r.n_left = 0; r.buf = 0; r.slot = 0;
+        r.state = 1; r.expanded = 0; r.child = -1; r.leaf_id = 0;
+        clear_split(r.best);
+        nodes[0] = r;
+        HistEntry e;
+        e.begin = 0; e.count = N; e.buf = 0; e.slot = 0; e.item_start = 0; e.groups = hist_groups(N, min_rows, max_groups);
+        hist_entries[0] = e;
+        hist_counts[0] = 1; hist_counts[1] = e.groups;
+        ScanItem it;
+        it.slot = 0; it.sub_parent = -1; it.sub_child = -1; it.valid = 1;
+        it.stat.n_rows = N; it.stat.sum_g = r.sum_g; it.stat.sum_h = r.sum_h;
+        it.out = &nodes[0].best;
+        items[0] = it;
+        scan_counters[0] = 0;
     }
 }
 
-// Finishes the previous step (per-feature candidates -> best split of the two new
-// leaves), then picks the open leaf with the largest gain (ties: lowest id) and
-// publishes the partition work of split number k.
-__global__ __launch_bounds__(256) void tree_choose_kernel(StepState* step, LeafState* leaves, const FeatCand* cand,
-                                                          const ScanItem* items, int F, int num_leaves, int k,
-                                                          PartWork* pwork, HistWork* hwork, ScanItem* items_w,
-                                                          TreeOut out) {
-    if (step->done) return;
-    const int tid = threadIdx.x;
-    if (step->pending) {
-        for (int c = 0; c < 2; ++c) {
-            const int l = step->pend_leaf[c];
-            if (l >= 0) reduce_features(cand + (int64_t)c * F, F, items[c].stat, &leaves[l].best, tid, blockDim.x);
-        }
+// Inclusive scan of one int per thread over the workgroup (1024 threads).
+__device__ __forceinline__ int block_scan_incl(int v, int* tmp /*[16]*/) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int u = __shfl_up(v, o);
+        if (lane >= o) v += u;
     }
     __syncthreads();
-    const int n = step->n_leaves;
-    double bg = 0.0;
-    int bl = -1;
-    for (int l = tid; l < n; l += blockDim.x) {
-        const qgbdt_split s = leaves[l].best;
-        if (s.feature >= 0 && s.gain > bg) { bg = s.gain; bl = l; }
+    if (lane == 63) tmp[wave] = v;
+    __syncthreads();
+    int add = 0;
+    for (int k = 0; k < wave; ++k) add += tmp[k];
+    return v + add;
+}
+
+// Commit phase and choice of the round's batch.  One workgroup of 1024 threads; the
+// replay itself runs in its first wavefront.
+__global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
+                                                         int32_t* hist_counts, int32_t* scan_counters, int F,
+                                                         int num_leaves, int batch_max, int max_expand, TreeOut out) {
+    if (step->done) return;
+    extern __shared__ unsigned char plan_lds[];
+    const int n_nodes0 = step->n_nodes;
+    // queue view: gain of every open leaf that can be split (else -1), its leaf id, expanded flag
+    double* key = reinterpret_cast<double*>(plan_lds);
+    int* lid = reinterpret_cast<int*>(key + (2 * max_expand + 1));
+    int* cand = lid + (2 * max_expand + 1);          // compacted candidates of the batch selection
+    unsigned char* expd = reinterpret_cast<unsigned char*>(cand + (2 * max_expand + 1));
+    __shared__ int s_tmp[16];
+    __shared__ int s_done, s_ncand, s_stall;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < n_nodes0; i += blockDim.x) {
+        const Node nd = nodes[i];
+        key[i] = (nd.state == 1 && nd.best.feature >= 0) ? nd.best.gain : -1.0;
+        lid[i] = nd.leaf_id;
+        expd[i] = (unsigned char)nd.expanded;
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        const double og = __shfl_xor(bg, o);
-        const int ol = __shfl_xor(bl, o);
-        if (ol >= 0 && (bl < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bl = ol; }
+    if (tid == 0) { s_done = 0; s_ncand = 0; s_stall = -1; }
+    __syncthreads();
+
+    if (tid < 64) {  // replay of the best-first order, one wavefront
+        int n_commits = step->n_commits, n_leaves = step->n_leaves;
+        int64_t units = step->hist_units;
+        for (;;) {
+            if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
+            double bg = 0.0;
+            int bi = -1, bl = 0x7fffffff;
+            for (int i = tid; i < n_nodes0; i += 64) {
+                const double g = key[i];
+                if (g > 0.0 && (g > bg || (g == bg && lid[i] < bl))) { bg = g; bi = i; bl = lid[i]; }
+            }
+            for (int o = 32; o > 0; o >>= 1) {
+                const double og = __shfl_xor(bg, o);
+                const int oi = __shfl_xor(bi, o), ol = __shfl_xor(bl, o);
+                if (oi >= 0 && (bi < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bi = oi; bl = ol; }
+            }
+            if (bi < 0) { if (tid == 0) s_done = 1; break; }      // no open leaf has a gain > 0
+            if (!expd[bi]) { if (tid == 0) s_stall = bi; break; }  // next split is not known yet
+            // commit split number n_commits: node bi, leaf id bl
+            if (tid == 0) {
+                const Node nd = nodes[bi];
+                const int k = n_commits;
+                out.t.split_leaf[k] = bl; out.t.split_feature[k] = nd.best.feature; out.t.split_bin[k] = nd.best.bin;
+                out.t.split_gain[k] = nd.best.gain;
+                out.t.split_stats[4 * k + 0] = nd.best.left_g; out.t.split_stats[4 * k + 1] = nd.best.left_h;
+                out.t.split_stats[4 * k + 2] = nd.best.right_g; out.t.split_stats[4 * k + 3] = nd.best.right_h;
+                out.t.split_n_left[k] = nd.n_left;
+                const int64_t nl = nd.n_left, nr = nd.count - nd.n_left;
+                units += (nl <= nr ? nl : nr) * (int64_t)F;
+                nodes[bi].state = 2;
+                const int c0 = nd.child, c1 = nd.child + 1;
+                nodes[c0].state = 1; nodes[c0].leaf_id = bl;
+                nodes[c1].state = 1; nodes[c1].leaf_id = n_leaves;
+                const qgbdt_split b0 = nodes[c0].best, b1 = nodes[c1].best;
+                key[bi] = -1.0;
+                key[c0] = (b0.feature >= 0) ? b0.gain : -1.0; lid[c0] = bl;
+                key[c1] = (b1.feature >= 0) ? b1.gain : -1.0; lid[c1] = n_leaves;
+            }
+            n_commits += 1; n_leaves += 1;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+        if (tid == 0) { step->n_commits = n_commits; step->n_leaves = n_leaves; step->hist_units = units; }
     }
-    __shared__ double sg[4];
-    __shared__ int sl[4];
-    if ((tid & 63) == 0) { sg[tid >> 6] = bg; sl[tid >> 6] = bl; }
+    __syncthreads();
+    if (s_done) {
+        if (tid == 0) {
+            step->done = 1; step->n_batch = 0; step->n_part_items = 0; step->n_scan_items = 0;
+            hist_counts[0] = 0; hist_counts[1] = 0;
+        }
+        return;
+    }
+    // batch: the open, not yet expanded leaves with the largest gains.  One expansion is
+    // certain (the leaf the replay stopped at); slots beyond those that the remaining certain
+    // expansions will need may be spent on speculation.
+    const int remaining = (num_leaves - 1) - step->n_commits;
+    const int spare = (max_expand - step->n_expanded) - remaining;
+    int want = 1 + (spare > 0 ? spare : 0);
+    if (want > remaining) want = remaining;
+    if (want > batch_max) want = batch_max;
+    for (int i = tid; i < n_nodes0; i += blockDim.x)
+        if (key[i] > 0.0 && !expd[i]) cand[atomicAdd(&s_ncand, 1)] = i;
+    __syncthreads();
+    const int nc = s_ncand;
+    const int n_batch = nc < want ? nc : want;
+    for (int c = tid; c < nc; c += blockDim.x) {
+        const int i = cand[c];
+        const double g = key[i];
+        const int l = lid[i];
+        int rank = 0;
+        for (int j = 0; j < nc; ++j) {
+            const int o = cand[j];
+            rank += (key[o] > g || (key[o] == g && lid[o] < l)) ? 1 : 0;
+        }
+        if (rank < n_batch) batch[rank].node = i;
+    }
+    __syncthreads();
+    __threadfence_block();
+    // segments of the batched partition, new histogram slots, child ids
+    int nseg = 0;
+    if (tid < n_batch) nseg = (int)((nodes[batch[tid].node].count + PART_SEG - 1) / PART_SEG);
+    const int incl = block_scan_incl(nseg, s_tmp);
+    const int n_nodes = n_nodes0, n_slots = step->n_slots;
+    if (tid < n_batch) {
+        const int i = batch[tid].node;
+        batch[tid].seg_start = incl - nseg;
+        batch[tid].n_seg = nseg;
+        batch[tid].new_slot = n_slots + tid;
+        nodes[i].expanded = 1;
+        nodes[i].child = n_nodes + 2 * tid;
+        scan_counters[2 * tid] = 0; scan_counters[2 * tid + 1] = 0;
+    }
+    if (tid == n_batch - 1) step->n_part_items = incl;
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 4; ++w)
-            if (sl[w] >= 0 && (bl < 0 || sg[w] > bg || (sg[w] == bg && sl[w] < bl))) { bg = sg[w]; bl = sl[w]; }
-        step->pending = 0;
-        if (bl < 0 || n >= num_leaves) {
-            step->done = 1;
-            pwork->count = 0; pwork->zero_slot = -1;
-            hwork->count = 0;
-            items_w[0].valid = 0; items_w[1].valid = 0;
-            return;
+        step->n_batch = n_batch;
+        step->n_nodes = n_nodes + 2 * n_batch;
+        step->n_slots = n_slots + n_batch;
+        step->n_expanded += n_batch;
+        step->rounds += 1;
+        step->n_scan_items = 2 * n_batch;
+    }
+}
+
+// Between the two partition passes: exclusive prefix of the segments' left counts, the
+// children of every expanded node, and the tables of the histogram and scan kernels.
+__global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* nodes, const BatchEntry* batch,
+                                                        const int32_t* seg_counts, int32_t* seg_prefix,
+                                                        HistEntry* hist_entries, int32_t* hist_counts, ScanItem* items,
+                                                        int min_rows, int max_groups) {
+    if (step->done) return;
+    __shared__ int s_tmp[16];
+    const int tid = threadIdx.x;
+    const int n_items = step->n_part_items, n_batch = step->n_batch;
+    // prefix over all segments: every thread owns a contiguous run
+    const int per = (n_items + blockDim.x - 1) / blockDim.x;
+    const int a = min(tid * per, n_items), b = min(a + per, n_items);
+    int local = 0;
+    for (int i = a; i < b; ++i) local += seg_counts[i];
+    const int incl = block_scan_incl(local, s_tmp);
+    int run = incl - local;
+    for (int i = a; i < b; ++i) { seg_prefix[i] = run; run += seg_counts[i]; }
+    if (tid == (int)blockDim.x - 1) seg_prefix[n_items] = incl;
+    __syncthreads();
+    __threadfence_block();
+    int groups = 0;
+    Node L, R;
+    int small_is_left = 1;
+    if (tid < n_batch) {
+        const BatchEntry be = batch[tid];
+        const Node P = nodes[be.node];
+        const int64_t nl = seg_prefix[be.seg_start + be.n_seg] - seg_prefix[be.seg_start];
+        const int64_t nr = P.count - nl;
+        nodes[be.node].n_left = nl;
+        small_is_left = (nl <= nr) ? 1 : 0;
+        const int cb = 1 - P.buf;
+        L.begin = P.begin; L.count = nl; L.sum_g = P.best.left_g; L.sum_h = P.best.left_h; L.n_left = 0; L.buf = cb;
+        R.begin = P.begin + nl; R.count = nr; R.sum_g = P.best.right_g; R.sum_h = P.best.right_h; R.n_left = 0; R.buf = cb;
+        L.slot = small_is_left ? be.new_slot : P.slot;
+        R.slot = small_is_left ? P.slot : be.new_slot;
+        L.state = 0; L.expanded = 0; L.child = -1; L.leaf_id = -1; clear_split(L.best);
+        R.state = 0; R.expanded = 0; R.child = -1; R.leaf_id = -1; clear_split(R.best);
+        nodes[P.child] = L; nodes[P.child + 1] = R;
+        groups = hist_groups(small_is_left ? nl : nr, min_rows, max_groups);
+        for (int c = 0; c < 2; ++c) {
+            const Node& C = c ? R : L;
+            const bool is_small = (c == 0) == (small_is_left == 1);
+            ScanItem it;
+            it.slot = C.slot;
+            it.sub_parent = is_small ? -1 : P.slot;
+            it.sub_child = is_small ? -1 : be.new_slot;
+            it.valid = 1;
+            it.stat.n_rows = C.count; it.stat.sum_g = C.sum_g; it.stat.sum_h = C.sum_h;
+            it.out = &nodes[P.child + c].best;
+            items[2 * tid + c] = it;
         }
-        const LeafState P = leaves[bl];
-        step->leaf = bl; step->new_leaf = n;
-        step->feature = P.best.feature; step->bin = P.best.bin;
-        step->src_buf = P.buf; step->begin = P.begin; step->count = P.count;
-        step->parent_slot = P.slot; step->new_slot = n;
-        pwork->begin = P.begin; pwork->count = P.count; pwork->feature = P.best.feature; pwork->bin = P.best.bin;
-        pwork->src_buf = P.buf; pwork->zero_slot = n;
-        out.t.split_leaf[k] = bl; out.t.split_feature[k] = P.best.feature; out.t.split_bin[k] = P.best.bin;
-        out.t.split_gain[k] = P.best.gain;
-        out.t.split_stats[4 * k + 0] = P.best.left_g; out.t.split_stats[4 * k + 1] = P.best.left_h;
-        out.t.split_stats[4 * k + 2] = P.best.right_g; out.t.split_stats[4 * k + 3] = P.best.right_h;
     }
+    const int gincl = block_scan_incl(groups, s_tmp);
+    if (tid < n_batch) {
+        const Node& S = small_is_left ? L : R;
+        HistEntry e;
+        e.begin = S.begin; e.count = S.count; e.buf = S.buf; e.slot = batch[tid].new_slot;
+        e.item_start = gincl - groups; e.groups = groups;
+        hist_entries[tid] = e;
+    }
+    if (tid == n_batch - 1) { hist_counts[0] = n_batch; hist_counts[1] = gincl; }
 }
 
-// After the partition: children's slices and totals, which child is built from its
-// rows (fewer rows, tie: left) and which by subtraction, and the work of the
-// histogram and scan kernels that follow.
-__global__ void tree_after_partition_kernel(StepState* step, LeafState* leaves, HistWork* hwork, ScanItem* items,
-                                            int k, TreeOut out) {
-    if (threadIdx.x != 0 || step->done) return;
-    const int s = step->leaf, r = step->new_leaf;
-    const LeafState P = leaves[s];
-    const int64_t nl = step->n_left, nr = step->count - nl;
-    out.t.split_n_left[k] = nl;
-    const int small_is_left = (nl <= nr) ? 1 : 0;
-    step->small_is_left = small_is_left;
-    const int child_buf = 1 - step->src_buf;
-    LeafState L, R;
-    L.begin = step->begin; L.count = nl; L.sum_g = P.best.left_g; L.sum_h = P.best.left_h; L.buf = child_buf;
-    R.begin = step->begin + nl; R.count = nr; R.sum_g = P.best.right_g; R.sum_h = P.best.right_h; R.buf = child_buf;
-    L.slot = small_is_left ? step->new_slot : step->parent_slot;
-    R.slot = small_is_left ? step->parent_slot : step->new_slot;
-    L.best.gain = 0.0; L.best.feature = -1; L.best.bin = -1;
-    L.best.left_g = L.best.left_h = L.best.right_g = L.best.right_h = L.best.left_count = 0;
-    R.best = L.best;
-    leaves[s] = L; leaves[r] = R;
-    const LeafState& S = small_is_left ? L : R;
-    hwork->begin = S.begin; hwork->count = S.count; hwork->use_idx = 1; hwork->buf = child_buf;
-    hwork->slot = step->new_slot;
-    for (int c = 0; c < 2; ++c) {
-        const LeafState& C = c ? R : L;
-        const bool is_small = (c == 0) == (small_is_left == 1);
-        items[c].slot = C.slot;
-        items[c].sub_parent = is_small ? -1 : step->parent_slot;
-        items[c].sub_child = is_small ? -1 : step->new_slot;
-        items[c].valid = 1;
-        items[c].stat.n_rows = C.count; items[c].stat.sum_g = C.sum_g; items[c].stat.sum_h = C.sum_h;
-    }
-    step->pend_leaf[0] = s; step->pend_leaf[1] = r; step->pending = 1;
-    step->n_leaves = r + 1;
-}
-
-__global__ void tree_finalize_kernel(const StepState* step, const LeafState* leaves, const float* delta,
-                                     TreeOut out) {
+__global__ __launch_bounds__(256) void tree_finalize_kernel(const StepState* step, const Node* nodes,
+                                                            const float* delta, int32_t* leaf_node, TreeOut out) {
     const int n = step->n_leaves;
     const double dg = (double)delta[0], dh = (double)delta[1];
     for (int l = threadIdx.x; l < out.max_leaves; l += blockDim.x) {
-        if (l < n) {
-            const LeafState S = leaves[l];
-            out.t.leaf_begin[l] = S.begin; out.t.leaf_count[l] = S.count;
-            out.t.leaf_sum_g[l] = S.sum_g; out.t.leaf_sum_h[l] = S.sum_h;
-            out.t.leaf_value_quant[l] =
-                (S.sum_h > 0 && dh > 0.0) ? -((double)S.sum_g * dg) / ((double)S.sum_h * dh) : 0.0;
-        } else {
+        if (l >= n) {
             out.t.leaf_begin[l] = 0; out.t.leaf_count[l] = 0; out.t.leaf_sum_g[l] = 0; out.t.leaf_sum_h[l] = 0;
             out.t.leaf_value_quant[l] = 0.0;
+            leaf_node[l] = -1;
         }
+    }
+    for (int i = threadIdx.x; i < step->n_nodes; i += blockDim.x) {
+        const Node S = nodes[i];
+        if (S.state != 1) continue;
+        const int l = S.leaf_id;
+        out.t.leaf_begin[l] = S.begin; out.t.leaf_count[l] = S.count;
+        out.t.leaf_sum_g[l] = S.sum_g; out.t.leaf_sum_h[l] = S.sum_h;
+        out.t.leaf_value_quant[l] = (S.sum_h > 0 && dh > 0.0) ? -((double)S.sum_g * dg) / ((double)S.sum_h * dh) : 0.0;
+        leaf_node[l] = i;
     }
     if (threadIdx.x == 0) {
         *out.t.n_leaves = n;
@@ -155,13 +307,14 @@ __global__ void tree_finalize_kernel(const StepState* step, const LeafState* lea
 }
 
 // Copies every leaf's slice from the index buffer it ended up in to the output.
-__global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* step, const LeafState* leaves,
+__global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* step, const Node* nodes,
+                                                               const int32_t* __restrict__ leaf_node,
                                                                const int32_t* __restrict__ idx0,
                                                                const int32_t* __restrict__ idx1,
                                                                int32_t* __restrict__ out) {
     const int l = blockIdx.y;
     if (l >= step->n_leaves) return;
-    const LeafState S = leaves[l];
+    const Node S = nodes[leaf_node[l]];
     const int32_t* src = S.buf ? idx1 : idx0;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < S.count; j += (int64_t)gridDim.x * blockDim.x)
         out[S.begin + j] = src[S.begin + j];
@@ -172,7 +325,6 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     const int64_t N = ctx->shape.n_rows;
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     const int64_t W = (int64_t)F * nb;
-    ScanItem* items = reinterpret_cast<ScanItem*>(ctx->scan_items);
     TreeOut out;
     out.t = *tout;
     out.max_leaves = ctx->shape.max_leaves;
@@ -194,35 +346,76 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, ctx->step,
-                       ctx->leaves, ctx->qtotals, ctx->hwork, ctx->pwork, items, ctx->hist_pool, W);
-    rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], ctx->hwork, ctx->hist_pool, N, ctx->step);
+    hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
+                       ctx->nodes, ctx->qtotals, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
+                       ctx->scan_counters, ctx->hist_pool, W, plan.min_rows_per_group, plan.max_groups);
+    rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], false, ((uintptr_t)bins & 15) == 0,
+                     ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
+                     (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
     if (rc != QGBDT_OK) return rc;
-    rc = launch_scan_items(ctx, ctx->hist_pool, items, 2, ctx->delta, p->min_data_in_leaf, p->min_sum_hessian,
-                           ctx->cand);
+    rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 1, ctx->delta,
+                           p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    for (int k = 0; k + 1 < p->num_leaves; ++k) {
-        hipLaunchKernelGGL(tree_choose_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->step, ctx->leaves, ctx->cand,
-                           items, F, p->num_leaves, k, ctx->pwork, ctx->hwork, items, out);
-        rc = launch_partition_work(ctx, bins, ctx->idx[0], ctx->idx[1], ctx->pwork, &ctx->step->n_left, N);
+    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int) + 1) + 64;
+    const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
+    int launched = 0;
+    int to_launch = ctx->rounds_hint;
+    for (;;) {
+        for (int r = 0; r < to_launch; ++r) {
+            hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
+                               ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
+                               ctx->max_expand, out);
+            rc = launch_batch_partition_count(ctx, bins);
+            if (rc != QGBDT_OK) return rc;
+            hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
+                               ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
+                               plan.min_rows_per_group, plan.max_groups);
+            rc = launch_batch_partition_scatter(ctx);
+            if (rc != QGBDT_OK) return rc;
+            rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], true, false, ctx->hist_entries,
+                             ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
+            if (rc != QGBDT_OK) return rc;
+            rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
+                                   ctx->delta, p->min_data_in_leaf, p->min_sum_hessian);
+            if (rc != QGBDT_OK) return rc;
+        }
+        launched += to_launch;
+        // one more plan: commits what the last round made known and tells whether the tree is finished
+        hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
+                           ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
+                           ctx->max_expand, out);
+        QG_HIP(ctx, hipGetLastError());
+        QG_HIP(ctx, hipMemcpyAsync(ctx->host_state, ctx->step, sizeof(StepState), hipMemcpyDeviceToHost, ctx->stream));
+        QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->host_state->done) break;
+        if (launched > round_cap) return set_error(ctx, QGBDT_E_HIP, "tree growth did not finish in %d rounds", launched);
+        // the trailing plan has already chosen a batch: finish that round, then continue
+        rc = launch_batch_partition_count(ctx, bins);
         if (rc != QGBDT_OK) return rc;
-        hipLaunchKernelGGL(tree_after_partition_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->step, ctx->leaves,
-                           ctx->hwork, items, k, out);
-        rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], ctx->hwork, ctx->hist_pool, N / 2 + 1,
-                         ctx->step);
+        hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
+                           ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
+                           plan.min_rows_per_group, plan.max_groups);
+        rc = launch_batch_partition_scatter(ctx);
         if (rc != QGBDT_OK) return rc;
-        rc = launch_scan_items(ctx, ctx->hist_pool, items, 2, ctx->delta, p->min_data_in_leaf, p->min_sum_hessian,
-                               ctx->cand);
+        rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], true, false, ctx->hist_entries,
+                         ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
         if (rc != QGBDT_OK) return rc;
+        rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
+                               ctx->delta, p->min_data_in_leaf, p->min_sum_hessian);
+        if (rc != QGBDT_OK) return rc;
+        launched += 1;
+        to_launch = 3;
     }
-    hipLaunchKernelGGL(tree_finalize_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->step, ctx->leaves, ctx->delta,
-                       out);
+    ctx->rounds_hint = ctx->host_state->rounds > 0 ? ctx->host_state->rounds : 1;
+
+    hipLaunchKernelGGL(tree_finalize_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->step, ctx->nodes, ctx->delta,
+                       ctx->leaf_node, out);
     int gx = (int)((N / ctx->shape.max_leaves + 255) / 256);
     if (gx < 1) gx = 1;
     if (gx > 64) gx = 64;
     hipLaunchKernelGGL(tree_gather_rows_kernel, dim3(gx, ctx->shape.max_leaves), dim3(256), 0, ctx->stream, ctx->step,
-                       ctx->leaves, ctx->idx[0], ctx->idx[1], row_idx_out);
+                       ctx->nodes, ctx->leaf_node, ctx->idx[0], ctx->idx[1], row_idx_out);
     QG_HIP(ctx, hipGetLastError());
     return launch_refit(ctx, g, h, row_idx_out, out.t.leaf_begin, out.t.leaf_count, ctx->shape.max_leaves,
                         out.t.n_leaves, out.t.leaf_value);

@@ -23,8 +23,8 @@ def _pack_gh(gq, hq):
 
 
 def _pack_hist(hist):
-    """oracle hist [F, nb, 2] -> packed 32|32 words (the library's layout)."""
-    return (hist[..., 0].astype(np.int64) << 32) + hist[..., 1].astype(np.int64)
+    """oracle hist [F, nb, 2] -> packed 32|32 words in the library's [nb, F] layout."""
+    return np.ascontiguousarray(((hist[..., 0].astype(np.int64) << 32) + hist[..., 1].astype(np.int64)).T)
 
 
 def _rand_gh(rng, N, bits_g, bits_h, dev):
@@ -110,7 +110,7 @@ def test_histogram_bit_exact(N, F, nb, bg, bh, acc):
         gkw = dict(kw)
         if "row_idx" in gkw:
             gkw["row_idx"] = didx
-        got = ctx.build_histograms(dbins, gh, bits_g=bg, bits_h=bh, acc_width=acc, **gkw).cpu().numpy().reshape(F, nb)
+        got = ctx.build_histograms(dbins, gh, bits_g=bg, bits_h=bh, acc_width=acc, **gkw).cpu().numpy().reshape(nb, F)
         assert np.array_equal(got, exp), (kw.keys(), acc)
 
 
@@ -127,7 +127,7 @@ def test_histogram_worst_case_first_tree_values():
         exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq))
         for acc in (16, 32):
             got = ctx.build_histograms(torch.from_numpy(bins).cuda(), gh, bits_g=bg, bits_h=bh, acc_width=acc)
-            assert np.array_equal(got.cpu().numpy().reshape(F, nb), exp)
+            assert np.array_equal(got.cpu().numpy().reshape(nb, F), exp)
 
 
 def test_subtract_bit_exact():
@@ -143,9 +143,9 @@ def test_subtract_bit_exact():
     hl = ctx.build_histograms(dbins, gh, row_idx=torch.from_numpy(left).cuda(), bits_g=4, bits_h=4)
     hr = ctx.subtract_histograms(hp, hl)
     exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq, row_idx=idx[bins[:, 3] > 100]))
-    assert np.array_equal(hr.cpu().numpy().reshape(F, nb), exp)
+    assert np.array_equal(hr.cpu().numpy().reshape(nb, F), exp)
     ctx.subtract_histograms(hp, hl, out=hp)                                # aliasing the parent
-    assert np.array_equal(hp.cpu().numpy().reshape(F, nb), exp)
+    assert np.array_equal(hp.cpu().numpy().reshape(nb, F), exp)
 
 
 # ----------------------------------------------------------------------------
