@@ -85,6 +85,7 @@ def main():
 
     # ---- timed region: W warm-up steps, then exactly K steps ---------------------------------
     units = torch.zeros(1, dtype=torch.int64, device=dev)
+    stats = []
     for it in range(W):
         ctx.grow_tree(bins, gs[it], hs[it], bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf,
                       acc_width=args.acc_width, tree=tree)
@@ -97,6 +98,7 @@ def main():
         ctx.grow_tree(bins, gs[it], hs[it], bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf,
                       acc_width=args.acc_width, tree=tree)
         units += tree.hist_units
+        stats.append(ctx.tree_stats())
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     hist_ms, hist_launches, hist_bytes = ctx.read_profile()
@@ -164,6 +166,8 @@ def main():
                       "rows_x_features_per_s": N * F / (root_avg_ms * 1e-3) if root_avg_ms > 0 else 0.0,
                       "reps": root_n},
         "hist_time_share": hist_ms / (elapsed * 1e3),
+        "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,
+                   "committed_per_tree": sum(x[2] for x in stats) / K},
         "cpu_baseline": cpu,
         "paper_context": "paper: V100, Higgs 10.5M x 28, 3-bit: 4.74 s histogram time / 500 trees = 9.5 ms per tree "
                          "(another machine; context, not the target)",

@@ -196,6 +196,11 @@ QGBDT_API int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on);
 QGBDT_API int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches,
                        double* hist_bytes);
 
+/* Figures of the last grow_tree call on this context (host out int32[4]): rounds of
+ * batched expansion, nodes expanded (committed splits plus speculative ones), committed
+ * splits, nodes created.  For callers that time or tune; no paper quantity. */
+QGBDT_API int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4);
+
 #ifdef __cplusplus
 }
 #endif

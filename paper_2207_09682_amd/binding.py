@@ -23,7 +23,7 @@ EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
     "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
     "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
-    "qgbdt_set_profiling", "qgbdt_read_profile",
+    "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats",
 ]
 
 
@@ -77,6 +77,7 @@ def load_library() -> C.CDLL:
                                         C.POINTER(TreePtrs), C.c_void_p]
         lib.qgbdt_set_profiling.argtypes = [C.c_void_p, C.c_int32]
         lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        lib.qgbdt_tree_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         _lib = lib
     return _lib
 
@@ -256,6 +257,16 @@ class Context:
         ms = C.c_double(0); n = C.c_int64(0); b = C.c_double(0)
         self._chk(self.lib.qgbdt_read_profile(self._h, C.byref(ms), C.byref(n), C.byref(b)))
         return ms.value, n.value, b.value
+
+
+def _tree_stats(self):
+    """(rounds, expanded nodes, committed splits, nodes) of the last grow_tree call."""
+    out = (C.c_int32 * 4)()
+    self._chk(self.lib.qgbdt_tree_stats(self._h, out))
+    return tuple(int(x) for x in out)
+
+
+Context.tree_stats = _tree_stats
 
 
 def unpack_splits(raw: torch.Tensor):

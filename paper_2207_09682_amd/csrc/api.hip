@@ -304,4 +304,11 @@ int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches, 
     return QGBDT_OK;
 }
 
+int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4) {
+    if (!ctx || !out4 || !ctx->host_state) return QGBDT_E_INVALID_ARG;
+    out4[0] = ctx->host_state->rounds; out4[1] = ctx->host_state->n_expanded;
+    out4[2] = ctx->host_state->n_commits; out4[3] = ctx->host_state->n_nodes;
+    return QGBDT_OK;
+}
+
 }  // extern "C"

@@ -36,13 +36,12 @@ __global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n,
 
 // One workgroup per (feature, histogram): thread b owns bin b.  Workgroup-wide
 // inclusive scan of the packed words (fields cannot overflow: every prefix is
-// bounded by the leaf totals), then each thread evaluates its threshold.  The
-// workgroup that finishes a histogram's last feature reduces its per-feature
-// candidates to the histogram's best split (counter + fences, no waiting).
+// bounded by the leaf totals), then each thread evaluates its threshold and the
+// workgroup keeps the feature's best one.
 __global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                    const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                    const float* __restrict__ delta, int64_t min_data,
-                                                   double min_sum_hess, FeatCand* cand_base, int32_t* counters) {
+                                                   double min_sum_hess, FeatCand* cand_base) {
     const int n_items = *n_items_ptr;
     const int f = blockIdx.x, b = threadIdx.x;
     const int lane = b & 63, wave = b >> 6;
@@ -53,7 +52,6 @@ __global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const Sca
     __shared__ double sg[4];
     __shared__ int sb[4];
     __shared__ int64_t sl[4];
-    __shared__ int s_last;
     for (int item = blockIdx.y; item < n_items; item += gridDim.y) {
         const ScanItem it = items[item];
         if (!it.valid) continue;
@@ -110,16 +108,21 @@ __global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const Sca
             FeatCand c;
             c.gain = gain; c.left = left; c.bin = bin; c.pad = 0;
             cand_base[(int64_t)item * F + f] = c;
-            __threadfence();  // the candidate is visible before the count
-            s_last = (atomicAdd(&counters[item], 1) == F - 1) ? 1 : 0;
         }
         __syncthreads();
-        if (s_last) {
-            __threadfence();  // the other workgroups' candidates are visible after the count
-            reduce_features(cand_base + (int64_t)item * F, F, it.stat, it.out, b, blockDim.x);
-            if (b == 0) counters[item] = 0;
-        }
-        __syncthreads();
+    }
+}
+
+// Per-feature candidates -> best split of every scanned histogram, one wavefront per histogram.
+__global__ __launch_bounds__(256) void reduce_items_kernel(const FeatCand* __restrict__ cand_base,
+                                                           const ScanItem* __restrict__ items,
+                                                           const int32_t* __restrict__ n_items_ptr, int F) {
+    const int n_items = *n_items_ptr;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int item = blockIdx.x * 4 + wave; item < n_items; item += gridDim.x * 4) {
+        const ScanItem it = items[item];
+        if (!it.valid) continue;
+        reduce_features_wave(cand_base + (int64_t)item * F, F, it.stat, it.out, lane);
     }
 }
 
@@ -133,7 +136,10 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
     if (gy > max_items) gy = max_items;
     if (gy < 1) gy = 1;
     hipLaunchKernelGGL(scan_kernel, dim3(F, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb, delta,
-                       (int64_t)min_data, min_sum_hess, ctx->cand, ctx->scan_counters);
+                       (int64_t)min_data, min_sum_hess, ctx->cand);
+    int gr = (max_items + 3) / 4;
+    if (gr > 64) gr = 64;
+    hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, ctx->cand, items, n_items, F);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

@@ -35,13 +35,13 @@ __device__ __forceinline__ int64_t count_estimate(int64_t HL, int64_t Hs, int64_
 }
 
 // Reduces the per-feature candidates of one leaf to its best split: largest gain,
-// ties to the lowest feature.  Must be called by all threads of a workgroup of
-// `nthreads` (multiple of 64, <= 1024); thread 0 writes the result.
-__device__ inline void reduce_features(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
-                                       int tid, int nthreads) {
+// ties to the lowest feature.  Called by all 64 lanes of one wavefront; lane 0
+// writes the result.
+__device__ inline void reduce_features_wave(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
+                                            int lane) {
     double bg = 0.0;
     int bf = -1;
-    for (int f = tid; f < F; f += nthreads) {
+    for (int f = lane; f < F; f += 64) {
         const FeatCand c = cand[f];
         if (c.bin >= 0 && (c.gain > bg)) { bg = c.gain; bf = f; }  // ascending f: strict > keeps the lowest
     }
@@ -50,14 +50,7 @@ __device__ inline void reduce_features(const FeatCand* cand, int F, const qgbdt_
         const int of = __shfl_xor(bf, o);
         if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) { bg = og; bf = of; }
     }
-    __shared__ double sg[16];
-    __shared__ int sf[16];
-    const int w = tid >> 6;
-    if ((tid & 63) == 0) { sg[w] = bg; sf[w] = bf; }
-    __syncthreads();
-    if (tid == 0) {
-        for (int k = 1; k < (nthreads >> 6); ++k)
-            if (sf[k] >= 0 && (bf < 0 || sg[k] > bg || (sg[k] == bg && sf[k] < bf))) { bg = sg[k]; bf = sf[k]; }
+    if (lane == 0) {
         qgbdt_split s;
         s.gain = 0.0; s.feature = -1; s.bin = -1;
         s.left_g = s.left_h = s.right_g = s.right_h = s.left_count = 0;
@@ -70,7 +63,6 @@ __device__ inline void reduce_features(const FeatCand* cand, int F, const qgbdt_
         }
         *out = s;
     }
-    __syncthreads();
 }
 
 }  // namespace qgbdt

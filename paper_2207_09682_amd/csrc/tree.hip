@@ -99,38 +99,46 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     double* key = reinterpret_cast<double*>(plan_lds);
     int* lid = reinterpret_cast<int*>(key + (2 * max_expand + 1));
     int* cand = lid + (2 * max_expand + 1);          // compacted candidates of the batch selection
-    unsigned char* expd = reinterpret_cast<unsigned char*>(cand + (2 * max_expand + 1));
+    int* open = cand + (2 * max_expand + 1);         // open leaves that can be split (unordered list)
+    unsigned char* expd = reinterpret_cast<unsigned char*>(open + (2 * max_expand + 1));
     __shared__ int s_tmp[16];
-    __shared__ int s_done, s_ncand, s_stall;
+    __shared__ int s_done, s_ncand, s_nopen;
     const int tid = threadIdx.x;
+    if (tid == 0) { s_done = 0; s_ncand = 0; s_nopen = 0; }
+    __syncthreads();
     for (int i = tid; i < n_nodes0; i += blockDim.x) {
-        const Node nd = nodes[i];
-        key[i] = (nd.state == 1 && nd.best.feature >= 0) ? nd.best.gain : -1.0;
-        lid[i] = nd.leaf_id;
-        expd[i] = (unsigned char)nd.expanded;
+        const Node* nd = &nodes[i];
+        const int st = nd->state, ft = nd->best.feature;
+        const double kg = (st == 1 && ft >= 0) ? nd->best.gain : -1.0;
+        key[i] = kg;
+        lid[i] = nd->leaf_id;
+        expd[i] = (unsigned char)nd->expanded;
+        if (kg > 0.0) open[atomicAdd(&s_nopen, 1)] = i;
     }
-    if (tid == 0) { s_done = 0; s_ncand = 0; s_stall = -1; }
     __syncthreads();
 
     if (tid < 64) {  // replay of the best-first order, one wavefront
-        int n_commits = step->n_commits, n_leaves = step->n_leaves;
+        int n_commits = step->n_commits, n_leaves = step->n_leaves, n_open = s_nopen;
         int64_t units = step->hist_units;
         for (;;) {
             if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
             double bg = 0.0;
-            int bi = -1, bl = 0x7fffffff;
-            for (int i = tid; i < n_nodes0; i += 64) {
+            int bi = -1, bl = 0x7fffffff, bp = -1;
+            for (int p = tid; p < n_open; p += 64) {
+                const int i = open[p];
                 const double g = key[i];
-                if (g > 0.0 && (g > bg || (g == bg && lid[i] < bl))) { bg = g; bi = i; bl = lid[i]; }
+                const int l = lid[i];
+                if (g > bg || (g == bg && l < bl)) { bg = g; bi = i; bl = l; bp = p; }
             }
             for (int o = 32; o > 0; o >>= 1) {
                 const double og = __shfl_xor(bg, o);
-                const int oi = __shfl_xor(bi, o), ol = __shfl_xor(bl, o);
-                if (oi >= 0 && (bi < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bi = oi; bl = ol; }
+                const int oi = __shfl_xor(bi, o), ol = __shfl_xor(bl, o), op = __shfl_xor(bp, o);
+                if (oi >= 0 && (bi < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bi = oi; bl = ol; bp = op; }
             }
-            if (bi < 0) { if (tid == 0) s_done = 1; break; }      // no open leaf has a gain > 0
-            if (!expd[bi]) { if (tid == 0) s_stall = bi; break; }  // next split is not known yet
+            if (bi < 0) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
+            if (!expd[bi]) break;                              // the next split is not known yet
             // commit split number n_commits: node bi, leaf id bl
+            int add0 = 0, add1 = 0, c0 = 0;
             if (tid == 0) {
                 const Node nd = nodes[bi];
                 const int k = n_commits;
@@ -142,18 +150,30 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
                 const int64_t nl = nd.n_left, nr = nd.count - nd.n_left;
                 units += (nl <= nr ? nl : nr) * (int64_t)F;
                 nodes[bi].state = 2;
-                const int c0 = nd.child, c1 = nd.child + 1;
+                c0 = nd.child;
+                const int c1 = c0 + 1;
                 nodes[c0].state = 1; nodes[c0].leaf_id = bl;
                 nodes[c1].state = 1; nodes[c1].leaf_id = n_leaves;
                 const qgbdt_split b0 = nodes[c0].best, b1 = nodes[c1].best;
                 key[bi] = -1.0;
                 key[c0] = (b0.feature >= 0) ? b0.gain : -1.0; lid[c0] = bl;
                 key[c1] = (b1.feature >= 0) ? b1.gain : -1.0; lid[c1] = n_leaves;
+                add0 = key[c0] > 0.0; add1 = key[c1] > 0.0;
+                // open list: the committed node leaves, its splittable children enter
+                open[bp] = open[n_open - 1];
+                int no = n_open - 1;
+                if (add0) open[no++] = c0;
+                if (add1) open[no++] = c1;
             }
+            add0 = __shfl(add0, 0); add1 = __shfl(add1, 0);
+            n_open += add0 + add1 - 1;
             n_commits += 1; n_leaves += 1;
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         }
-        if (tid == 0) { step->n_commits = n_commits; step->n_leaves = n_leaves; step->hist_units = units; }
+        if (tid == 0) {
+            step->n_commits = n_commits; step->n_leaves = n_leaves; step->hist_units = units;
+            s_nopen = n_open;
+        }
     }
     __syncthreads();
     if (s_done) {
@@ -171,8 +191,10 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     int want = 1 + (spare > 0 ? spare : 0);
     if (want > remaining) want = remaining;
     if (want > batch_max) want = batch_max;
-    for (int i = tid; i < n_nodes0; i += blockDim.x)
-        if (key[i] > 0.0 && !expd[i]) cand[atomicAdd(&s_ncand, 1)] = i;
+    for (int p = tid; p < s_nopen; p += blockDim.x) {
+        const int i = open[p];
+        if (!expd[i]) cand[atomicAdd(&s_ncand, 1)] = i;
+    }
     __syncthreads();
     const int nc = s_ncand;
     const int n_batch = nc < want ? nc : want;
@@ -357,7 +379,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int) + 1) + 64;
+    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 3 * sizeof(int) + 1) + 64;
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
