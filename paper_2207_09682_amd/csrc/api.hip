@@ -50,7 +50,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 }
 
 static void free_all(qgbdt_ctx* c) {
-    void* ptrs[] = {c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+    void* ptrs[] = {c->obins[0], c->obins[1], c->ogh[0], c->ogh[1], c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -103,6 +103,14 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     c->max_seg = (int)(N / PART_SEG) + c->batch_max + 2;
     c->rounds_hint = 10;
     int rc = QGBDT_OK;
+    // narrow rows: moving a row costs less than gathering it twice per level
+    c->ordered = (shape->n_features % 4 == 0 && shape->n_features >= 16 && shape->n_features <= 64) ? 1 : 0;
+    if (c->ordered) {
+        for (int b = 0; b < 2 && rc == QGBDT_OK; ++b) {
+            rc = ws_alloc(c, &c->obins[b], (size_t)N * shape->n_features);
+            if (rc == QGBDT_OK) rc = ws_alloc(c, &c->ogh[b], (size_t)N);
+        }
+    }
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
@@ -207,10 +215,12 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     const HistPlan plan = make_hist_plan(ctx->shape, bits_g, bits_h, acc_width);
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
-    return launch_hist(ctx, plan, (const uint8_t*)bins, gh, row_idx, row_idx, row_idx != nullptr,
-                       (((uintptr_t)bins + (uint64_t)begin * ctx->shape.n_features) & 15) == 0, ctx->hist_entries,
-                       ctx->hist_counts, hist_out, (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group,
-                       ctx->step);
+    RowSource rows;
+    rows.bins[0] = rows.bins[1] = rows.bins[2] = (const uint8_t*)bins;
+    rows.gh[0] = rows.gh[1] = rows.gh[2] = gh;
+    return launch_hist(ctx, plan, rows, row_idx, row_idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
+                       ctx->hist_entries, ctx->hist_counts, hist_out,
+                       (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
 }
 
 int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* sibling_out) {

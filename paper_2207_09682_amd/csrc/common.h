@@ -96,6 +96,14 @@ struct HistPlan {
 
 struct ScanItem;
 
+// Where the rows of a slice live.  Buffer 2 is the caller's data in original row order (bin
+// matrix, quantized gradients); buffers 0 and 1 are the library's leaf-ordered copies, which
+// exist only in ordered mode (narrow rows).  Row ids of buffers 0 and 2 share one array.
+struct RowSource {
+    const uint8_t* bins[3];
+    const int16_t* gh[3];
+};
+
 }  // namespace qgbdt
 
 struct qgbdt_ctx {
@@ -110,6 +118,9 @@ struct qgbdt_ctx {
     int max_seg;
     int rounds_hint;
     // workspace
+    int ordered;           // narrow rows: children get physically leaf-ordered copies of their rows
+    uint8_t* obins[2];     // [N][F] each (ordered mode)
+    int16_t* ogh[2];       // [N] each (ordered mode)
     int32_t* idx[2];       // [N] each
     int16_t* gh;           // [N]
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
@@ -144,7 +155,7 @@ namespace qgbdt {
 
 constexpr int PART_GROUPS = 512;
 constexpr int REFIT_PARTS = 32;
-constexpr int PART_SEG = 2048;  // rows per partition segment of the batched partition
+constexpr int PART_SEG = 1024;  // rows per partition segment of the batched partition
 
 int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...);
 
@@ -163,9 +174,9 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh, const int32_t* idx0,
-                const int32_t* idx1, bool use_idx, bool flat_aligned, const HistEntry* entries,
-                const int32_t* table_counts, int64_t* hist_base, int64_t grid_items, StepState* step);
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const int32_t* idx0, const int32_t* idx1,
+                bool use_idx, bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
+                int64_t grid_items, StepState* step);
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
@@ -176,8 +187,8 @@ int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, in
                           int64_t* n_left_out, int64_t max_count);
 int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,
                        int feature, int bin, int64_t* n_left_out);
-int launch_batch_partition_count(qgbdt_ctx* ctx, const uint8_t* bins);
-int launch_batch_partition_scatter(qgbdt_ctx* ctx);
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows);
+int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);

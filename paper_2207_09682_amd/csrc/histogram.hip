@@ -113,8 +113,7 @@ __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_
 // cost ~5 VALU instructions: one bit-field extract and one 24-bit multiply-add
 // into the byte address of its LDS word, plus its share of the per-row work.
 template <int W, bool IDX, int U>
-__global__ __launch_bounds__(1024) void hist_kernel(const uint8_t* __restrict__ bins, const int16_t* __restrict__ gh,
-                                                    const int32_t* __restrict__ idx0,
+__global__ __launch_bounds__(1024) void hist_kernel(RowSource src, const int32_t* __restrict__ idx0,
                                                     const int32_t* __restrict__ idx1,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
@@ -150,7 +149,6 @@ __global__ __launch_bounds__(1024) void hist_kernel(const uint8_t* __restrict__ 
     }
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);  // LDS bytes per bin row
     const int S = U * rpi;                                          // rows per block of one wavefront
-    const uint8_t* colbase = bins + f0 + 4 * q;
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
@@ -159,7 +157,11 @@ __global__ __launch_bounds__(1024) void hist_kernel(const uint8_t* __restrict__ 
         if (gbegin >= en.count) continue;
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        const int32_t* idx = IDX ? ((en.buf ? idx1 : idx0) + en.begin) : nullptr;
+        const int32_t* idx = IDX ? ((en.buf == 1 ? idx1 : idx0) + en.begin) : nullptr;
+        // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
+        const int sb = IDX ? 2 : en.buf;
+        const uint8_t* colbase = src.bins[sb] + f0 + 4 * q;
+        const int16_t* gh = src.gh[sb];
 
         for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
@@ -229,8 +231,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(const uint8_t* __restrict__ 
 // whole kernel; they lie in at most two consecutive rows.  Blocks of U iterations
 // are software-pipelined like in hist_kernel.
 template <int W, int U>
-__global__ __launch_bounds__(1024) void hist_flat_kernel(const uint8_t* __restrict__ bins,
-                                                         const int16_t* __restrict__ gh,
+__global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
                                                          const HistEntry* __restrict__ entries,
                                                          const int32_t* __restrict__ table_counts,
                                                          int64_t* hist_base, int F, int nb, HistPlan plan,
@@ -276,18 +277,28 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(const uint8_t* __restri
     const int chunk = plan.chunk_rows / BR * BR > 0 ? plan.chunk_rows / BR * BR : BR;
     const int dpr = F / 4;
 
+    const int align_rows = 16 / ((F % 16 == 0) ? 16 : (F % 8 == 0) ? 8 : 4);  // rows after which a row start is 16-byte aligned again
+
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
-        int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
+        const uint8_t* bins = src.bins[en.buf];
+        const int16_t* gh = src.gh[en.buf];
+        // the first rows up to a 16-byte aligned row start are taken by group 0, one dword at a time
+        const int64_t head = min(en.count, (int64_t)((align_rows - (int)(en.begin % align_rows)) % align_rows));
+        const int64_t body = en.count - head;
+        int64_t rows_per_group = (body + en.groups - 1) / en.groups;
         rows_per_group = (rows_per_group + BR - 1) / BR * BR;  // keeps every group start 16-byte aligned
-        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
-        if (gbegin >= en.count) continue;
+        if (rows_per_group < BR) rows_per_group = BR;
+        const int g = item - en.item_start;
+        const int64_t gbegin = head + (int64_t)g * rows_per_group;
+        if (gbegin >= en.count && !(g == 0 && head > 0)) continue;
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        bool first = true;
 
-        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += chunk) {
+        for (int64_t cbegin = gbegin; first || cbegin < gend; cbegin += chunk) {
             const int64_t cend = min(gend, cbegin + (int64_t)chunk);
-            const int crow = (int)(cend - cbegin);
+            const int crow = cbegin < cend ? (int)(cend - cbegin) : 0;
             __syncthreads();
             const uint8_t* cb = bins + (en.begin + cbegin) * (int64_t)F;
             const int16_t* gb = gh + (en.begin + cbegin);
@@ -330,12 +341,17 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(const uint8_t* __restri
                     for (int u = 0; u < U; ++u) { d[u] = dn[u]; ga[u] = gan[u]; gbv[u] = gbn[u]; }
                 }
             }
-            // rows left over after the last whole block: one dword per thread and step
+            // rows left over after the last whole block, and (first chunk of group 0) the unaligned
+            // head rows in front of the group: one dword per thread and step
             const int tail0 = n_blocks * BR;
-            for (int e = threadIdx.x; e < (crow - tail0) * dpr; e += blockDim.x) {
-                const int row = tail0 + e / dpr, q = e % dpr;
-                const uint32_t dwd = *reinterpret_cast<const uint32_t*>(cb + (size_t)row * (size_t)F + 4 * q);
-                const word v = Acc<W>::expand(gb[row]);
+            const int n_head = (first && g == 0) ? (int)head : 0;
+            const int n_tail = crow - tail0;
+            for (int e = threadIdx.x; e < (n_head + n_tail) * dpr; e += blockDim.x) {
+                const int rs = e / dpr, q = e - rs * dpr;
+                // row index inside the entry: head rows come first, tail rows follow the chunk's blocks
+                const int64_t arow = rs < n_head ? (int64_t)rs : cbegin + tail0 + (rs - n_head);
+                const uint32_t dwd = *reinterpret_cast<const uint32_t*>(bins + (en.begin + arow) * (int64_t)F + 4 * q);
+                const word v = Acc<W>::expand(gh[en.begin + arow]);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const uint32_t b = (dwd >> (8 * k)) & 0xffu;
@@ -344,15 +360,14 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(const uint8_t* __restri
             }
             __syncthreads();
             merge_local<W>(lds, lds_words, ftp, F, 0, F, hist);
+            first = false;
         }
     }
 }
 
 // Any feature count (no alignment assumption): one byte load per (row, feature).
 template <int W>
-__global__ __launch_bounds__(1024) void hist_generic_kernel(const uint8_t* __restrict__ bins,
-                                                            const int16_t* __restrict__ gh,
-                                                            const int32_t* __restrict__ idx0,
+__global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, const int32_t* __restrict__ idx0,
                                                             const int32_t* __restrict__ idx1, int use_idx,
                                                             const HistEntry* __restrict__ entries,
                                                             const int32_t* __restrict__ table_counts,
@@ -376,7 +391,9 @@ __global__ __launch_bounds__(1024) void hist_generic_kernel(const uint8_t* __res
         if (gbegin >= en.count) continue;
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        const int32_t* idx = use_idx ? ((en.buf ? idx1 : idx0) + en.begin) : nullptr;
+        const int32_t* idx = use_idx ? ((en.buf == 1 ? idx1 : idx0) + en.begin) : nullptr;
+        const uint8_t* bins = src.bins[use_idx ? 2 : en.buf];
+        const int16_t* gh = src.gh[use_idx ? 2 : en.buf];
         for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             __syncthreads();
@@ -482,7 +499,7 @@ __global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64
         if (g > max_groups) g = max_groups;
         if (g < 1) g = 1;
         HistEntry e;
-        e.begin = begin; e.count = count; e.buf = 0; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
+        e.begin = begin; e.count = count; e.buf = 2; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
         entries[0] = e;
         counts[0] = 1;
         counts[1] = count > 0 ? (int32_t)g : 0;
@@ -498,9 +515,9 @@ int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, i
 
 // Launches the kernel variant for (plan, row source).  `grid_items` is the host's upper bound on
 // the number of work items; workgroups beyond the table's item count return at once.
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const int16_t* gh, const int32_t* idx0,
-                const int32_t* idx1, bool use_idx, bool flat_aligned, const HistEntry* entries,
-                const int32_t* table_counts, int64_t* hist_base, int64_t grid_items, StepState* step) {
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const int32_t* idx0, const int32_t* idx1,
+                bool use_idx, bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
+                int64_t grid_items, StepState* step) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int64_t groups = grid_items;
     if (groups > plan.max_groups) groups = plan.max_groups;
@@ -512,10 +529,10 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const
         e0 = ctx->ev[ctx->ev_used++]; e1 = ctx->ev[ctx->ev_used++];
         QG_HIP(ctx, hipEventRecord(e0, ctx->stream));
     }
-    const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_aligned;
+    const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_ok;
     if (flat) {
 #define QG_LAUNCH_FLAT(W_, U_)                                                                                   \
-    hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, bins, gh, entries, \
+    hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, entries, \
                        table_counts, hist_base, F, nb, plan, step)
         if (plan.acc_width == 16) {
             if (plan.flat_unroll >= 4) QG_LAUNCH_FLAT(16, 4);
@@ -531,7 +548,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
 #define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                              \
-    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1, \
+    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1, \
                        entries, table_counts, hist_base, F, nb, plan, step)
 #define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
     switch (U) {                                                                        \
@@ -549,10 +566,10 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const uint8_t* bins, const
 #undef QG_LAUNCH_HIST_U
 #undef QG_LAUNCH_HIST
     } else if (plan.acc_width == 16) {
-        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1,
+        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1,
                            use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     } else {
-        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, bins, gh, idx0, idx1,
+        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1,
                            use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     }
     QG_HIP(ctx, hipGetLastError());

@@ -168,8 +168,10 @@ __device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, 
 }
 
 // Left-going rows per segment (flags kept as bytes); on the way the histogram slots
-// that this round's builds accumulate into are cleared.
-__global__ __launch_bounds__(256) void batch_part_count_kernel(const uint8_t* __restrict__ bins, int F,
+// that this round's builds accumulate into are cleared.  In ordered mode the rows of a
+// node are physically contiguous in its buffer and the bin is read at the row's position;
+// otherwise it is gathered from the original matrix through the row id.
+__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int F,
                                                                const int32_t* __restrict__ buf0,
                                                                const int32_t* __restrict__ buf1,
                                                                const StepState* __restrict__ step,
@@ -191,14 +193,15 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(const uint8_t* __
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
-        const int32_t* src = (nd.buf ? buf1 : buf0) + nd.begin;
+        const int32_t* src = (nd.buf == 1 ? buf1 : buf0) + nd.begin;
+        const uint8_t* brow = rows.bins[ordered ? nd.buf : 2] + (ordered ? nd.begin * (int64_t)F : 0);
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int feature = nd.best.feature, bin = nd.best.bin;
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
-            const int64_t row = src[p];
-            const int fl = bins[row * F + feature] <= bin;
+            const int64_t row = ordered ? p : (int64_t)src[p];
+            const int fl = brow[row * F + feature] <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;
         }
@@ -210,9 +213,15 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(const uint8_t* __
     }
 }
 
-// Order-preserving scatter of every segment into the other index buffer; seg_prefix is the
-// exclusive prefix of seg_counts over all segments of the round.
-__global__ __launch_bounds__(256) void batch_part_scatter_kernel(const int32_t* __restrict__ buf0r,
+// Order-preserving scatter of every segment into the other buffer; seg_prefix is the
+// exclusive prefix of seg_counts over all segments of the round.  ORDERED: the packed
+// gradients and the bin rows move with the row ids, so that the children's rows are
+// contiguous again (rows are copied as dwords by the whole workgroup, coalesced on the
+// reading side and in two compacted streams on the writing side).
+template <bool ORDERED>
+__global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows, uint8_t* obins0, uint8_t* obins1,
+                                                                 int16_t* ogh0, int16_t* ogh1, int F,
+                                                                 const int32_t* __restrict__ buf0r,
                                                                  const int32_t* __restrict__ buf1r, int32_t* buf0w,
                                                                  int32_t* buf1w, const StepState* __restrict__ step,
                                                                  const BatchEntry* __restrict__ batch,
@@ -222,12 +231,19 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(const int32_t* 
     if (step->done) return;
     const int n_items = step->n_part_items, n_batch = step->n_batch;
     __shared__ int wl[4];
+    __shared__ int s_dpos[256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int dpr = F / 4;
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
-        const int32_t* src = (nd.buf ? buf1r : buf0r) + nd.begin;
-        int32_t* dst = (nd.buf ? buf0w : buf1w) + nd.begin;
+        const bool to0 = nd.buf == 1;  // children of buffer 1 go to buffer 0, all others to buffer 1
+        const int32_t* src = (nd.buf == 1 ? buf1r : buf0r) + nd.begin;
+        int32_t* dst = (to0 ? buf0w : buf1w) + nd.begin;
+        const int16_t* gsrc = ORDERED ? rows.gh[nd.buf] + nd.begin : nullptr;
+        int16_t* gdst = ORDERED ? (to0 ? ogh0 : ogh1) + nd.begin : nullptr;
+        const uint8_t* bsrc = ORDERED ? rows.bins[nd.buf] + nd.begin * (int64_t)F : nullptr;
+        uint8_t* bdst = ORDERED ? (to0 ? obins0 : obins1) + nd.begin * (int64_t)F : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int64_t before = seg_prefix[item] - seg_prefix[be.seg_start];  // left rows in earlier segments
@@ -238,7 +254,12 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(const int32_t* 
             const bool on = p < send;
             int fl = 0;
             int32_t v = 0;
-            if (on) { fl = flags[nd.begin + p]; v = src[p]; }
+            int g16 = 0;
+            if (on) {
+                fl = flags[nd.begin + p];
+                v = src[p];
+                if (ORDERED) g16 = gsrc[p];
+            }
             const unsigned long long m = __ballot(on && fl);
             const int rank = __popcll(m & ((1ull << lane) - 1ull));
             __syncthreads();
@@ -247,11 +268,34 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(const int32_t* 
             int lw = 0, ltile = 0;
             for (int k = 0; k < 4; ++k) { if (k < wave) lw += wl[k]; ltile += wl[k]; }
             const int pos_in_tile = wave * 64 + lane;
+            const int64_t dp = fl ? lpos + lw + rank : rpos + (pos_in_tile - (lw + rank));
             if (on) {
-                if (fl) dst[lpos + lw + rank] = v;
-                else dst[rpos + (pos_in_tile - (lw + rank))] = v;
+                dst[dp] = v;
+                if (ORDERED) gdst[dp] = (int16_t)g16;
             }
             const int tile_n = (int)min((int64_t)256, send - t0);
+            if (ORDERED) {
+                s_dpos[threadIdx.x] = (int)dp;  // destination row, relative to the slice
+                __syncthreads();
+                const uint32_t* s32 = reinterpret_cast<const uint32_t*>(bsrc + t0 * (int64_t)F);
+                const int n_dw = tile_n * dpr;
+                for (int e0 = threadIdx.x; e0 < n_dw; e0 += 4 * 256) {  // four independent loads in flight
+                    uint32_t v4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * 256;
+                        v4[u] = e < n_dw ? s32[e] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * 256;
+                        if (e < n_dw) {
+                            const int r = e / dpr, q = e - r * dpr;
+                            reinterpret_cast<uint32_t*>(bdst + (int64_t)s_dpos[r] * F)[q] = v4[u];
+                        }
+                    }
+                }
+            }
             lpos += ltile;
             rpos += tile_n - ltile;
         }
@@ -265,19 +309,26 @@ static int batch_part_grid(const qgbdt_ctx* ctx) {
     return (int)g;
 }
 
-int launch_batch_partition_count(qgbdt_ctx* ctx, const uint8_t* bins) {
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows) {
     const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
-    hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, bins,
-                       ctx->shape.n_features, ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
-                       ctx->seg_counts, ctx->hist_pool, W);
+    hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
+                       ctx->ordered, ctx->shape.n_features, ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes,
+                       ctx->flags, ctx->seg_counts, ctx->hist_pool, W);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
-int launch_batch_partition_scatter(qgbdt_ctx* ctx) {
-    hipLaunchKernelGGL(batch_part_scatter_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, ctx->idx[0],
-                       ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
-                       ctx->seg_prefix);
+int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows) {
+    if (ctx->ordered)
+        hipLaunchKernelGGL(batch_part_scatter_kernel<true>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
+                           ctx->obins[0], ctx->obins[1], ctx->ogh[0], ctx->ogh[1], ctx->shape.n_features, ctx->idx[0],
+                           ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                           ctx->seg_prefix);
+    else
+        hipLaunchKernelGGL(batch_part_scatter_kernel<false>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
+                           ctx->obins[0], ctx->obins[1], ctx->ogh[0], ctx->ogh[1], ctx->shape.n_features, ctx->idx[0],
+                           ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                           ctx->seg_prefix);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

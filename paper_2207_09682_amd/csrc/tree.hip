@@ -42,7 +42,7 @@ __device__ __forceinline__ int hist_groups(int64_t count, int min_rows, int max_
 }
 
 __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, int F, StepState* step, Node* nodes,
-                                                        const int64_t* qtotals, HistEntry* hist_entries,
+                                                        const int64_t* qtotals, int root_buf, HistEntry* hist_entries,
                                                         int32_t* hist_counts, ScanItem* items, int32_t* scan_counters,
                                                         int64_t* hist0, int64_t hist_words, int min_rows,
                                                         int max_groups) {
@@ -55,12 +55,12 @@ __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N
         step->n_slots = 1; step->n_batch = 0; step->rounds = 0; step->n_part_items = 0; step->n_scan_items = 1;
         step->hist_units = N * (int64_t)F;
         Node r;
-        r.begin = 0; r.count = N; r.sum_g = qtotals[0]; r.sum_h = qtotals[1]; r.n_left = 0; r.buf = 0; r.slot = 0;
+        r.begin = 0; r.count = N; r.sum_g = qtotals[0]; r.sum_h = qtotals[1]; r.n_left = 0; r.buf = root_buf; r.slot = 0;
         r.state = 1; r.expanded = 0; r.child = -1; r.leaf_id = 0;
         clear_split(r.best);
         nodes[0] = r;
         HistEntry e;
-        e.begin = 0; e.count = N; e.buf = 0; e.slot = 0; e.item_start = 0; e.groups = hist_groups(N, min_rows, max_groups);
+        e.begin = 0; e.count = N; e.buf = root_buf; e.slot = 0; e.item_start = 0; e.groups = hist_groups(N, min_rows, max_groups);
         hist_entries[0] = e;
         hist_counts[0] = 1; hist_counts[1] = e.groups;
         ScanItem it;
@@ -88,38 +88,41 @@ __device__ __forceinline__ int block_scan_incl(int v, int* tmp /*[16]*/) {
 }
 
 // Commit phase and choice of the round's batch.  One workgroup of 1024 threads; the
-// replay itself runs in its first wavefront.
+// replay itself runs in its first wavefront on an LDS copy of the queue (gain, leaf id,
+// children, expanded flag of every node) and only records the order of the commits; the
+// outputs of the committed splits are then written by all threads.
 __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
                                                          int32_t* hist_counts, int32_t* scan_counters, int F,
                                                          int num_leaves, int batch_max, int max_expand, TreeOut out) {
     if (step->done) return;
     extern __shared__ unsigned char plan_lds[];
     const int n_nodes0 = step->n_nodes;
-    // queue view: gain of every open leaf that can be split (else -1), its leaf id, expanded flag
-    double* key = reinterpret_cast<double*>(plan_lds);
-    int* lid = reinterpret_cast<int*>(key + (2 * max_expand + 1));
-    int* cand = lid + (2 * max_expand + 1);          // compacted candidates of the batch selection
-    int* open = cand + (2 * max_expand + 1);         // open leaves that can be split (unordered list)
-    unsigned char* expd = reinterpret_cast<unsigned char*>(open + (2 * max_expand + 1));
+    const int cap = 2 * max_expand + 1;
+    double* key = reinterpret_cast<double*>(plan_lds);  // gain of the node's best split, -1 if it has none
+    int* lid = reinterpret_cast<int*>(key + cap);       // leaf id (open leaves)
+    int* child = lid + cap;                             // left child, -1 if not expanded
+    int* cand = child + cap;                            // compacted candidates of the batch selection
+    int* open = cand + cap;                             // open leaves that can be split (unordered list)
+    int* commit = open + cap;                           // nodes committed in this call, in order
     __shared__ int s_tmp[16];
-    __shared__ int s_done, s_ncand, s_nopen;
+    __shared__ int s_done, s_ncand, s_nopen, s_ncommit, s_commits0, s_leaves0;
+    __shared__ unsigned long long s_units;
     const int tid = threadIdx.x;
-    if (tid == 0) { s_done = 0; s_ncand = 0; s_nopen = 0; }
+    if (tid == 0) { s_done = 0; s_ncand = 0; s_nopen = 0; s_ncommit = 0; s_units = 0ull; }
     __syncthreads();
     for (int i = tid; i < n_nodes0; i += blockDim.x) {
         const Node* nd = &nodes[i];
-        const int st = nd->state, ft = nd->best.feature;
-        const double kg = (st == 1 && ft >= 0) ? nd->best.gain : -1.0;
+        const double kg = (nd->best.feature >= 0) ? nd->best.gain : -1.0;
         key[i] = kg;
         lid[i] = nd->leaf_id;
-        expd[i] = (unsigned char)nd->expanded;
-        if (kg > 0.0) open[atomicAdd(&s_nopen, 1)] = i;
+        child[i] = nd->expanded ? nd->child : -1;
+        if (nd->state == 1 && kg > 0.0) open[atomicAdd(&s_nopen, 1)] = i;
     }
     __syncthreads();
 
-    if (tid < 64) {  // replay of the best-first order, one wavefront
-        int n_commits = step->n_commits, n_leaves = step->n_leaves, n_open = s_nopen;
-        int64_t units = step->hist_units;
+    if (tid < 64) {  // replay of the best-first order, one wavefront, LDS only
+        const int commits0 = step->n_commits, leaves0 = step->n_leaves;
+        int n_commits = commits0, n_leaves = leaves0, n_open = s_nopen;
         for (;;) {
             if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
             double bg = 0.0;
@@ -136,45 +139,45 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
                 if (oi >= 0 && (bi < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bi = oi; bl = ol; bp = op; }
             }
             if (bi < 0) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
-            if (!expd[bi]) break;                              // the next split is not known yet
-            // commit split number n_commits: node bi, leaf id bl
-            int add0 = 0, add1 = 0, c0 = 0;
+            const int c0 = child[bi];
+            if (c0 < 0) break;                                 // the next split is not known yet
+            // commit: the node leaves the queue, its children enter (left keeps the leaf id)
+            const int add0 = key[c0] > 0.0, add1 = key[c0 + 1] > 0.0;
             if (tid == 0) {
-                const Node nd = nodes[bi];
-                const int k = n_commits;
-                out.t.split_leaf[k] = bl; out.t.split_feature[k] = nd.best.feature; out.t.split_bin[k] = nd.best.bin;
-                out.t.split_gain[k] = nd.best.gain;
-                out.t.split_stats[4 * k + 0] = nd.best.left_g; out.t.split_stats[4 * k + 1] = nd.best.left_h;
-                out.t.split_stats[4 * k + 2] = nd.best.right_g; out.t.split_stats[4 * k + 3] = nd.best.right_h;
-                out.t.split_n_left[k] = nd.n_left;
-                const int64_t nl = nd.n_left, nr = nd.count - nd.n_left;
-                units += (nl <= nr ? nl : nr) * (int64_t)F;
-                nodes[bi].state = 2;
-                c0 = nd.child;
-                const int c1 = c0 + 1;
-                nodes[c0].state = 1; nodes[c0].leaf_id = bl;
-                nodes[c1].state = 1; nodes[c1].leaf_id = n_leaves;
-                const qgbdt_split b0 = nodes[c0].best, b1 = nodes[c1].best;
-                key[bi] = -1.0;
-                key[c0] = (b0.feature >= 0) ? b0.gain : -1.0; lid[c0] = bl;
-                key[c1] = (b1.feature >= 0) ? b1.gain : -1.0; lid[c1] = n_leaves;
-                add0 = key[c0] > 0.0; add1 = key[c1] > 0.0;
-                // open list: the committed node leaves, its splittable children enter
+                commit[n_commits - commits0] = bi;
+                lid[c0] = bl; lid[c0 + 1] = n_leaves;
                 open[bp] = open[n_open - 1];
                 int no = n_open - 1;
                 if (add0) open[no++] = c0;
-                if (add1) open[no++] = c1;
+                if (add1) open[no++] = c0 + 1;
             }
-            add0 = __shfl(add0, 0); add1 = __shfl(add1, 0);
             n_open += add0 + add1 - 1;
             n_commits += 1; n_leaves += 1;
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         }
         if (tid == 0) {
-            step->n_commits = n_commits; step->n_leaves = n_leaves; step->hist_units = units;
-            s_nopen = n_open;
+            s_ncommit = n_commits - commits0; s_commits0 = commits0; s_leaves0 = leaves0; s_nopen = n_open;
+            step->n_commits = n_commits; step->n_leaves = n_leaves;
         }
     }
+    __syncthreads();
+    // outputs and node states of the splits committed above
+    for (int c = tid; c < s_ncommit; c += blockDim.x) {
+        const int i = commit[c], k = s_commits0 + c;
+        const Node nd = nodes[i];
+        out.t.split_leaf[k] = lid[i]; out.t.split_feature[k] = nd.best.feature; out.t.split_bin[k] = nd.best.bin;
+        out.t.split_gain[k] = nd.best.gain;
+        out.t.split_stats[4 * k + 0] = nd.best.left_g; out.t.split_stats[4 * k + 1] = nd.best.left_h;
+        out.t.split_stats[4 * k + 2] = nd.best.right_g; out.t.split_stats[4 * k + 3] = nd.best.right_h;
+        out.t.split_n_left[k] = nd.n_left;
+        const int64_t nl = nd.n_left, nr = nd.count - nd.n_left;
+        atomicAdd(&s_units, (unsigned long long)((nl <= nr ? nl : nr) * (int64_t)F));
+        nodes[nd.child].state = 1; nodes[nd.child].leaf_id = lid[nd.child];
+        nodes[nd.child + 1].state = 1; nodes[nd.child + 1].leaf_id = lid[nd.child + 1];
+    }
+    __syncthreads();  // a child may itself have been committed in this call: "internal" is written last
+    for (int c = tid; c < s_ncommit; c += blockDim.x) nodes[commit[c]].state = 2;
+    if (tid == 0) step->hist_units += (int64_t)s_units;
     __syncthreads();
     if (s_done) {
         if (tid == 0) {
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     if (want > batch_max) want = batch_max;
     for (int p = tid; p < s_nopen; p += blockDim.x) {
         const int i = open[p];
-        if (!expd[i]) cand[atomicAdd(&s_ncand, 1)] = i;
+        if (child[i] < 0) cand[atomicAdd(&s_ncand, 1)] = i;
     }
     __syncthreads();
     const int nc = s_ncand;
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
     if (tid == (int)blockDim.x - 1) seg_prefix[n_items] = incl;
     __syncthreads();
     __threadfence_block();
-    int groups = 0;
+    int groups = 0, small_rows = 0;
     Node L, R;
     int small_is_left = 1;
     if (tid < n_batch) {
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
         const int64_t nr = P.count - nl;
         nodes[be.node].n_left = nl;
         small_is_left = (nl <= nr) ? 1 : 0;
-        const int cb = 1 - P.buf;
+        const int cb = (P.buf == 1) ? 0 : 1;  // children of buffer 1 live in buffer 0, all others in buffer 1
         L.begin = P.begin; L.count = nl; L.sum_g = P.best.left_g; L.sum_h = P.best.left_h; L.n_left = 0; L.buf = cb;
         R.begin = P.begin + nl; R.count = nr; R.sum_g = P.best.right_g; R.sum_h = P.best.right_h; R.n_left = 0; R.buf = cb;
         L.slot = small_is_left ? be.new_slot : P.slot;
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
         L.state = 0; L.expanded = 0; L.child = -1; L.leaf_id = -1; clear_split(L.best);
         R.state = 0; R.expanded = 0; R.child = -1; R.leaf_id = -1; clear_split(R.best);
         nodes[P.child] = L; nodes[P.child + 1] = R;
-        groups = hist_groups(small_is_left ? nl : nr, min_rows, max_groups);
+        small_rows = (int)(small_is_left ? nl : nr);
         for (int c = 0; c < 2; ++c) {
             const Node& C = c ? R : L;
             const bool is_small = (c == 0) == (small_is_left == 1);
@@ -289,6 +292,17 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
             it.out = &nodes[P.child + c].best;
             items[2 * tid + c] = it;
         }
+    }
+    // row groups of the histogram builds: about max_groups items in total, shared out by size
+    const int total_small = block_scan_incl(small_rows, s_tmp);
+    __shared__ int s_total;
+    if (tid == (int)blockDim.x - 1) s_total = total_small;
+    __syncthreads();
+    if (tid < n_batch) {
+        int target = (s_total + max_groups - 1) / max_groups;
+        if (target < min_rows) target = min_rows;
+        groups = (small_rows + target - 1) / target;
+        if (groups < 1) groups = 1;
     }
     const int gincl = block_scan_incl(groups, s_tmp);
     if (tid < n_batch) {
@@ -337,7 +351,7 @@ __global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* 
     const int l = blockIdx.y;
     if (l >= step->n_leaves) return;
     const Node S = nodes[leaf_node[l]];
-    const int32_t* src = S.buf ? idx1 : idx0;
+    const int32_t* src = (S.buf == 1) ? idx1 : idx0;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < S.count; j += (int64_t)gridDim.x * blockDim.x)
         out[S.begin + j] = src[S.begin + j];
 }
@@ -365,13 +379,21 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                              (long long)tot[1], (long long)tot[2]);
     }
     const HistPlan plan = make_hist_plan(ctx->shape, p->bits_g, p->bits_h, p->acc_width);
+    // Row sources: buffer 2 = the caller's matrix and the quantized gradients in original order;
+    // in ordered mode buffers 0/1 are the leaf-ordered copies that the partition writes.
+    RowSource rows;
+    rows.bins[0] = ctx->obins[0]; rows.bins[1] = ctx->obins[1]; rows.bins[2] = bins;
+    rows.gh[0] = ctx->ogh[0]; rows.gh[1] = ctx->ogh[1]; rows.gh[2] = ctx->gh;
+    const bool ordered = ctx->ordered != 0;
+    const int root_buf = ordered ? 2 : 0;
+    if (!ordered) { rows.bins[0] = rows.bins[1] = bins; rows.gh[0] = rows.gh[1] = ctx->gh; }
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
-                       ctx->nodes, ctx->qtotals, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
+                       ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                        ctx->scan_counters, ctx->hist_pool, W, plan.min_rows_per_group, plan.max_groups);
-    rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], false, ((uintptr_t)bins & 15) == 0,
+    rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
                      (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
     if (rc != QGBDT_OK) return rc;
@@ -379,7 +401,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 3 * sizeof(int) + 1) + 64;
+    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 5 * sizeof(int)) + 64;
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
@@ -388,14 +410,14 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                                ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
                                ctx->max_expand, out);
-            rc = launch_batch_partition_count(ctx, bins);
+            rc = launch_batch_partition_count(ctx, rows);
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                                ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                                plan.min_rows_per_group, plan.max_groups);
-            rc = launch_batch_partition_scatter(ctx);
+            rc = launch_batch_partition_scatter(ctx, rows);
             if (rc != QGBDT_OK) return rc;
-            rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], true, false, ctx->hist_entries,
+            rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], !ordered, ordered, ctx->hist_entries,
                              ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
             if (rc != QGBDT_OK) return rc;
             rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
@@ -413,14 +435,14 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         if (ctx->host_state->done) break;
         if (launched > round_cap) return set_error(ctx, QGBDT_E_HIP, "tree growth did not finish in %d rounds", launched);
         // the trailing plan has already chosen a batch: finish that round, then continue
-        rc = launch_batch_partition_count(ctx, bins);
+        rc = launch_batch_partition_count(ctx, rows);
         if (rc != QGBDT_OK) return rc;
         hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                            ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                            plan.min_rows_per_group, plan.max_groups);
-        rc = launch_batch_partition_scatter(ctx);
+        rc = launch_batch_partition_scatter(ctx, rows);
         if (rc != QGBDT_OK) return rc;
-        rc = launch_hist(ctx, plan, bins, ctx->gh, ctx->idx[0], ctx->idx[1], true, false, ctx->hist_entries,
+        rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], !ordered, ordered, ctx->hist_entries,
                          ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
         if (rc != QGBDT_OK) return rc;
         rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
