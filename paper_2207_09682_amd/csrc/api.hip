@@ -50,7 +50,8 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 }
 
 static void free_all(qgbdt_ctx* c) {
-    void* ptrs[] = {c->obins[0], c->obins[1], c->ogh[0], c->ogh[1], c->idx[0], c->idx[1], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+    void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
+                    c->idx[2], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -98,7 +99,7 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     const int64_t W = (int64_t)shape->n_features * shape->n_bins;
     const int L = shape->max_leaves;
     c->batch_max = L;
-    c->max_expand = 2 * L;
+    c->max_expand = 3 * L;
     c->max_nodes = 2 * c->max_expand + 1;
     c->max_seg = (int)(N / PART_SEG) + c->batch_max + 2;
     c->rounds_hint = 10;
@@ -106,13 +107,14 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     // narrow rows: moving a row costs less than gathering it twice per level
     c->ordered = (shape->n_features % 4 == 0 && shape->n_features >= 16 && shape->n_features <= 64) ? 1 : 0;
     if (c->ordered) {
-        for (int b = 0; b < 2 && rc == QGBDT_OK; ++b) {
+        for (int b = 0; b < 3 && rc == QGBDT_OK; ++b) {
             rc = ws_alloc(c, &c->obins[b], (size_t)N * shape->n_features);
             if (rc == QGBDT_OK) rc = ws_alloc(c, &c->ogh[b], (size_t)N);
         }
     }
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[2], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (c->max_expand + 1)));
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->flags, (size_t)N);
@@ -216,9 +218,9 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
     RowSource rows;
-    rows.bins[0] = rows.bins[1] = rows.bins[2] = (const uint8_t*)bins;
-    rows.gh[0] = rows.gh[1] = rows.gh[2] = gh;
-    return launch_hist(ctx, plan, rows, row_idx, row_idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
+    IdxSet idx;
+    for (int b = 0; b < 4; ++b) { rows.bins[b] = (const uint8_t*)bins; rows.gh[b] = gh; idx.p[b] = const_cast<int32_t*>(row_idx); }
+    return launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
                        ctx->hist_entries, ctx->hist_counts, hist_out,
                        (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
 }
@@ -319,6 +321,11 @@ int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4) {
     out4[0] = ctx->host_state->rounds; out4[1] = ctx->host_state->n_expanded;
     out4[2] = ctx->host_state->n_commits; out4[3] = ctx->host_state->n_nodes;
     return QGBDT_OK;
+}
+
+__attribute__((visibility("default"))) int qgbdt_debug_rounds(const qgbdt_ctx* ctx, int64_t* rows96, int32_t* batch96) {
+    for (int i = 0; i < 96; ++i) { rows96[i] = ctx->host_state->round_rows[i]; batch96[i] = ctx->host_state->round_batch[i]; }
+    return 0;
 }
 
 }  // extern "C"

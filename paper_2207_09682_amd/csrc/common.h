@@ -41,6 +41,8 @@ struct StepState {
     int64_t prof_rows_contig, prof_rows_idx;  // rows seen by histogram launches
     int64_t prof_launches;                    // histogram launches that had rows
     int64_t prof_builds;                      // histogram builds served by those launches
+    int64_t round_rows[96];                   // rows partitioned per round (diagnostics)
+    int32_t round_batch[96];                  // nodes expanded per round (diagnostics)
 };
 
 // One node expanded in the current round.
@@ -96,13 +98,25 @@ struct HistPlan {
 
 struct ScanItem;
 
-// Where the rows of a slice live.  Buffer 2 is the caller's data in original row order (bin
-// matrix, quantized gradients); buffers 0 and 1 are the library's leaf-ordered copies, which
-// exist only in ordered mode (narrow rows).  Row ids of buffers 0 and 2 share one array.
+// Where the rows of a slice live.  Buffers 0..2 rotate with the depth of a node (the children
+// of buffer b live in buffer (b+1)%3, so a node's rows survive until its grandchildren are
+// expanded); buffer 3 is the caller's data in original row order (bin matrix, quantized
+// gradients), where the root lives in ordered mode.  Row ids of buffer 3 use array 0.
+// In ordered mode (narrow rows) buffers 0..2 hold leaf-ordered copies of the bin rows and
+// packed gradients; otherwise all four entries point at the original arrays.
+constexpr int BUF_ORIGINAL = 3;
 struct RowSource {
-    const uint8_t* bins[3];
-    const int16_t* gh[3];
+    const uint8_t* bins[4];
+    const int16_t* gh[4];
 };
+struct RowDest {
+    uint8_t* bins[3];
+    int16_t* gh[3];
+};
+struct IdxSet {
+    int32_t* p[4];  // p[3] == p[0]
+};
+__host__ __device__ inline int child_buffer(int buf) { return buf == BUF_ORIGINAL ? 1 : (buf + 1) % 3; }
 
 }  // namespace qgbdt
 
@@ -119,9 +133,9 @@ struct qgbdt_ctx {
     int rounds_hint;
     // workspace
     int ordered;           // narrow rows: children get physically leaf-ordered copies of their rows
-    uint8_t* obins[2];     // [N][F] each (ordered mode)
-    int16_t* ogh[2];       // [N] each (ordered mode)
-    int32_t* idx[2];       // [N] each
+    uint8_t* obins[3];     // [N][F] each (ordered mode)
+    int16_t* ogh[3];       // [N] each (ordered mode)
+    int32_t* idx[3];       // [N] each
     int16_t* gh;           // [N]
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
     uint8_t* flags;        // [N] partition flags
@@ -174,8 +188,8 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const int32_t* idx0, const int32_t* idx1,
-                bool use_idx, bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,
+                bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
                 int64_t grid_items, StepState* step);
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);

@@ -113,8 +113,7 @@ __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_
 // cost ~5 VALU instructions: one bit-field extract and one 24-bit multiply-add
 // into the byte address of its LDS word, plus its share of the per-row work.
 template <int W, bool IDX, int U>
-__global__ __launch_bounds__(1024) void hist_kernel(RowSource src, const int32_t* __restrict__ idx0,
-                                                    const int32_t* __restrict__ idx1,
+__global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
                                                     int F, int nb, HistPlan plan, StepState* step) {
@@ -157,9 +156,9 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, const int32_t
         if (gbegin >= en.count) continue;
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        const int32_t* idx = IDX ? ((en.buf == 1 ? idx1 : idx0) + en.begin) : nullptr;
+        const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
-        const int sb = IDX ? 2 : en.buf;
+        const int sb = IDX ? BUF_ORIGINAL : en.buf;
         const uint8_t* colbase = src.bins[sb] + f0 + 4 * q;
         const int16_t* gh = src.gh[sb];
 
@@ -367,8 +366,7 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
 
 // Any feature count (no alignment assumption): one byte load per (row, feature).
 template <int W>
-__global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, const int32_t* __restrict__ idx0,
-                                                            const int32_t* __restrict__ idx1, int use_idx,
+__global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSet idxs, int use_idx,
                                                             const HistEntry* __restrict__ entries,
                                                             const int32_t* __restrict__ table_counts,
                                                             int64_t* hist_base, int F, int nb, HistPlan plan,
@@ -391,9 +389,9 @@ __global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, const
         if (gbegin >= en.count) continue;
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        const int32_t* idx = use_idx ? ((en.buf == 1 ? idx1 : idx0) + en.begin) : nullptr;
-        const uint8_t* bins = src.bins[use_idx ? 2 : en.buf];
-        const int16_t* gh = src.gh[use_idx ? 2 : en.buf];
+        const int32_t* idx = use_idx ? (idxs.p[en.buf] + en.begin) : nullptr;
+        const uint8_t* bins = src.bins[use_idx ? BUF_ORIGINAL : en.buf];
+        const int16_t* gh = src.gh[use_idx ? BUF_ORIGINAL : en.buf];
         for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             __syncthreads();
@@ -499,7 +497,7 @@ __global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64
         if (g > max_groups) g = max_groups;
         if (g < 1) g = 1;
         HistEntry e;
-        e.begin = begin; e.count = count; e.buf = 2; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
+        e.begin = begin; e.count = count; e.buf = BUF_ORIGINAL; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
         entries[0] = e;
         counts[0] = 1;
         counts[1] = count > 0 ? (int32_t)g : 0;
@@ -515,8 +513,8 @@ int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, i
 
 // Launches the kernel variant for (plan, row source).  `grid_items` is the host's upper bound on
 // the number of work items; workgroups beyond the table's item count return at once.
-int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const int32_t* idx0, const int32_t* idx1,
-                bool use_idx, bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
+int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,
+                bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
                 int64_t grid_items, StepState* step) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int64_t groups = grid_items;
@@ -548,7 +546,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
 #define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                              \
-    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1, \
+    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
                        entries, table_counts, hist_base, F, nb, plan, step)
 #define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
     switch (U) {                                                                        \
@@ -566,10 +564,10 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
 #undef QG_LAUNCH_HIST_U
 #undef QG_LAUNCH_HIST
     } else if (plan.acc_width == 16) {
-        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1,
+        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
                            use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     } else {
-        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, rows, idx0, idx1,
+        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
                            use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
     }
     QG_HIP(ctx, hipGetLastError());

@@ -171,9 +171,7 @@ __device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, 
 // that this round's builds accumulate into are cleared.  In ordered mode the rows of a
 // node are physically contiguous in its buffer and the bin is read at the row's position;
 // otherwise it is gathered from the original matrix through the row id.
-__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int F,
-                                                               const int32_t* __restrict__ buf0,
-                                                               const int32_t* __restrict__ buf1,
+__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int F, IdxSet idxs,
                                                                const StepState* __restrict__ step,
                                                                const BatchEntry* __restrict__ batch,
                                                                const Node* __restrict__ nodes,
@@ -193,8 +191,8 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, i
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
-        const int32_t* src = (nd.buf == 1 ? buf1 : buf0) + nd.begin;
-        const uint8_t* brow = rows.bins[ordered ? nd.buf : 2] + (ordered ? nd.begin * (int64_t)F : 0);
+        const int32_t* src = idxs.p[nd.buf] + nd.begin;
+        const uint8_t* brow = rows.bins[ordered ? nd.buf : BUF_ORIGINAL] + (ordered ? nd.begin * (int64_t)F : 0);
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int feature = nd.best.feature, bin = nd.best.bin;
@@ -219,11 +217,8 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, i
 // contiguous again (rows are copied as dwords by the whole workgroup, coalesced on the
 // reading side and in two compacted streams on the writing side).
 template <bool ORDERED>
-__global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows, uint8_t* obins0, uint8_t* obins1,
-                                                                 int16_t* ogh0, int16_t* ogh1, int F,
-                                                                 const int32_t* __restrict__ buf0r,
-                                                                 const int32_t* __restrict__ buf1r, int32_t* buf0w,
-                                                                 int32_t* buf1w, const StepState* __restrict__ step,
+__global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows, RowDest out, int F, IdxSet idxs,
+                                                                 const StepState* __restrict__ step,
                                                                  const BatchEntry* __restrict__ batch,
                                                                  const Node* __restrict__ nodes,
                                                                  const uint8_t* __restrict__ flags,
@@ -237,13 +232,13 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
-        const bool to0 = nd.buf == 1;  // children of buffer 1 go to buffer 0, all others to buffer 1
-        const int32_t* src = (nd.buf == 1 ? buf1r : buf0r) + nd.begin;
-        int32_t* dst = (to0 ? buf0w : buf1w) + nd.begin;
+        const int cbuf = child_buffer(nd.buf);
+        const int32_t* src = idxs.p[nd.buf] + nd.begin;
+        int32_t* dst = idxs.p[cbuf] + nd.begin;
         const int16_t* gsrc = ORDERED ? rows.gh[nd.buf] + nd.begin : nullptr;
-        int16_t* gdst = ORDERED ? (to0 ? ogh0 : ogh1) + nd.begin : nullptr;
+        int16_t* gdst = ORDERED ? out.gh[cbuf] + nd.begin : nullptr;
         const uint8_t* bsrc = ORDERED ? rows.bins[nd.buf] + nd.begin * (int64_t)F : nullptr;
-        uint8_t* bdst = ORDERED ? (to0 ? obins0 : obins1) + nd.begin * (int64_t)F : nullptr;
+        uint8_t* bdst = ORDERED ? out.bins[cbuf] + nd.begin * (int64_t)F : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int64_t before = seg_prefix[item] - seg_prefix[be.seg_start];  // left rows in earlier segments
@@ -309,25 +304,31 @@ static int batch_part_grid(const qgbdt_ctx* ctx) {
     return (int)g;
 }
 
+static IdxSet idx_set(const qgbdt_ctx* ctx) {
+    IdxSet s;
+    s.p[0] = ctx->idx[0]; s.p[1] = ctx->idx[1]; s.p[2] = ctx->idx[2]; s.p[3] = ctx->idx[0];
+    return s;
+}
+
 int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows) {
     const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
     hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                       ctx->ordered, ctx->shape.n_features, ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes,
-                       ctx->flags, ctx->seg_counts, ctx->hist_pool, W);
+                       ctx->ordered, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                       ctx->seg_counts, ctx->hist_pool, W);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows) {
+    RowDest out;
+    for (int b = 0; b < 3; ++b) { out.bins[b] = ctx->obins[b]; out.gh[b] = ctx->ogh[b]; }
     if (ctx->ordered)
         hipLaunchKernelGGL(batch_part_scatter_kernel<true>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                           ctx->obins[0], ctx->obins[1], ctx->ogh[0], ctx->ogh[1], ctx->shape.n_features, ctx->idx[0],
-                           ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                           out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
                            ctx->seg_prefix);
     else
         hipLaunchKernelGGL(batch_part_scatter_kernel<false>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                           ctx->obins[0], ctx->obins[1], ctx->ogh[0], ctx->ogh[1], ctx->shape.n_features, ctx->idx[0],
-                           ctx->idx[1], ctx->idx[0], ctx->idx[1], ctx->step, ctx->batch, ctx->nodes, ctx->flags,
+                           out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
                            ctx->seg_prefix);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;

@@ -97,13 +97,13 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     if (step->done) return;
     extern __shared__ unsigned char plan_lds[];
     const int n_nodes0 = step->n_nodes;
-    const int cap = 2 * max_expand + 1;
+    const int cap = 2 * max_expand + 1;                 // nodes
     double* key = reinterpret_cast<double*>(plan_lds);  // gain of the node's best split, -1 if it has none
     int* lid = reinterpret_cast<int*>(key + cap);       // leaf id (open leaves)
     int* child = lid + cap;                             // left child, -1 if not expanded
-    int* cand = child + cap;                            // compacted candidates of the batch selection
-    int* open = cand + cap;                             // open leaves that can be split (unordered list)
-    int* commit = open + cap;                           // nodes committed in this call, in order
+    int* open = child + cap;                            // [num_leaves] open leaves that can be split (unordered list)
+    int* commit = open + num_leaves + 1;                // [num_leaves] nodes committed in this call, in order
+    int* cand = commit + num_leaves + 1;                // [3*num_leaves] candidates of the batch selection
     __shared__ int s_tmp[16];
     __shared__ int s_done, s_ncand, s_nopen, s_ncommit, s_commits0, s_leaves0;
     __shared__ unsigned long long s_units;
@@ -194,21 +194,33 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     int want = 1 + (spare > 0 ? spare : 0);
     if (want > remaining) want = remaining;
     if (want > batch_max) want = batch_max;
+    // Candidates: open leaves that are not expanded yet (class 0: the leaf the replay stopped at is
+    // the best of them) and, one level ahead, the not yet expanded children of expanded open leaves
+    // (class 1; encoded as -1-node).  A node's rows outlive the expansion of its children, so
+    // expanding the children of a leaf whose split is not committed yet is safe.
     for (int p = tid; p < s_nopen; p += blockDim.x) {
         const int i = open[p];
-        if (child[i] < 0) cand[atomicAdd(&s_ncand, 1)] = i;
+        const int c0 = child[i];
+        if (c0 < 0) {
+            cand[atomicAdd(&s_ncand, 1)] = i;
+        } else {
+            if (key[c0] > 0.0 && child[c0] < 0) cand[atomicAdd(&s_ncand, 1)] = -1 - c0;
+            if (key[c0 + 1] > 0.0 && child[c0 + 1] < 0) cand[atomicAdd(&s_ncand, 1)] = -1 - (c0 + 1);
+        }
     }
     __syncthreads();
     const int nc = s_ncand;
     const int n_batch = nc < want ? nc : want;
     for (int c = tid; c < nc; c += blockDim.x) {
-        const int i = cand[c];
+        const int e = cand[c];
+        const int cls = e < 0, i = e < 0 ? -1 - e : e;
         const double g = key[i];
-        const int l = lid[i];
         int rank = 0;
         for (int j = 0; j < nc; ++j) {
-            const int o = cand[j];
-            rank += (key[o] > g || (key[o] == g && lid[o] < l)) ? 1 : 0;
+            const int eo = cand[j];
+            const int co = eo < 0, o = eo < 0 ? -1 - eo : eo;
+            const double go = key[o];
+            rank += (co < cls || (co == cls && (go > g || (go == g && o < i)))) ? 1 : 0;
         }
         if (rank < n_batch) batch[rank].node = i;
     }
@@ -229,6 +241,12 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         scan_counters[2 * tid] = 0; scan_counters[2 * tid + 1] = 0;
     }
     if (tid == n_batch - 1) step->n_part_items = incl;
+    {   // diagnostics: rows partitioned in this round
+        int rows_k = 0;
+        if (tid < n_batch) rows_k = (int)((nodes[batch[tid].node].count + 1023) >> 10);
+        const int tot = block_scan_incl(rows_k, s_tmp);
+        if (tid == (int)blockDim.x - 1 && step->rounds < 96) { step->round_rows[step->rounds] = (int64_t)tot << 10; step->round_batch[step->rounds] = n_batch; }
+    }
     __syncthreads();
     if (tid == 0) {
         step->n_batch = n_batch;
@@ -271,7 +289,7 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
         const int64_t nr = P.count - nl;
         nodes[be.node].n_left = nl;
         small_is_left = (nl <= nr) ? 1 : 0;
-        const int cb = (P.buf == 1) ? 0 : 1;  // children of buffer 1 live in buffer 0, all others in buffer 1
+        const int cb = child_buffer(P.buf);
         L.begin = P.begin; L.count = nl; L.sum_g = P.best.left_g; L.sum_h = P.best.left_h; L.n_left = 0; L.buf = cb;
         R.begin = P.begin + nl; R.count = nr; R.sum_g = P.best.right_g; R.sum_h = P.best.right_h; R.n_left = 0; R.buf = cb;
         L.slot = small_is_left ? be.new_slot : P.slot;
@@ -345,13 +363,11 @@ __global__ __launch_bounds__(256) void tree_finalize_kernel(const StepState* ste
 // Copies every leaf's slice from the index buffer it ended up in to the output.
 __global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* step, const Node* nodes,
                                                                const int32_t* __restrict__ leaf_node,
-                                                               const int32_t* __restrict__ idx0,
-                                                               const int32_t* __restrict__ idx1,
-                                                               int32_t* __restrict__ out) {
+                                                               IdxSet idxs, int32_t* __restrict__ out) {
     const int l = blockIdx.y;
     if (l >= step->n_leaves) return;
     const Node S = nodes[leaf_node[l]];
-    const int32_t* src = (S.buf == 1) ? idx1 : idx0;
+    const int32_t* src = idxs.p[S.buf];
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < S.count; j += (int64_t)gridDim.x * blockDim.x)
         out[S.begin + j] = src[S.begin + j];
 }
@@ -382,18 +398,22 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // Row sources: buffer 2 = the caller's matrix and the quantized gradients in original order;
     // in ordered mode buffers 0/1 are the leaf-ordered copies that the partition writes.
     RowSource rows;
-    rows.bins[0] = ctx->obins[0]; rows.bins[1] = ctx->obins[1]; rows.bins[2] = bins;
-    rows.gh[0] = ctx->ogh[0]; rows.gh[1] = ctx->ogh[1]; rows.gh[2] = ctx->gh;
+    IdxSet idxs;
     const bool ordered = ctx->ordered != 0;
-    const int root_buf = ordered ? 2 : 0;
-    if (!ordered) { rows.bins[0] = rows.bins[1] = bins; rows.gh[0] = rows.gh[1] = ctx->gh; }
+    for (int b = 0; b < 3; ++b) {
+        rows.bins[b] = ordered ? ctx->obins[b] : bins;
+        rows.gh[b] = ordered ? ctx->ogh[b] : ctx->gh;
+        idxs.p[b] = ctx->idx[b];
+    }
+    rows.bins[BUF_ORIGINAL] = bins; rows.gh[BUF_ORIGINAL] = ctx->gh; idxs.p[BUF_ORIGINAL] = ctx->idx[0];
+    const int root_buf = ordered ? BUF_ORIGINAL : 0;
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                        ctx->scan_counters, ctx->hist_pool, W, plan.min_rows_per_group, plan.max_groups);
-    rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], false, ((uintptr_t)bins & 15) == 0,
+    rc = launch_hist(ctx, plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
                      (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
     if (rc != QGBDT_OK) return rc;
@@ -401,7 +421,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 5 * sizeof(int)) + 64;
+    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int)) +
+                            (size_t)(5 * p->num_leaves + 8) * sizeof(int) + 64;
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
@@ -417,7 +438,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                                plan.min_rows_per_group, plan.max_groups);
             rc = launch_batch_partition_scatter(ctx, rows);
             if (rc != QGBDT_OK) return rc;
-            rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], !ordered, ordered, ctx->hist_entries,
+            rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
                              ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
             if (rc != QGBDT_OK) return rc;
             rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
@@ -442,7 +463,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            plan.min_rows_per_group, plan.max_groups);
         rc = launch_batch_partition_scatter(ctx, rows);
         if (rc != QGBDT_OK) return rc;
-        rc = launch_hist(ctx, plan, rows, ctx->idx[0], ctx->idx[1], !ordered, ordered, ctx->hist_entries,
+        rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
                          ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
         if (rc != QGBDT_OK) return rc;
         rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
@@ -459,7 +480,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (gx < 1) gx = 1;
     if (gx > 64) gx = 64;
     hipLaunchKernelGGL(tree_gather_rows_kernel, dim3(gx, ctx->shape.max_leaves), dim3(256), 0, ctx->stream, ctx->step,
-                       ctx->nodes, ctx->leaf_node, ctx->idx[0], ctx->idx[1], row_idx_out);
+                       ctx->nodes, ctx->leaf_node, idxs, row_idx_out);
     QG_HIP(ctx, hipGetLastError());
     return launch_refit(ctx, g, h, row_idx_out, out.t.leaf_begin, out.t.leaf_count, ctx->shape.max_leaves,
                         out.t.n_leaves, out.t.leaf_value);
