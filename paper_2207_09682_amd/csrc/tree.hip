@@ -112,7 +112,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     __syncthreads();
     for (int i = tid; i < n_nodes0; i += blockDim.x) {
         const Node* nd = &nodes[i];
-        const double kg = (nd->best.feature >= 0) ? nd->best.gain : -1.0;
+        const double kg = (nd->best.feature >= 0 && nd->state != 2) ? nd->best.gain : -1.0;
         key[i] = kg;
         lid[i] = nd->leaf_id;
         child[i] = nd->expanded ? nd->child : -1;
@@ -145,6 +145,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
             const int add0 = key[c0] > 0.0, add1 = key[c0 + 1] > 0.0;
             if (tid == 0) {
                 commit[n_commits - commits0] = bi;
+                key[bi] = -1.0;
                 lid[c0] = bl; lid[c0 + 1] = n_leaves;
                 open[bp] = open[n_open - 1];
                 int no = n_open - 1;
@@ -210,19 +211,56 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     }
     __syncthreads();
     const int nc = s_ncand;
-    const int n_batch = nc < want ? nc : want;
+    // Rank of every candidate's gain among all nodes that may still be committed (every known,
+    // not committed node with a gain > 0; ties by node id).  A candidate that already has
+    // `remaining` better nodes in front of it is not worth expanding yet.  Four threads share
+    // one candidate's pass over the nodes.
+    int* crank = cand + 3 * num_leaves;  // [3*num_leaves]
+    for (int c = tid; c < nc; c += blockDim.x) crank[c] = 0;
+    __syncthreads();
+    for (int w = tid; w < 4 * nc; w += blockDim.x) {
+        const int c = w >> 2, part = w & 3;
+        const int e = cand[c];
+        const int i = e < 0 ? -1 - e : e;
+        const double g = key[i];
+        int r = 0;
+        for (int j = part; j < n_nodes0; j += 4) {
+            const double go = key[j];
+            r += (go > g || (go == g && j < i)) ? 1 : 0;
+        }
+        atomicAdd(&crank[c], r);
+    }
+    __syncthreads();
+    // order of the batch: class 0 first, then class 1, each by rank; the best class-0 candidate
+    // (the leaf the replay stopped at) always passes the filter
+    int* posbuf = crank + 3 * num_leaves;  // [3*num_leaves + 2] node per position, -1 = filtered out
     for (int c = tid; c < nc; c += blockDim.x) {
         const int e = cand[c];
-        const int cls = e < 0, i = e < 0 ? -1 - e : e;
-        const double g = key[i];
-        int rank = 0;
+        const int cls = e < 0 ? 1 : 0;
+        const int rk = crank[c];
+        int pos = 0, better0 = 0;
         for (int j = 0; j < nc; ++j) {
-            const int eo = cand[j];
-            const int co = eo < 0, o = eo < 0 ? -1 - eo : eo;
-            const double go = key[o];
-            rank += (co < cls || (co == cls && (go > g || (go == g && o < i)))) ? 1 : 0;
+            const int cj = cand[j] < 0 ? 1 : 0, rj = crank[j];
+            pos += ((cj < cls) || (cj == cls && rj < rk)) ? 1 : 0;
+            better0 += (cj == 0 && rj < rk) ? 1 : 0;
         }
-        if (rank < n_batch) batch[rank].node = i;
+        const bool pass = (cls == 0 && better0 == 0) || rk < remaining;
+        posbuf[pos] = pass ? (e < 0 ? -1 - e : e) : -1;
+    }
+    __syncthreads();
+    // compaction of the passing candidates in position order (two positions per thread)
+    const int p0 = 2 * tid, p1 = 2 * tid + 1;
+    const int f0 = (p0 < nc && posbuf[p0] >= 0) ? 1 : 0, f1 = (p1 < nc && posbuf[p1] >= 0) ? 1 : 0;
+    const int pincl = block_scan_incl(f0 + f1, s_tmp);
+    __shared__ int s_npass;
+    if (tid == (int)blockDim.x - 1) s_npass = pincl;
+    __syncthreads();
+    const int n_pass = s_npass;
+    const int n_batch = n_pass < want ? n_pass : want;
+    {
+        int o = pincl - (f0 + f1);
+        if (f0) { if (o < n_batch) batch[o].node = posbuf[p0]; ++o; }
+        if (f1) { if (o < n_batch) batch[o].node = posbuf[p1]; }
     }
     __syncthreads();
     __threadfence_block();
@@ -422,7 +460,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (rc != QGBDT_OK) return rc;
 
     const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int)) +
-                            (size_t)(5 * p->num_leaves + 8) * sizeof(int) + 64;
+                            (size_t)(11 * p->num_leaves + 16) * sizeof(int) + 64;
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
