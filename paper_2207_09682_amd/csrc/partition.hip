@@ -211,11 +211,12 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, i
     }
 }
 
-// Order-preserving scatter of every segment into the other buffer; seg_prefix is the
-// exclusive prefix of seg_counts over all segments of the round.  ORDERED: the packed
-// gradients and the bin rows move with the row ids, so that the children's rows are
-// contiguous again (rows are copied as dwords by the whole workgroup, coalesced on the
-// reading side and in two compacted streams on the writing side).
+// Order-preserving scatter of every segment into the children's buffer; seg_prefix is the
+// exclusive prefix of seg_counts over all segments of the round.  A workgroup takes a whole
+// segment (PART_SEG = 4 x 256 rows) at once: four rows per thread are loaded together, their
+// destinations follow from one round of ballots, and then (ORDERED) the bin rows move as
+// dwords, eight independent loads per thread in flight, coalesced on the reading side and in
+// two compacted streams on the writing side; the packed gradients move with the row ids.
 template <bool ORDERED>
 __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows, RowDest out, int F, IdxSet idxs,
                                                                  const StepState* __restrict__ step,
@@ -223,10 +224,11 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
                                                                  const Node* __restrict__ nodes,
                                                                  const uint8_t* __restrict__ flags,
                                                                  const int32_t* __restrict__ seg_prefix) {
+    static_assert(PART_SEG == 1024, "four sub-tiles of 256 rows");
     if (step->done) return;
     const int n_items = step->n_part_items, n_batch = step->n_batch;
-    __shared__ int wl[4];
-    __shared__ int s_dpos[256];
+    __shared__ int wl[4][4];
+    __shared__ int s_dpos[PART_SEG];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int dpr = F / 4;
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
@@ -241,59 +243,64 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
         uint8_t* bdst = ORDERED ? out.bins[cbuf] + nd.begin * (int64_t)F : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
+        const int n = (int)(send - sbegin);
         const int64_t before = seg_prefix[item] - seg_prefix[be.seg_start];  // left rows in earlier segments
-        int64_t lpos = before;                          // next left slot (relative to the node's slice)
-        int64_t rpos = nd.n_left + (sbegin - before);   // next right slot
-        for (int64_t t0 = sbegin; t0 < send; t0 += 256) {
-            const int64_t p = t0 + threadIdx.x;
-            const bool on = p < send;
-            int fl = 0;
-            int32_t v = 0;
-            int g16 = 0;
-            if (on) {
-                fl = flags[nd.begin + p];
-                v = src[p];
-                if (ORDERED) g16 = gsrc[p];
-            }
-            const unsigned long long m = __ballot(on && fl);
-            const int rank = __popcll(m & ((1ull << lane) - 1ull));
-            __syncthreads();
-            if (lane == 0) wl[wave] = __popcll(m);
-            __syncthreads();
-            int lw = 0, ltile = 0;
-            for (int k = 0; k < 4; ++k) { if (k < wave) lw += wl[k]; ltile += wl[k]; }
-            const int pos_in_tile = wave * 64 + lane;
-            const int64_t dp = fl ? lpos + lw + rank : rpos + (pos_in_tile - (lw + rank));
-            if (on) {
-                dst[dp] = v;
-                if (ORDERED) gdst[dp] = (int16_t)g16;
-            }
-            const int tile_n = (int)min((int64_t)256, send - t0);
-            if (ORDERED) {
-                s_dpos[threadIdx.x] = (int)dp;  // destination row, relative to the slice
-                __syncthreads();
-                const uint32_t* s32 = reinterpret_cast<const uint32_t*>(bsrc + t0 * (int64_t)F);
-                const int n_dw = tile_n * dpr;
-                for (int e0 = threadIdx.x; e0 < n_dw; e0 += 4 * 256) {  // four independent loads in flight
-                    uint32_t v4[4];
+        const int64_t lpos0 = before;                          // first left slot of this segment (slice-relative)
+        const int64_t rpos0 = nd.n_left + (sbegin - before);   // first right slot
+        int fl[4], rank[4], g16[4];
+        int32_t v[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = e0 + u * 256;
-                        v4[u] = e < n_dw ? s32[e] : 0u;
-                    }
+        for (int u = 0; u < 4; ++u) {
+            const int r = u * 256 + threadIdx.x;
+            fl[u] = 0; v[u] = 0; g16[u] = 0;
+            if (r < n) {
+                fl[u] = flags[nd.begin + sbegin + r];
+                v[u] = src[sbegin + r];
+                if (ORDERED) g16[u] = gsrc[sbegin + r];
+            }
+        }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = e0 + u * 256;
-                        if (e < n_dw) {
-                            const int r = e / dpr, q = e - r * dpr;
-                            reinterpret_cast<uint32_t*>(bdst + (int64_t)s_dpos[r] * F)[q] = v4[u];
-                        }
+        for (int u = 0; u < 4; ++u) {
+            const unsigned long long m = __ballot(fl[u] != 0);
+            rank[u] = __popcll(m & ((1ull << lane) - 1ull));
+            if (lane == 0) wl[u][wave] = __popcll(m);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int lw = 0;  // left rows of the segment in front of this wavefront's 64 rows of sub-tile u
+            for (int uu = 0; uu < 4; ++uu)
+                for (int w = 0; w < 4; ++w)
+                    if (uu < u || (uu == u && w < wave)) lw += wl[uu][w];
+            const int r = u * 256 + threadIdx.x;
+            const int64_t dp = fl[u] ? lpos0 + lw + rank[u] : rpos0 + (r - (lw + rank[u]));
+            if (r < n) {
+                dst[dp] = v[u];
+                if (ORDERED) { gdst[dp] = (int16_t)g16[u]; s_dpos[r] = (int)dp; }
+            }
+        }
+        if (ORDERED) {
+            __syncthreads();
+            const uint32_t* s32 = reinterpret_cast<const uint32_t*>(bsrc + sbegin * (int64_t)F);
+            const int n_dw = n * dpr;
+            for (int e0 = threadIdx.x; e0 < n_dw; e0 += 8 * 256) {
+                uint32_t v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + u * 256;
+                    v8[u] = e < n_dw ? s32[e] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + u * 256;
+                    if (e < n_dw) {
+                        const int r = e / dpr, q = e - r * dpr;
+                        reinterpret_cast<uint32_t*>(bdst + (int64_t)s_dpos[r] * F)[q] = v8[u];
                     }
                 }
             }
-            lpos += ltile;
-            rpos += tile_n - ltile;
         }
+        __syncthreads();  // wl and s_dpos are reused by the next item
     }
 }
 

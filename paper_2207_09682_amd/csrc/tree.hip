@@ -87,6 +87,20 @@ __device__ __forceinline__ int block_scan_incl(int v, int* tmp /*[16]*/) {
     return v + add;
 }
 
+// Wavefront-wide maximum of one unsigned value per lane with DPP moves (no LDS traffic);
+// the result is uniform.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#define QG_DPP(x, ctrl, rmask) (uint32_t)__builtin_amdgcn_update_dpp((int)(x), (int)(x), ctrl, rmask, 0xf, false)
+    v = max(v, QG_DPP(v, 0xB1, 0xf));   // quad_perm [1,0,3,2]
+    v = max(v, QG_DPP(v, 0x4E, 0xf));   // quad_perm [2,3,0,1]
+    v = max(v, QG_DPP(v, 0x141, 0xf));  // row_half_mirror
+    v = max(v, QG_DPP(v, 0x140, 0xf));  // row_mirror: every lane of a row holds the row's maximum
+    v = max(v, QG_DPP(v, 0x142, 0xa));  // row_bcast:15 into rows 1 and 3
+    v = max(v, QG_DPP(v, 0x143, 0xc));  // row_bcast:31 into rows 2 and 3
+#undef QG_DPP
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // Commit phase and choice of the round's batch.  One workgroup of 1024 threads; the
 // replay itself runs in its first wavefront on an LDS copy of the queue (gain, leaf id,
 // children, expanded flag of every node) and only records the order of the commits; the
@@ -101,9 +115,13 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     double* key = reinterpret_cast<double*>(plan_lds);  // gain of the node's best split, -1 if it has none
     int* lid = reinterpret_cast<int*>(key + cap);       // leaf id (open leaves)
     int* child = lid + cap;                             // left child, -1 if not expanded
-    int* open = child + cap;                            // [num_leaves] open leaves that can be split (unordered list)
-    int* commit = open + num_leaves + 1;                // [num_leaves] nodes committed in this call, in order
-    int* cand = commit + num_leaves + 1;                // [3*num_leaves] candidates of the batch selection
+    // open leaves that can be split: unordered list of (node, gain bits, leaf id), [num_leaves+1] each
+    int* o_node = child + cap;
+    uint32_t* o_hi = reinterpret_cast<uint32_t*>(o_node + num_leaves + 1);
+    uint32_t* o_lo = o_hi + num_leaves + 1;
+    uint32_t* o_lid = o_lo + num_leaves + 1;
+    int* commit = reinterpret_cast<int*>(o_lid + num_leaves + 1);  // [num_leaves] nodes committed in this call, in order
+    int* cand = commit + num_leaves + 1;                           // [3*num_leaves] candidates of the batch selection
     __shared__ int s_tmp[16];
     __shared__ int s_done, s_ncand, s_nopen, s_ncommit, s_commits0, s_leaves0;
     __shared__ unsigned long long s_units;
@@ -116,41 +134,59 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         key[i] = kg;
         lid[i] = nd->leaf_id;
         child[i] = nd->expanded ? nd->child : -1;
-        if (nd->state == 1 && kg > 0.0) open[atomicAdd(&s_nopen, 1)] = i;
+        if (nd->state == 1 && kg > 0.0) {
+            const int p = atomicAdd(&s_nopen, 1);
+            o_node[p] = i; o_hi[p] = (uint32_t)__double2hiint(kg); o_lo[p] = (uint32_t)__double2loint(kg);
+            o_lid[p] = (uint32_t)nd->leaf_id;
+        }
     }
     __syncthreads();
 
-    if (tid < 64) {  // replay of the best-first order, one wavefront, LDS only
+    if (tid < 64) {
+        // Replay of the best-first order by one wavefront, LDS and registers only.  A positive
+        // double orders like its bit pattern, so the largest gain (ties: lowest leaf id) is found
+        // by three wavefront-wide maxima: high word, low word among the high word's winners,
+        // complemented leaf id among those.
         const int commits0 = step->n_commits, leaves0 = step->n_leaves;
         int n_commits = commits0, n_leaves = leaves0, n_open = s_nopen;
         for (;;) {
             if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
-            double bg = 0.0;
-            int bi = -1, bl = 0x7fffffff, bp = -1;
+            if (n_open <= 0) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
+            uint32_t bh = 0, bl = 0, bd = 0xffffffffu;
+            int bp = -1;
             for (int p = tid; p < n_open; p += 64) {
-                const int i = open[p];
-                const double g = key[i];
-                const int l = lid[i];
-                if (g > bg || (g == bg && l < bl)) { bg = g; bi = i; bl = l; bp = p; }
+                const uint32_t h = o_hi[p], l = o_lo[p], d = o_lid[p];
+                if (bp < 0 || h > bh || (h == bh && (l > bl || (l == bl && d < bd)))) { bh = h; bl = l; bd = d; bp = p; }
             }
-            for (int o = 32; o > 0; o >>= 1) {
-                const double og = __shfl_xor(bg, o);
-                const int oi = __shfl_xor(bi, o), ol = __shfl_xor(bl, o), op = __shfl_xor(bp, o);
-                if (oi >= 0 && (bi < 0 || og > bg || (og == bg && ol < bl))) { bg = og; bi = oi; bl = ol; bp = op; }
-            }
-            if (bi < 0) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
+            const uint32_t mh = wave_max_u32(bp >= 0 ? bh : 0u);
+            const bool in1 = bp >= 0 && bh == mh;
+            const uint32_t ml = wave_max_u32(in1 ? bl : 0u);
+            const bool in2 = in1 && bl == ml;
+            const uint32_t md = ~wave_max_u32(in2 ? ~bd : 0u);
+            const unsigned long long win = __ballot(in2 && bd == md);
+            const int wl = __ffsll((long long)win) - 1;
+            const int wp = __builtin_amdgcn_readlane(bp, wl);
+            const int bi = o_node[wp];
             const int c0 = child[bi];
-            if (c0 < 0) break;                                 // the next split is not known yet
+            if (c0 < 0) break;  // the next split is not known yet
             // commit: the node leaves the queue, its children enter (left keeps the leaf id)
-            const int add0 = key[c0] > 0.0, add1 = key[c0 + 1] > 0.0;
+            const double k0 = key[c0], k1 = key[c0 + 1];
+            const int add0 = k0 > 0.0, add1 = k1 > 0.0;
             if (tid == 0) {
                 commit[n_commits - commits0] = bi;
                 key[bi] = -1.0;
-                lid[c0] = bl; lid[c0 + 1] = n_leaves;
-                open[bp] = open[n_open - 1];
-                int no = n_open - 1;
-                if (add0) open[no++] = c0;
-                if (add1) open[no++] = c0 + 1;
+                lid[c0] = (int)md; lid[c0 + 1] = n_leaves;
+                const int last = n_open - 1;
+                o_node[wp] = o_node[last]; o_hi[wp] = o_hi[last]; o_lo[wp] = o_lo[last]; o_lid[wp] = o_lid[last];
+                int no = last;
+                if (add0) {
+                    o_node[no] = c0; o_hi[no] = (uint32_t)__double2hiint(k0); o_lo[no] = (uint32_t)__double2loint(k0);
+                    o_lid[no] = md; ++no;
+                }
+                if (add1) {
+                    o_node[no] = c0 + 1; o_hi[no] = (uint32_t)__double2hiint(k1); o_lo[no] = (uint32_t)__double2loint(k1);
+                    o_lid[no] = (uint32_t)n_leaves; ++no;
+                }
             }
             n_open += add0 + add1 - 1;
             n_commits += 1; n_leaves += 1;
@@ -200,7 +236,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     // (class 1; encoded as -1-node).  A node's rows outlive the expansion of its children, so
     // expanding the children of a leaf whose split is not committed yet is safe.
     for (int p = tid; p < s_nopen; p += blockDim.x) {
-        const int i = open[p];
+        const int i = o_node[p];
         const int c0 = child[i];
         if (c0 < 0) {
             cand[atomicAdd(&s_ncand, 1)] = i;
@@ -460,7 +496,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (rc != QGBDT_OK) return rc;
 
     const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int)) +
-                            (size_t)(11 * p->num_leaves + 16) * sizeof(int) + 64;
+                            (size_t)(14 * p->num_leaves + 24) * sizeof(int) + 64;
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
