@@ -126,20 +126,31 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         bins_h = bins.cpu().numpy()
-        g_h = gs[W].cpu().numpy(); h_h = hs[W].cpu().numpy()
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        gq, hq, _ = oracle.quantize_gradients(g_h, h_h, bits_g, bits_h, cfg.seed, W)
+        # whole trees of the oracle on the (g, h) of the first timed iterations, until about 10 s are spent
+        c_units, c_trees, c_el, c_match = 0, 0, 0.0, True
         c0 = time.perf_counter()
-        reps = 0
-        while True:
-            oracle.build_histograms(bins_h, nb, gq, hq)
-            reps += 1
-            if time.perf_counter() - c0 > 12.0 or reps >= 20:
-                break
-        c_el = time.perf_counter() - c0
-        cpu = {"value": reps * N * F / c_el, "unit": "rows*features/s", "cores": threads, "kind": "oracle",
-               "sample": f"{reps} root-pass histogram builds of the oracle (all {N} rows x {F} features, "
-                         f"{bits_g}-bit), {c_el:.1f} s"}
+        while c_trees < K and time.perf_counter() - c0 < 10.0:
+            it = W + c_trees
+            g_h = gs[it].cpu().numpy(); h_h = hs[it].cpu().numpy()
+            c1 = time.perf_counter()
+            tr = oracle.grow_tree(bins_h, nb, g_h, h_h, bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf)
+            c_el += time.perf_counter() - c1
+            c_units += int(tr.hist_units); c_trees += 1
+            # the same tree from the library, in the launch configuration that was timed (untimed check)
+            ctx.grow_tree(bins, gs[it], hs[it], bits_g, bits_h, cfg.seed, it, L, cfg.min_data_in_leaf,
+                          acc_width=args.acc_width, tree=tree)
+            ns = int(tree.n_leaves.item()) - 1
+            c_match = c_match and ns == tr.n_leaves - 1 \
+                and np.array_equal(tree.split_feature[:ns].cpu().numpy(), tr.split_feature[:ns]) \
+                and np.array_equal(tree.split_bin[:ns].cpu().numpy(), tr.split_bin[:ns]) \
+                and np.array_equal(tree.split_leaf[:ns].cpu().numpy(), tr.split_leaf[:ns]) \
+                and np.array_equal(tree.row_idx.cpu().numpy(), tr.row_idx)
+        cpu = {"value": c_units / c_el, "unit": "rows*features/s", "cores": threads, "kind": "oracle",
+               "sample": f"{c_trees} whole tree(s) of the oracle (quantize, histograms, subtraction, scan, partition, "
+                         f"refit) on all {N} rows x {F} features, the (g, h) of timed step(s) 0..{c_trees - 1}, "
+                         f"{c_el:.1f} s", "s_per_tree": c_el / c_trees,
+               "library_tree_equals_oracle_tree": bool(c_match)}
 
     achieved = (hist_bytes / hist_launches) / (hist_ms / hist_launches * 1e-3) / 1e9 if hist_launches and hist_ms > 0 else 0.0
     out = {

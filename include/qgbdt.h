@@ -108,8 +108,10 @@ typedef struct {
 /* ---- lifecycle ---------------------------------------------------------- */
 
 /* Creates a context for `shape` on the current device and allocates its workspace
- * (row-index double buffer, quantized gradients, one histogram per leaf, small
- * descriptors).  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
+ * (three row-index buffers, quantized gradients, a pool of histograms, small
+ * descriptors; for 16..64 features that are a multiple of 4 also three leaf-ordered
+ * copies of the bin rows).  `stream` is a hipStream_t (NULL = default stream).
+ * Synchronous. */
 QGBDT_API int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream);
 /* Frees the workspace and the context.  Synchronises the stream first. */
 QGBDT_API int qgbdt_destroy(qgbdt_ctx* ctx);
@@ -179,8 +181,14 @@ QGBDT_API int qgbdt_refit_leaves(qgbdt_ctx* ctx, const float* g, const float* h,
  * left child keeps the parent's id, the right child takes the next id; the child
  * with fewer rows (tie: left) is built from its rows, its sibling by subtraction;
  * stops at num_leaves or when no gain > 0 is left; leaf values are refit at the end.
- * The whole tree is enqueued without any host synchronisation.  bins: dev; g, h: dev
- * float[n_rows]; row_idx_out: dev int32[n_rows], leaf-ordered rows. */
+ * The result is that of this sequential procedure; the work is done in rounds that
+ * expand several leaves at once (the one the procedure needs next plus leaves it is
+ * likely to need), and the order of the splits is replayed on the device.  The host
+ * waits on the stream once per batch of rounds to read a 'finished' flag (normally
+ * once per tree) and, when n_rows exceeds what a 32-bit field surely holds, once
+ * more after quantization to check the quantized totals (QGBDT_E_OVERFLOW_RISK).
+ * bins: dev; g, h: dev float[n_rows]; row_idx_out: dev int32[n_rows], leaf-ordered
+ * rows (ascending inside each leaf). */
 QGBDT_API int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const float* h,
                     const qgbdt_params* params, uint32_t iteration, const qgbdt_tree* tree_out,
                     int32_t* row_idx_out);

@@ -51,7 +51,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->gh, c->hist_pool, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->idx[2], c->gh, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -117,6 +117,18 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[2], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (c->max_expand + 1)));
+    if (rc == QGBDT_OK) {
+        // slots of the row groups' local bins, for either accumulator width
+        size_t need = 0;
+        for (int w = 16; w <= 32; w += 16) {
+            const HistPlan hp = make_hist_plan(*shape, 2, 2, w);
+            const size_t b = (size_t)hp.max_items * hp.n_tiles * hp.slot_bytes;
+            if (b > need) need = b;
+        }
+        unsigned char* pp = nullptr;
+        rc = ws_alloc(c, &pp, need);
+        c->hist_partials = pp;
+    }
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->flags, (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->part_counts, (size_t)PART_GROUPS);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_counts, (size_t)c->max_seg);

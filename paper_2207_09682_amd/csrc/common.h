@@ -94,7 +94,24 @@ struct HistPlan {
     int32_t flat_lanes;  // > 0: contiguous slices may use the flat 16-byte-load kernel with this many lanes
     int32_t flat_rows;   // rows per wavefront iteration of that kernel
     int32_t flat_unroll;
+    int32_t max_items;    // most work items (row groups) of one launch = slots of the partial-histogram buffer
+    int32_t slot_bytes;   // bytes of one (item, tile) slot: the tile's local bins, padded to 16 bytes
+    int32_t single_rows;  // a group of at most this many rows is accumulated in one chunk by every kernel variant
 };
+
+// Rows per row group when `total` rows of `n_entries` builds are shared out: about max_groups
+// groups in all, none smaller than min_rows_per_group unless its build is; and, when the item
+// table has room, no group larger than one chunk, so that no group merges through atomics.
+__host__ __device__ inline int64_t hist_target_rows(const HistPlan& p, int64_t total, int n_entries) {
+    int64_t t = (total + p.max_groups - 1) / p.max_groups;
+    if (t < p.min_rows_per_group) t = p.min_rows_per_group;
+    if (t > p.single_rows) {
+        const int64_t room = (int64_t)p.max_items - n_entries - 1;
+        if (total / p.single_rows < room) t = p.single_rows;
+        else if (room > 0 && (total + room - 1) / room > t) t = (total + room - 1) / room;
+    }
+    return t;
+}
 
 struct ScanItem;
 
@@ -138,6 +155,7 @@ struct qgbdt_ctx {
     int32_t* idx[3];       // [N] each
     int16_t* gh;           // [N]
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
+    void* hist_partials;   // [max_items][n_tiles] local bins of the row groups, summed by the reduce kernel
     uint8_t* flags;        // [N] partition flags
     int64_t* part_counts;  // [PART_GROUPS] (stand-alone partition)
     int32_t* seg_counts;   // [max_seg] left rows per partition segment

@@ -101,6 +101,25 @@ __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_
     }
 }
 
+// Last chunk of a row group: the local bins go to the group's slot as they are (plain 16-byte
+// stores, padding included) and are reset; the reduce kernel adds the slots of a build to
+// its histogram.  Costs a quarter of the same merge through atomics.
+template <int W>
+__device__ __forceinline__ void store_partial(typename Acc<W>::word* lds, int lds_bytes, unsigned char* slot) {
+    uint4* l4 = reinterpret_cast<uint4*>(lds);
+    uint4* s4 = reinterpret_cast<uint4*>(slot);
+    const int n4 = lds_bytes >> 4;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+        s4[i] = l4[i];
+        l4[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    const int done = n4 << 4;  // a tile whose bins are not a multiple of 16 bytes
+    for (int i = done + 4 * threadIdx.x; i < lds_bytes; i += 4 * blockDim.x) {
+        *reinterpret_cast<uint32_t*>(slot + i) = *reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(lds) + i);
+        *reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(lds) + i) = 0u;
+    }
+}
+
 // Fast path (feature count a multiple of 4), any row set.  lane -> (row r of the
 // iteration, dword q of the row's feature tile); U row-iterations (U*rows_per_it
 // <= 64 rows) form one block of a wavefront.  All loads of a block are issued before
@@ -116,7 +135,8 @@ template <int W, bool IDX, int U>
 __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
-                                                    int F, int nb, HistPlan plan, StepState* step) {
+                                                    unsigned char* partials, int F, int nb, HistPlan plan,
+                                                    StepState* step) {
     using word = typename Acc<W>::word;
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
@@ -152,17 +172,18 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
-        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
-        if (gbegin >= en.count) continue;
+        const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        unsigned char* slot = partials + ((size_t)item * gridDim.y + blockIdx.y) * (size_t)plan.slot_bytes;
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
         const uint8_t* colbase = src.bins[sb] + f0 + 4 * q;
         const int16_t* gh = src.gh[sb];
 
-        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
+        // a group without rows still hands over its (empty) bins
+        for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             const int crow = (int)(cend - cbegin);
             __syncthreads();
@@ -218,7 +239,8 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
                 }
             }
             __syncthreads();
-            merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist);
+            if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist);
         }
     }
 }
@@ -233,8 +255,8 @@ template <int W, int U>
 __global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
                                                          const HistEntry* __restrict__ entries,
                                                          const int32_t* __restrict__ table_counts,
-                                                         int64_t* hist_base, int F, int nb, HistPlan plan,
-                                                         StepState* step) {
+                                                         int64_t* hist_base, unsigned char* partials, int F, int nb,
+                                                         HistPlan plan, StepState* step) {
     using word = typename Acc<W>::word;
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
@@ -289,11 +311,11 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
         rows_per_group = (rows_per_group + BR - 1) / BR * BR;  // keeps every group start 16-byte aligned
         if (rows_per_group < BR) rows_per_group = BR;
         const int g = item - en.item_start;
-        const int64_t gbegin = head + (int64_t)g * rows_per_group;
-        if (gbegin >= en.count && !(g == 0 && head > 0)) continue;
+        const int64_t gbegin = min(en.count, head + (int64_t)g * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        bool first = true;
+        unsigned char* slot = partials + (size_t)item * (size_t)plan.slot_bytes;
+        bool first = true;  // a group without rows still hands over its (empty) bins
 
         for (int64_t cbegin = gbegin; first || cbegin < gend; cbegin += chunk) {
             const int64_t cend = min(gend, cbegin + (int64_t)chunk);
@@ -358,7 +380,8 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
                 }
             }
             __syncthreads();
-            merge_local<W>(lds, lds_words, ftp, F, 0, F, hist);
+            if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
+            else merge_local<W>(lds, lds_words, ftp, F, 0, F, hist);
             first = false;
         }
     }
@@ -369,8 +392,8 @@ template <int W>
 __global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSet idxs, int use_idx,
                                                             const HistEntry* __restrict__ entries,
                                                             const int32_t* __restrict__ table_counts,
-                                                            int64_t* hist_base, int F, int nb, HistPlan plan,
-                                                            StepState* step) {
+                                                            int64_t* hist_base, unsigned char* partials, int F,
+                                                            int nb, HistPlan plan, StepState* step) {
     using word = typename Acc<W>::word;
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
@@ -385,14 +408,14 @@ __global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSe
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
-        const int64_t gbegin = (int64_t)(item - en.item_start) * rows_per_group;
-        if (gbegin >= en.count) continue;
+        const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        unsigned char* slot = partials + ((size_t)item * gridDim.y + blockIdx.y) * (size_t)plan.slot_bytes;
         const int32_t* idx = use_idx ? (idxs.p[en.buf] + en.begin) : nullptr;
         const uint8_t* bins = src.bins[use_idx ? BUF_ORIGINAL : en.buf];
         const int16_t* gh = src.gh[use_idx ? BUF_ORIGINAL : en.buf];
-        for (int64_t cbegin = gbegin; cbegin < gend; cbegin += plan.chunk_rows) {
+        for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             __syncthreads();
             const int64_t n_el = (cend - cbegin) * ft;
@@ -404,8 +427,61 @@ __global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSe
                 Acc<W>::add(&lds[b * ft + f], Acc<W>::expand(gh[i]));
             }
             __syncthreads();
-            merge_local<W>(lds, lds_words, ft, ft, f0, F, hist);
+            if (cend >= gend) store_partial<W>(lds, lds_words * (int)sizeof(word), slot);
+            else merge_local<W>(lds, lds_words, ft, ft, f0, F, hist);
         }
+    }
+}
+
+// Adds the slots of every build's row groups to the build's histogram.  Thread -> one word
+// of a tile's local bins; the launch's items are cut into gridDim.z runs, a thread walks its
+// run (consecutive items mostly belong to one build) and issues one 64-bit atomic per build
+// it meets.  `generic` slots have the pitch of their tile's width, the others plan.ftp.
+template <int W>
+__global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* __restrict__ partials,
+                                                          const HistEntry* __restrict__ entries,
+                                                          const int32_t* __restrict__ table_counts,
+                                                          int64_t* hist_base, int F, int nb, HistPlan plan,
+                                                          int generic) {
+    using word = typename Acc<W>::word;
+    const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int per = (n_items + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int i0 = blockIdx.z * per, i1 = min(n_items, i0 + per);
+    if (i0 >= i1) return;
+    const int f0 = blockIdx.y * plan.ft;
+    const int ft = min(plan.ft, F - f0);
+    const int pitch = generic ? ft : plan.ftp;
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = w / pitch, f = w - b * pitch;
+    if (b >= nb || f >= ft) return;
+    const size_t stride = (size_t)gridDim.y * (size_t)plan.slot_bytes;  // bytes from one item's slot to the next
+    const unsigned char* base = partials + (size_t)blockIdx.y * (size_t)plan.slot_bytes + (size_t)w * sizeof(word);
+    const int64_t hoff = (int64_t)b * F + f0 + f;
+    int e = find_entry(entries, n_entries, i0);
+    int i = i0;
+    while (i < i1) {
+        const int iend = min(i1, entries[e].item_start + entries[e].groups);
+        int64_t sg = 0, sh = 0;
+        for (; i + 4 <= iend; i += 4) {
+            word v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const word*>(base + (size_t)(i + k) * stride);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (W == 16) { sg += (int32_t)v[k] >> 16; sh += (uint32_t)v[k] & 0xffffu; }
+                else sg += (int64_t)v[k];
+            }
+        }
+        for (; i < iend; ++i) {
+            const word v = *reinterpret_cast<const word*>(base + (size_t)i * stride);
+            if (W == 16) { sg += (int32_t)v >> 16; sh += (uint32_t)v & 0xffffu; }
+            else sg += (int64_t)v;
+        }
+        const int64_t sum = (W == 16) ? sg * 4294967296LL + sh : sg;
+        if (sum != 0)
+            atomicAdd(reinterpret_cast<unsigned long long*>(hist_base + (int64_t)entries[e].slot * F * nb + hoff),
+                      (unsigned long long)sum);
+        ++e;
     }
 }
 
@@ -481,6 +557,11 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
             if ((16 * l) % F == 0) { p.flat_lanes = l; p.flat_rows = 16 * l / F; break; }
     }
     p.flat_unroll = 2;
+    p.slot_bytes = (p.lds_bytes + 15) & ~15;
+    p.max_items = 4 * p.max_groups;
+    if (p.max_items < 2 * s.max_leaves + 64) p.max_items = 2 * s.max_leaves + 64;
+    p.single_rows = p.chunk_rows >= 1024 ? p.chunk_rows - 320 : p.chunk_rows / 2;
+    if (p.single_rows < 1) p.single_rows = 1;
     if (const char* e = getenv("QGBDT_NOFLAT")) { if (atoi(e)) p.flat_lanes = 0; }
     if (const char* e = getenv("QGBDT_FLAT_U")) p.flat_unroll = atoi(e);
     if (const char* e = getenv("QGBDT_MAX_GROUPS")) p.max_groups = atoi(e);
@@ -490,11 +571,10 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
 }
 
 // One entry table for a stand-alone build.
-__global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64_t begin, int64_t count, int min_rows,
-                                      int max_groups) {
+__global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64_t begin, int64_t count, HistPlan plan) {
     if (threadIdx.x == 0) {
-        int64_t g = (count + min_rows - 1) / min_rows;
-        if (g > max_groups) g = max_groups;
+        const int64_t t = hist_target_rows(plan, count, 1);
+        int64_t g = (count + t - 1) / t;
         if (g < 1) g = 1;
         HistEntry e;
         e.begin = begin; e.count = count; e.buf = BUF_ORIGINAL; e.slot = 0; e.item_start = 0; e.groups = (int32_t)g;
@@ -506,7 +586,7 @@ __global__ void set_hist_table_kernel(HistEntry* entries, int32_t* counts, int64
 
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count) {
     hipLaunchKernelGGL(set_hist_table_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->hist_entries, ctx->hist_counts,
-                       begin, count, plan.min_rows_per_group, plan.max_groups);
+                       begin, count, plan);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
@@ -517,6 +597,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
                 bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
                 int64_t grid_items, StepState* step) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
+    unsigned char* partials = static_cast<unsigned char*>(ctx->hist_partials);
     int64_t groups = grid_items;
     if (groups > plan.max_groups) groups = plan.max_groups;
     if (groups < 1) groups = 1;
@@ -531,7 +612,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     if (flat) {
 #define QG_LAUNCH_FLAT(W_, U_)                                                                                   \
     hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, entries, \
-                       table_counts, hist_base, F, nb, plan, step)
+                       table_counts, hist_base, partials, F, nb, plan, step)
         if (plan.acc_width == 16) {
             if (plan.flat_unroll >= 4) QG_LAUNCH_FLAT(16, 4);
             else if (plan.flat_unroll >= 2) QG_LAUNCH_FLAT(16, 2);
@@ -547,7 +628,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
 #define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                              \
     hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
-                       entries, table_counts, hist_base, F, nb, plan, step)
+                       entries, table_counts, hist_base, partials, F, nb, plan, step)
 #define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
     switch (U) {                                                                        \
         case 8: QG_LAUNCH_HIST(W_, IDX_, 8); break;                                     \
@@ -565,12 +646,30 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
 #undef QG_LAUNCH_HIST
     } else if (plan.acc_width == 16) {
         hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
-                           use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
+                           use_idx ? 1 : 0, entries, table_counts, hist_base, partials, F, nb, plan, step);
     } else {
         hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
-                           use_idx ? 1 : 0, entries, table_counts, hist_base, F, nb, plan, step);
+                           use_idx ? 1 : 0, entries, table_counts, hist_base, partials, F, nb, plan, step);
     }
     QG_HIP(ctx, hipGetLastError());
+    {
+        // the slots of the row groups are added to the histograms
+        const int tile_words = nb * (fast ? plan.ftp : plan.ft);
+        const int xb = (tile_words + 255) / 256;
+        int64_t items_bound = grid_items < plan.max_items ? grid_items : plan.max_items;
+        int z = (int)(2048 / ((int64_t)xb * plan.n_tiles));
+        if (z > 64) z = 64;
+        if (z > items_bound) z = (int)items_bound;
+        if (z < 1) z = 1;
+        dim3 rgrid((unsigned)xb, (unsigned)plan.n_tiles, (unsigned)z);
+        if (plan.acc_width == 16)
+            hipLaunchKernelGGL(hist_reduce_kernel<16>, rgrid, dim3(256), 0, ctx->stream, partials, entries, table_counts,
+                               hist_base, F, nb, plan, fast ? 0 : 1);
+        else
+            hipLaunchKernelGGL(hist_reduce_kernel<32>, rgrid, dim3(256), 0, ctx->stream, partials, entries, table_counts,
+                               hist_base, F, nb, plan, fast ? 0 : 1);
+        QG_HIP(ctx, hipGetLastError());
+    }
     if (e1) QG_HIP(ctx, hipEventRecord(e1, ctx->stream));
     return QGBDT_OK;
 }

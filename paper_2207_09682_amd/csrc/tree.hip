@@ -34,9 +34,9 @@ __device__ __forceinline__ void clear_split(qgbdt_split& s) {
     s.left_g = s.left_h = s.right_g = s.right_h = s.left_count = 0;
 }
 
-__device__ __forceinline__ int hist_groups(int64_t count, int min_rows, int max_groups) {
-    int64_t g = (count + min_rows - 1) / min_rows;
-    if (g > max_groups) g = max_groups;
+__device__ __forceinline__ int hist_groups(int64_t count, const HistPlan& plan) {
+    const int64_t t = hist_target_rows(plan, count, 1);
+    int64_t g = (count + t - 1) / t;
     if (g < 1) g = 1;
     return (int)g;
 }
@@ -44,8 +44,7 @@ __device__ __forceinline__ int hist_groups(int64_t count, int min_rows, int max_
 __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, int F, StepState* step, Node* nodes,
                                                         const int64_t* qtotals, int root_buf, HistEntry* hist_entries,
                                                         int32_t* hist_counts, ScanItem* items, int32_t* scan_counters,
-                                                        int64_t* hist0, int64_t hist_words, int min_rows,
-                                                        int max_groups) {
+                                                        int64_t* hist0, int64_t hist_words, HistPlan plan) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = t; i < N; i += stride) idx0[i] = (int32_t)i;
@@ -60,7 +59,7 @@ __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N
         clear_split(r.best);
         nodes[0] = r;
         HistEntry e;
-        e.begin = 0; e.count = N; e.buf = root_buf; e.slot = 0; e.item_start = 0; e.groups = hist_groups(N, min_rows, max_groups);
+        e.begin = 0; e.count = N; e.buf = root_buf; e.slot = 0; e.item_start = 0; e.groups = hist_groups(N, plan);
         hist_entries[0] = e;
         hist_counts[0] = 1; hist_counts[1] = e.groups;
         ScanItem it;
@@ -337,7 +336,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
 __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* nodes, const BatchEntry* batch,
                                                         const int32_t* seg_counts, int32_t* seg_prefix,
                                                         HistEntry* hist_entries, int32_t* hist_counts, ScanItem* items,
-                                                        int min_rows, int max_groups) {
+                                                        HistPlan plan) {
     if (step->done) return;
     __shared__ int s_tmp[16];
     const int tid = threadIdx.x;
@@ -391,8 +390,7 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
     if (tid == (int)blockDim.x - 1) s_total = total_small;
     __syncthreads();
     if (tid < n_batch) {
-        int target = (s_total + max_groups - 1) / max_groups;
-        if (target < min_rows) target = min_rows;
+        const int target = (int)hist_target_rows(plan, s_total, n_batch);
         groups = (small_rows + target - 1) / target;
         if (groups < 1) groups = 1;
     }
@@ -486,7 +484,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
-                       ctx->scan_counters, ctx->hist_pool, W, plan.min_rows_per_group, plan.max_groups);
+                       ctx->scan_counters, ctx->hist_pool, W, plan);
     rc = launch_hist(ctx, plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
                      (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
@@ -509,7 +507,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                                ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
-                               plan.min_rows_per_group, plan.max_groups);
+                               plan);
             rc = launch_batch_partition_scatter(ctx, rows);
             if (rc != QGBDT_OK) return rc;
             rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
@@ -534,7 +532,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         if (rc != QGBDT_OK) return rc;
         hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                            ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
-                           plan.min_rows_per_group, plan.max_groups);
+                           plan);
         rc = launch_batch_partition_scatter(ctx, rows);
         if (rc != QGBDT_OK) return rc;
         rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
