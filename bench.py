@@ -38,7 +38,33 @@ def parse():
     ap.add_argument("--acc-width", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--root-reps", type=int, default=20)
+    ap.add_argument("--root-only", action="store_true",
+                    help="only the full-size root-pass histogram build (3 warm-up + --root-reps launches); prints "
+                         "the root_pass object alone (used for the per-kernel rocprofv3 summaries)")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="counter collection run: 5 root-pass builds, one tree, then three plain 256 MiB copies "
+                         "(the last dispatches of the process) that calibrate FETCH_SIZE / WRITE_SIZE; no timing")
     return ap.parse_args()
+
+
+def root_pass(ctx, torch, bins, g, h, bits_g, bits_h, cfg, args, iteration, N, F, nb):
+    """Times the histogram build of all rows (quantized (g, h) of one iteration) with HIP events."""
+    gh, _ = ctx.quantize_gradients(g, h, bits_g, bits_h, cfg.seed, iteration)
+    hist = torch.empty(F * nb, dtype=torch.int64, device=bins.device)
+    for _ in range(3):
+        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    torch.cuda.synchronize()
+    ctx.set_profiling(True)
+    ctx.read_profile()
+    for _ in range(args.root_reps):
+        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    root_ms, root_n, root_bytes = ctx.read_profile()
+    ctx.set_profiling(False)
+    avg_ms = root_ms / max(root_n, 1)
+    gbs = root_bytes / max(root_n, 1) / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    return {"avg_launch_us": avg_ms * 1e3, "achieved_GBps": gbs, "frac": gbs / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": root_bytes / max(root_n, 1),
+            "rows_x_features_per_s": N * F / (avg_ms * 1e-3) if avg_ms > 0 else 0.0, "reps": root_n}
 
 
 def main():
@@ -67,6 +93,33 @@ def main():
     ctx = Context(N, F, nb, max_leaves=L)
     K, W = args.steps, args.warmup
     sys.stderr.write(f"[bench] workload {cfg.name}: {N} x {F}, {nb} bins, generated in {time.time() - t0:.1f}s\n")
+
+    if args.pmc_probe:
+        g, h = workloads.gradients(wl, torch.zeros(N, device=dev))
+        tree = ctx.new_tree()
+        ctx.grow_tree(bins, g, h, bits_g, bits_h, cfg.seed, 0, L, cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
+        upd = torch.zeros(N, device=dev)
+        g, h = workloads.gradients(wl, upd.normal_(0.0, 0.5))  # spread gradients, like a later iteration
+        gh, _ = ctx.quantize_gradients(g, h, bits_g, bits_h, cfg.seed, 1)
+        hist = torch.empty(F * nb, dtype=torch.int64, device=dev)
+        for _ in range(5):
+            ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+        torch.cuda.synchronize()
+        n_copy = 256 * 1024 * 1024
+        src = torch.zeros(n_copy, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "root_pass_algorithmic_bytes": N * (F + 2) + F * nb * 8,
+                          "copy_bytes_read": n_copy, "copy_bytes_written": n_copy}))
+        return
+
+    if args.root_only:
+        g, h = workloads.gradients(wl, torch.zeros(N, device=dev).normal_(0.0, 0.5))
+        print(json.dumps({"root_pass": root_pass(ctx, torch, bins, g, h, bits_g, bits_h, cfg, args, 1, N, F, nb)}))
+        return
 
     # ---- set-up (untimed): a real boosting run that records (g, h) of every iteration --------
     score = torch.zeros(N, device=dev)
@@ -107,19 +160,7 @@ def main():
     n_leaves_last = int(tree.n_leaves.item())
 
     # ---- root pass alone (contiguous rows): the kernel at its full-size launch -----------------
-    gh, _ = ctx.quantize_gradients(gs[W], hs[W], bits_g, bits_h, cfg.seed, W)
-    hist = torch.empty(F * nb, dtype=torch.int64, device=dev)
-    for _ in range(3):
-        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
-    torch.cuda.synchronize()
-    ctx.set_profiling(True)
-    ctx.read_profile()
-    for _ in range(args.root_reps):
-        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
-    root_ms, root_n, root_bytes = ctx.read_profile()
-    ctx.set_profiling(False)
-    root_avg_ms = root_ms / max(root_n, 1)
-    root_gbs = root_bytes / max(root_n, 1) / (root_avg_ms * 1e-3) / 1e9 if root_avg_ms > 0 else 0.0
+    root = root_pass(ctx, torch, bins, gs[W], hs[W], bits_g, bits_h, cfg, args, W, N, F, nb)
 
     # ---- CPU oracle on the same inputs -----------------------------------------------------------
     cpu = None
@@ -173,9 +214,7 @@ def main():
                      "kernel": "hist_kernel (all launches of the timed trees)",
                      "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
                      "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1)},
-        "root_pass": {"avg_launch_us": root_avg_ms * 1e3, "achieved_GBps": root_gbs, "frac": root_gbs / HBM_PEAK_GBS,
-                      "rows_x_features_per_s": N * F / (root_avg_ms * 1e-3) if root_avg_ms > 0 else 0.0,
-                      "reps": root_n},
+        "root_pass": root,
         "hist_time_share": hist_ms / (elapsed * 1e3),
         "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,
                    "committed_per_tree": sum(x[2] for x in stats) / K},

@@ -100,121 +100,175 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Commit phase and choice of the round's batch.  One workgroup of 1024 threads; the
-// replay itself runs in its first wavefront on an LDS copy of the queue (gain, leaf id,
-// children, expanded flag of every node) and only records the order of the commits; the
-// outputs of the committed splits are then written by all threads.
+// Sorts P (a power of two) 64-bit keys in LDS into descending order with their payloads:
+// bitonic network, one compare-exchange per thread and step.  A wavefront's 64 threads own
+// 128 consecutive elements in every step with a distance of at most 64, so only the steps
+// with a larger distance need a workgroup barrier.
+__device__ inline void bitonic_sort_desc(unsigned long long* key, int* val, int P) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (P >> 1); t += nt) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int q = i | j;
+                const bool desc = (i & k) == 0;
+                const unsigned long long a = key[i], b = key[q];
+                if ((a < b) == desc) {
+                    key[i] = b; key[q] = a;
+                    const int va = val[i], vb = val[q];
+                    val[i] = vb; val[q] = va;
+                }
+            }
+            if (j > 64) __syncthreads();
+            else __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+        if (k >= 128) __syncthreads();  // the next phase starts with a distance its wavefronts do not own
+    }
+    __syncthreads();
+}
+
+// Exclusive prefix sum over P values in LDS (in place); every thread owns a contiguous run.
+// Returns the total.
+__device__ inline int block_scan_array(int* v, int P, int* tmp /*[16]*/) {
+    const int per = (P + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int a = min((int)threadIdx.x * per, P), b = min(a + per, P);
+    int local = 0;
+    for (int i = a; i < b; ++i) local += v[i];
+    const int incl = block_scan_incl(local, tmp);
+    int run = incl - local;
+    for (int i = a; i < b; ++i) { const int x = v[i]; v[i] = run; run += x; }
+    __shared__ int s_scan_total;
+    if (threadIdx.x == blockDim.x - 1) s_scan_total = incl;
+    __syncthreads();
+    return s_scan_total;
+}
+
+// Priority of an open leaf in the replay as one unsigned word: better gain rank first, then
+// the lower leaf id.  Never 0.
+__device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
+    return ((uint32_t)(0xffff - rank) << 16) | (uint32_t)(0xffff - leaf);
+}
+
+// Commit phase and choice of the round's batch.  One workgroup of 1024 threads.
+//  1. All known nodes that can still be split are sorted by gain (LDS, bitonic); a node's rank
+//     is the number of nodes with a strictly larger gain.
+//  2. One wavefront replays best-first selection: the open leaves are kept in an array indexed
+//     by leaf id whose entries combine (rank, leaf id), so the leaf with the largest gain (ties:
+//     lowest leaf id) is one wavefront-wide maximum; it is committed if it has been expanded
+//     (its children become open leaves: the left one in its place, the right one as the next
+//     leaf id), else the replay stops.  Only the order is recorded.
+//  3. All threads write the outputs of the committed splits.
+//  4. The batch is chosen by walking the sorted order (prefix sums over sorted positions).
 __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
                                                          int32_t* hist_counts, int32_t* scan_counters, int F,
-                                                         int num_leaves, int batch_max, int max_expand, TreeOut out) {
+                                                         int num_leaves, int batch_max, int max_expand, int p_max,
+                                                         TreeOut out) {
     if (step->done) return;
     extern __shared__ unsigned char plan_lds[];
     const int n_nodes0 = step->n_nodes;
-    const int cap = 2 * max_expand + 1;                 // nodes
-    double* key = reinterpret_cast<double*>(plan_lds);  // gain of the node's best split, -1 if it has none
-    int* lid = reinterpret_cast<int*>(key + cap);       // leaf id (open leaves)
-    int* child = lid + cap;                             // left child, -1 if not expanded
-    // open leaves that can be split: unordered list of (node, gain bits, leaf id), [num_leaves+1] each
-    int* o_node = child + cap;
-    uint32_t* o_hi = reinterpret_cast<uint32_t*>(o_node + num_leaves + 1);
-    uint32_t* o_lo = o_hi + num_leaves + 1;
-    uint32_t* o_lid = o_lo + num_leaves + 1;
-    int* commit = reinterpret_cast<int*>(o_lid + num_leaves + 1);  // [num_leaves] nodes committed in this call, in order
-    int* cand = commit + num_leaves + 1;                           // [3*num_leaves] candidates of the batch selection
+    const int cap = 2 * max_expand + 1;  // nodes
+    int P = 64;
+    while (P < n_nodes0) P <<= 1;
+    unsigned long long* skey = reinterpret_cast<unsigned long long*>(plan_lds);  // [p_max] gain bits, sorted
+    int* sidx = reinterpret_cast<int*>(skey + p_max);                            // [p_max] node at a sorted position
+    int* rankof = sidx + p_max;                                                  // [cap] -1: cannot be split
+    int* posof = rankof + cap;                                                   // [cap] sorted position
+    int* child = posof + cap;                                                    // [cap] left child, -1 if not expanded
+    uint32_t* okey = reinterpret_cast<uint32_t*>(child + cap);                   // [num_leaves+1] by leaf id, 0: no gain
+    int* onode = reinterpret_cast<int*>(okey + num_leaves + 1);                  // [num_leaves+1] node of a leaf id
+    int* commit = onode + num_leaves + 1;                                        // [num_leaves] nodes committed, in order
+    int* commit_lid = commit + num_leaves;                                       // [num_leaves] their leaf ids
+    int* flag = reinterpret_cast<int*>(skey);  // [P] per sorted position, reuses the keys once the ranks are known
+    int* flag2 = flag + p_max;                 // [P]
     __shared__ int s_tmp[16];
-    __shared__ int s_done, s_ncand, s_nopen, s_ncommit, s_commits0, s_leaves0;
+    __shared__ int s_done, s_ncommit, s_commits0, s_leaves0, s_nleaves;
     __shared__ unsigned long long s_units;
     const int tid = threadIdx.x;
-    if (tid == 0) { s_done = 0; s_ncand = 0; s_nopen = 0; s_ncommit = 0; s_units = 0ull; }
-    __syncthreads();
-    for (int i = tid; i < n_nodes0; i += blockDim.x) {
-        const Node* nd = &nodes[i];
-        const double kg = (nd->best.feature >= 0 && nd->state != 2) ? nd->best.gain : -1.0;
-        key[i] = kg;
-        lid[i] = nd->leaf_id;
-        child[i] = nd->expanded ? nd->child : -1;
-        if (nd->state == 1 && kg > 0.0) {
-            const int p = atomicAdd(&s_nopen, 1);
-            o_node[p] = i; o_hi[p] = (uint32_t)__double2hiint(kg); o_lo[p] = (uint32_t)__double2loint(kg);
-            o_lid[p] = (uint32_t)nd->leaf_id;
+    const int commits0 = step->n_commits, leaves0 = step->n_leaves;
+    if (tid == 0) { s_done = 0; s_ncommit = 0; s_units = 0ull; }
+    for (int i = tid; i < P; i += blockDim.x) {
+        unsigned long long kb = 0ull;
+        if (i < n_nodes0) {
+            const Node* nd = &nodes[i];
+            const int st = nd->state;
+            const double kg = (nd->best.feature >= 0 && st != 2) ? nd->best.gain : -1.0;
+            if (kg > 0.0) kb = (unsigned long long)__double_as_longlong(kg);  // positive doubles order like their bits
+            child[i] = nd->expanded ? nd->child : -1;
+            if (st == 1) onode[nd->leaf_id] = i;
         }
+        skey[i] = kb;
+        sidx[i] = i;
+    }
+    bitonic_sort_desc(skey, sidx, P);
+    for (int p = tid; p < P; p += blockDim.x) {
+        const int i = sidx[p];
+        if (i >= n_nodes0) continue;
+        const unsigned long long kb = skey[p];
+        posof[i] = p;
+        int r = -1;
+        if (kb != 0ull) {
+            r = p;
+            while (r > 0 && skey[r - 1] == kb) --r;  // equal gains share a rank
+        }
+        rankof[i] = r;
+    }
+    __syncthreads();
+    for (int l = tid; l < leaves0; l += blockDim.x) {
+        const int r = rankof[onode[l]];
+        okey[l] = r >= 0 ? replay_key(r, l) : 0u;
     }
     __syncthreads();
 
     if (tid < 64) {
-        // Replay of the best-first order by one wavefront, LDS and registers only.  A positive
-        // double orders like its bit pattern, so the largest gain (ties: lowest leaf id) is found
-        // by three wavefront-wide maxima: high word, low word among the high word's winners,
-        // complemented leaf id among those.
-        const int commits0 = step->n_commits, leaves0 = step->n_leaves;
-        int n_commits = commits0, n_leaves = leaves0, n_open = s_nopen;
+        int n_commits = commits0, n_leaves = leaves0;
         for (;;) {
             if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
-            if (n_open <= 0) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
-            uint32_t bh = 0, bl = 0, bd = 0xffffffffu;
-            int bp = -1;
-            for (int p = tid; p < n_open; p += 64) {
-                const uint32_t h = o_hi[p], l = o_lo[p], d = o_lid[p];
-                if (bp < 0 || h > bh || (h == bh && (l > bl || (l == bl && d < bd)))) { bh = h; bl = l; bd = d; bp = p; }
-            }
-            const uint32_t mh = wave_max_u32(bp >= 0 ? bh : 0u);
-            const bool in1 = bp >= 0 && bh == mh;
-            const uint32_t ml = wave_max_u32(in1 ? bl : 0u);
-            const bool in2 = in1 && bl == ml;
-            const uint32_t md = ~wave_max_u32(in2 ? ~bd : 0u);
-            const unsigned long long win = __ballot(in2 && bd == md);
-            const int wl = __ffsll((long long)win) - 1;
-            const int wp = __builtin_amdgcn_readlane(bp, wl);
-            const int bi = o_node[wp];
+            uint32_t m = 0u;
+            for (int l = tid; l < n_leaves; l += 64) m = max(m, okey[l]);
+            m = wave_max_u32(m);
+            if (m == 0u) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
+            const int wl = 0xffff - (int)(m & 0xffffu);
+            const int bi = onode[wl];
             const int c0 = child[bi];
             if (c0 < 0) break;  // the next split is not known yet
-            // commit: the node leaves the queue, its children enter (left keeps the leaf id)
-            const double k0 = key[c0], k1 = key[c0 + 1];
-            const int add0 = k0 > 0.0, add1 = k1 > 0.0;
+            // commit: the left child takes the leaf's place, the right child the next leaf id
+            const int r0 = rankof[c0], r1 = rankof[c0 + 1];
             if (tid == 0) {
                 commit[n_commits - commits0] = bi;
-                key[bi] = -1.0;
-                lid[c0] = (int)md; lid[c0 + 1] = n_leaves;
-                const int last = n_open - 1;
-                o_node[wp] = o_node[last]; o_hi[wp] = o_hi[last]; o_lo[wp] = o_lo[last]; o_lid[wp] = o_lid[last];
-                int no = last;
-                if (add0) {
-                    o_node[no] = c0; o_hi[no] = (uint32_t)__double2hiint(k0); o_lo[no] = (uint32_t)__double2loint(k0);
-                    o_lid[no] = md; ++no;
-                }
-                if (add1) {
-                    o_node[no] = c0 + 1; o_hi[no] = (uint32_t)__double2hiint(k1); o_lo[no] = (uint32_t)__double2loint(k1);
-                    o_lid[no] = (uint32_t)n_leaves; ++no;
-                }
+                commit_lid[n_commits - commits0] = wl;
+                okey[wl] = r0 >= 0 ? replay_key(r0, wl) : 0u;
+                onode[wl] = c0;
+                okey[n_leaves] = r1 >= 0 ? replay_key(r1, n_leaves) : 0u;
+                onode[n_leaves] = c0 + 1;
             }
-            n_open += add0 + add1 - 1;
             n_commits += 1; n_leaves += 1;
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         }
         if (tid == 0) {
-            s_ncommit = n_commits - commits0; s_commits0 = commits0; s_leaves0 = leaves0; s_nopen = n_open;
+            s_ncommit = n_commits - commits0; s_commits0 = commits0; s_leaves0 = leaves0; s_nleaves = n_leaves;
             step->n_commits = n_commits; step->n_leaves = n_leaves;
         }
     }
     __syncthreads();
     // outputs and node states of the splits committed above
-    for (int c = tid; c < s_ncommit; c += blockDim.x) {
-        const int i = commit[c], k = s_commits0 + c;
+    const int n_commit = s_ncommit;
+    for (int c = tid; c < n_commit; c += blockDim.x) {
+        const int i = commit[c], k = commits0 + c;
         const Node nd = nodes[i];
-        out.t.split_leaf[k] = lid[i]; out.t.split_feature[k] = nd.best.feature; out.t.split_bin[k] = nd.best.bin;
+        out.t.split_leaf[k] = commit_lid[c]; out.t.split_feature[k] = nd.best.feature; out.t.split_bin[k] = nd.best.bin;
         out.t.split_gain[k] = nd.best.gain;
         out.t.split_stats[4 * k + 0] = nd.best.left_g; out.t.split_stats[4 * k + 1] = nd.best.left_h;
         out.t.split_stats[4 * k + 2] = nd.best.right_g; out.t.split_stats[4 * k + 3] = nd.best.right_h;
         out.t.split_n_left[k] = nd.n_left;
         const int64_t nl = nd.n_left, nr = nd.count - nd.n_left;
         atomicAdd(&s_units, (unsigned long long)((nl <= nr ? nl : nr) * (int64_t)F));
-        nodes[nd.child].state = 1; nodes[nd.child].leaf_id = lid[nd.child];
-        nodes[nd.child + 1].state = 1; nodes[nd.child + 1].leaf_id = lid[nd.child + 1];
+        nodes[nd.child].state = 1; nodes[nd.child].leaf_id = commit_lid[c];
+        nodes[nd.child + 1].state = 1; nodes[nd.child + 1].leaf_id = leaves0 + c;
     }
     __syncthreads();  // a child may itself have been committed in this call: "internal" is written last
-    for (int c = tid; c < s_ncommit; c += blockDim.x) nodes[commit[c]].state = 2;
+    for (int c = tid; c < n_commit; c += blockDim.x) nodes[commit[c]].state = 2;
     if (tid == 0) step->hist_units += (int64_t)s_units;
-    __syncthreads();
     if (s_done) {
         if (tid == 0) {
             step->done = 1; step->n_batch = 0; step->n_part_items = 0; step->n_scan_items = 0;
@@ -222,80 +276,63 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         }
         return;
     }
-    // batch: the open, not yet expanded leaves with the largest gains.  One expansion is
-    // certain (the leaf the replay stopped at); slots beyond those that the remaining certain
-    // expansions will need may be spent on speculation.
-    const int remaining = (num_leaves - 1) - step->n_commits;
-    const int spare = (max_expand - step->n_expanded) - remaining;
+    // Batch.  One expansion is certain (the leaf the replay stopped at); expansions beyond those
+    // that the remaining certain ones will need may be spent on speculation.
+    const int remaining = (num_leaves - 1) - (commits0 + n_commit);
+    const int n_expanded0 = step->n_expanded;
+    const int spare = (max_expand - n_expanded0) - remaining;
     int want = 1 + (spare > 0 ? spare : 0);
     if (want > remaining) want = remaining;
     if (want > batch_max) want = batch_max;
-    // Candidates: open leaves that are not expanded yet (class 0: the leaf the replay stopped at is
-    // the best of them) and, one level ahead, the not yet expanded children of expanded open leaves
-    // (class 1; encoded as -1-node).  A node's rows outlive the expansion of its children, so
-    // expanding the children of a leaf whose split is not committed yet is safe.
-    for (int p = tid; p < s_nopen; p += blockDim.x) {
-        const int i = o_node[p];
+    // Candidates, marked at their sorted positions: open leaves that are not expanded yet (class 0:
+    // the leaf the replay stopped at is the best of them) and, one level ahead, the not yet
+    // expanded children of expanded open leaves (class 1).  A node's rows outlive the expansion of
+    // its children, so expanding the children of a leaf whose split is not committed yet is safe.
+    // flag: 1 = committed in this call, 1<<16 = class 0 candidate;  flag2: class (1 or 2), 0 none.
+    for (int p = tid; p < P; p += blockDim.x) { flag[p] = 0; flag2[p] = 0; }
+    __syncthreads();
+    for (int c = tid; c < n_commit; c += blockDim.x) flag[posof[commit[c]]] = 1;
+    const int n_leaves_now = s_nleaves;
+    for (int l = tid; l < n_leaves_now; l += blockDim.x) {
+        if (okey[l] == 0u) continue;
+        const int i = onode[l];
         const int c0 = child[i];
         if (c0 < 0) {
-            cand[atomicAdd(&s_ncand, 1)] = i;
+            const int p = posof[i];
+            flag[p] = 1 << 16; flag2[p] = 1;
         } else {
-            if (key[c0] > 0.0 && child[c0] < 0) cand[atomicAdd(&s_ncand, 1)] = -1 - c0;
-            if (key[c0 + 1] > 0.0 && child[c0 + 1] < 0) cand[atomicAdd(&s_ncand, 1)] = -1 - (c0 + 1);
+            if (rankof[c0] >= 0 && child[c0] < 0) flag2[posof[c0]] = 2;
+            if (rankof[c0 + 1] >= 0 && child[c0 + 1] < 0) flag2[posof[c0 + 1]] = 2;
         }
     }
     __syncthreads();
-    const int nc = s_ncand;
-    // Rank of every candidate's gain among all nodes that may still be committed (every known,
-    // not committed node with a gain > 0; ties by node id).  A candidate that already has
-    // `remaining` better nodes in front of it is not worth expanding yet.  Four threads share
-    // one candidate's pass over the nodes.
-    int* crank = cand + 3 * num_leaves;  // [3*num_leaves]
-    for (int c = tid; c < nc; c += blockDim.x) crank[c] = 0;
-    __syncthreads();
-    for (int w = tid; w < 4 * nc; w += blockDim.x) {
-        const int c = w >> 2, part = w & 3;
-        const int e = cand[c];
-        const int i = e < 0 ? -1 - e : e;
-        const double g = key[i];
-        int r = 0;
-        for (int j = part; j < n_nodes0; j += 4) {
-            const double go = key[j];
-            r += (go > g || (go == g && j < i)) ? 1 : 0;
+    // prefix over sorted positions: nodes committed in this call and class-0 candidates in front
+    block_scan_array(flag, P, s_tmp);
+    // A candidate is worth expanding if fewer than `remaining` nodes that can still be committed
+    // have a larger gain; the best class-0 candidate always is.
+    for (int p = tid; p < P; p += blockDim.x) {
+        const int cls = flag2[p];
+        int v = 0;
+        if (cls) {
+            const int before = flag[p];
+            const int rank_now = p - (before & 0xffff);
+            const bool pass = rank_now < remaining || (cls == 1 && (before >> 16) == 0);
+            if (pass) v = (cls == 1) ? 1 : (1 << 16);
         }
-        atomicAdd(&crank[c], r);
+        flag2[p] = v;
     }
     __syncthreads();
-    // order of the batch: class 0 first, then class 1, each by rank; the best class-0 candidate
-    // (the leaf the replay stopped at) always passes the filter
-    int* posbuf = crank + 3 * num_leaves;  // [3*num_leaves + 2] node per position, -1 = filtered out
-    for (int c = tid; c < nc; c += blockDim.x) {
-        const int e = cand[c];
-        const int cls = e < 0 ? 1 : 0;
-        const int rk = crank[c];
-        int pos = 0, better0 = 0;
-        for (int j = 0; j < nc; ++j) {
-            const int cj = cand[j] < 0 ? 1 : 0, rj = crank[j];
-            pos += ((cj < cls) || (cj == cls && rj < rk)) ? 1 : 0;
-            better0 += (cj == 0 && rj < rk) ? 1 : 0;
-        }
-        const bool pass = (cls == 0 && better0 == 0) || rk < remaining;
-        posbuf[pos] = pass ? (e < 0 ? -1 - e : e) : -1;
-    }
+    for (int p = tid; p < P; p += blockDim.x) flag[p] = flag2[p];
     __syncthreads();
-    // compaction of the passing candidates in position order (two positions per thread)
-    const int p0 = 2 * tid, p1 = 2 * tid + 1;
-    const int f0 = (p0 < nc && posbuf[p0] >= 0) ? 1 : 0, f1 = (p1 < nc && posbuf[p1] >= 0) ? 1 : 0;
-    const int pincl = block_scan_incl(f0 + f1, s_tmp);
-    __shared__ int s_npass;
-    if (tid == (int)blockDim.x - 1) s_npass = pincl;
-    __syncthreads();
-    const int n_pass = s_npass;
+    const int totals = block_scan_array(flag, P, s_tmp);
+    const int n0 = totals & 0xffff, n_pass = n0 + (totals >> 16);
     const int n_batch = n_pass < want ? n_pass : want;
-    {
-        int o = pincl - (f0 + f1);
-        if (f0) { if (o < n_batch) batch[o].node = posbuf[p0]; ++o; }
-        if (f1) { if (o < n_batch) batch[o].node = posbuf[p1]; }
+    // order of the batch: class 0 by gain, then class 1 by gain
+    for (int p = tid; p < P; p += blockDim.x) {
+        const int v = flag2[p];
+        if (!v) continue;
+        const int o = (v & 0xffff) ? (flag[p] & 0xffff) : n0 + (flag[p] >> 16);
+        if (o < n_batch) batch[o].node = sidx[p];
     }
     __syncthreads();
     __threadfence_block();
@@ -314,18 +351,12 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         scan_counters[2 * tid] = 0; scan_counters[2 * tid + 1] = 0;
     }
     if (tid == n_batch - 1) step->n_part_items = incl;
-    {   // diagnostics: rows partitioned in this round
-        int rows_k = 0;
-        if (tid < n_batch) rows_k = (int)((nodes[batch[tid].node].count + 1023) >> 10);
-        const int tot = block_scan_incl(rows_k, s_tmp);
-        if (tid == (int)blockDim.x - 1 && step->rounds < 96) { step->round_rows[step->rounds] = (int64_t)tot << 10; step->round_batch[step->rounds] = n_batch; }
-    }
     __syncthreads();
     if (tid == 0) {
         step->n_batch = n_batch;
         step->n_nodes = n_nodes + 2 * n_batch;
         step->n_slots = n_slots + n_batch;
-        step->n_expanded += n_batch;
+        step->n_expanded = n_expanded0 + n_batch;
         step->rounds += 1;
         step->n_scan_items = 2 * n_batch;
     }
@@ -493,8 +524,16 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    const size_t plan_lds = (size_t)ctx->max_nodes * (sizeof(double) + 2 * sizeof(int)) +
-                            (size_t)(14 * p->num_leaves + 24) * sizeof(int) + 64;
+    int p_max = 64;
+    while (p_max < ctx->max_nodes) p_max <<= 1;
+    const size_t plan_lds = (size_t)p_max * (sizeof(unsigned long long) + sizeof(int)) +
+                            (size_t)ctx->max_nodes * 3 * sizeof(int) + (size_t)(4 * p->num_leaves + 8) * sizeof(int);
+    if (plan_lds > 160 * 1024)
+        return set_error(ctx, QGBDT_E_UNSUPPORTED, "max_leaves=%d needs %zu bytes of LDS for the growth bookkeeping (limit 160 KB)",
+                         ctx->shape.max_leaves, plan_lds);
+    if (plan_lds > 48 * 1024)
+        QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(tree_plan_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan_lds));
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
@@ -502,7 +541,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         for (int r = 0; r < to_launch; ++r) {
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                                ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
-                               ctx->max_expand, out);
+                               ctx->max_expand, p_max, out);
             rc = launch_batch_partition_count(ctx, rows);
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
@@ -521,7 +560,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         // one more plan: commits what the last round made known and tells whether the tree is finished
         hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                            ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
-                           ctx->max_expand, out);
+                           ctx->max_expand, p_max, out);
         QG_HIP(ctx, hipGetLastError());
         QG_HIP(ctx, hipMemcpyAsync(ctx->host_state, ctx->step, sizeof(StepState), hipMemcpyDeviceToHost, ctx->stream));
         QG_HIP(ctx, hipStreamSynchronize(ctx->stream));

@@ -299,6 +299,25 @@ def test_grow_tree_cfg5_reduced_ranking():
     _lockstep(cfg, 60_000, cfg.n_features, 2, 127)
 
 
+def test_grow_tree_cfg5_full_leaf_budget():
+    # 511 leaves: the growth bookkeeping needs more than 64 KB of LDS
+    cfg = workloads.CONFIGS[4]
+    _lockstep(cfg, 150_000, 40, 1, 511)
+
+
+def test_quantize_unaligned_pointers():
+    # g, h that do not start on a 16-byte boundary take the scalar kernels
+    N = 70_001
+    rng = np.random.default_rng(11)
+    g = rng.normal(size=N + 1).astype(np.float32); h = rng.random(N + 1).astype(np.float32)
+    ctx = _ctx(N, 8, 32)
+    dg = torch.from_numpy(g).cuda(); dh = torch.from_numpy(h).cuda()
+    gh, delta = ctx.quantize_gradients(dg[1:], dh[1:], 4, 3, 5, 2)
+    gq, hq, d = oracle.quantize_gradients(g[1:], h[1:], 4, 3, 5, 2)
+    assert np.array_equal(delta.cpu().numpy(), d)
+    assert np.array_equal(gh.cpu().numpy(), _pack_gh(gq, hq))
+
+
 def test_grow_tree_degenerate_cases():
     N, F, nb = 3000, 8, 32
     rng = np.random.default_rng(4)
