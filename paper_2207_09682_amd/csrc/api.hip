@@ -52,7 +52,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
                     c->idx[2], c->gh, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
-                    c->absmax, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
+                    c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
     for (void* p : ptrs)
@@ -133,7 +133,8 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->part_counts, (size_t)PART_GROUPS);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_counts, (size_t)c->max_seg);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_prefix, (size_t)c->max_seg + 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->absmax, 2);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->absmax_part, (size_t)2 * QUANT_PARTS);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals_part, (size_t)3 * QUANT_PARTS);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals, 4);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->delta, 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->nodes, (size_t)c->max_nodes);

@@ -160,7 +160,8 @@ struct qgbdt_ctx {
     int64_t* part_counts;  // [PART_GROUPS] (stand-alone partition)
     int32_t* seg_counts;   // [max_seg] left rows per partition segment
     int32_t* seg_prefix;   // [max_seg + 1]
-    uint32_t* absmax;      // [2] float bits
+    float* absmax_part;    // [QUANT_PARTS][2] per-workgroup max|g|, max h
+    int64_t* qtotals_part; // [QUANT_PARTS][3] per-workgroup quantized totals
     int64_t* qtotals;      // [3] sum g~, sum h~, sum |g~|
     float* delta;          // [2]
     qgbdt::Node* nodes;          // [max_nodes]
@@ -187,6 +188,7 @@ namespace qgbdt {
 
 constexpr int PART_GROUPS = 512;
 constexpr int REFIT_PARTS = 32;
+constexpr int QUANT_PARTS = 2048;  // most workgroups of the quantizer kernels
 constexpr int PART_SEG = 1024;  // rows per partition segment of the batched partition
 
 int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...);

@@ -20,18 +20,14 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     o0 = c0; o1 = c1;
 }
 
-__global__ void absmax_init_kernel(uint32_t* absmax, int64_t* totals) {
-    if (threadIdx.x < 2) absmax[threadIdx.x] = 0u;
-    if (threadIdx.x < 3) totals[threadIdx.x] = 0;
-}
-
-// max|g| and max(h, 0) over all rows.  Non-negative floats order like their bit
-// patterns, so the grid-wide maximum is one unsigned atomicMax per workgroup.
+// max|g| and max(h, 0) over all rows: every workgroup writes its pair of maxima, the
+// quantizer's workgroups reduce those (atomics on one address cost ~20 ns each at the
+// memory side, more than the whole stream for a few thousand workgroups).
 // VEC: four rows per thread and step through 16-byte loads (g, h 16-byte aligned);
 // the last n % 4 rows are taken one by one.
 template <bool VEC>
 __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ g, const float* __restrict__ h,
-                                                     int64_t n, uint32_t* absmax) {
+                                                     int64_t n, float* __restrict__ part /*[gridDim.x][2]*/) {
     float mg = 0.0f, mh = 0.0f;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -70,9 +66,28 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ g
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int k = 1; k < 4; ++k) { mg = fmaxf(mg, sg[k]); mh = fmaxf(mh, sh[k]); }
-        atomicMax(&absmax[0], __float_as_uint(mg));
-        atomicMax(&absmax[1], __float_as_uint(mh));
+        part[2 * blockIdx.x] = mg;
+        part[2 * blockIdx.x + 1] = mh;
     }
+}
+
+// Maxima over the partial maxima of absmax_kernel, by every thread of a 256-thread workgroup.
+__device__ __forceinline__ void reduce_absmax(const float* __restrict__ part, int n_part, float& mg, float& mh) {
+    mg = 0.0f; mh = 0.0f;
+    for (int i = threadIdx.x; i < n_part; i += blockDim.x) {
+        mg = fmaxf(mg, part[2 * i]);
+        mh = fmaxf(mh, part[2 * i + 1]);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        mg = fmaxf(mg, __shfl_xor(mg, o));
+        mh = fmaxf(mh, __shfl_xor(mh, o));
+    }
+    __shared__ float rg[4], rh[4];
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { rg[w] = mg; rh[w] = mh; }
+    __syncthreads();
+    mg = fmaxf(fmaxf(rg[0], rg[1]), fmaxf(rg[2], rg[3]));
+    mh = fmaxf(fmaxf(rh[0], rh[1]), fmaxf(rh[2], rh[3]));
 }
 
 __device__ __forceinline__ int round_one(float v, float d, int lo, int hi, uint32_t rnd, int rounding) {
@@ -106,13 +121,15 @@ __device__ __forceinline__ int quantize_row(float gv, float hv, int64_t row, flo
 
 template <bool VEC>
 __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ g, const float* __restrict__ h,
-                                                       int64_t n, const uint32_t* __restrict__ absmax, int kg,
-                                                       int kh, uint32_t seed_lo, uint32_t seed_hi,
-                                                       uint32_t iteration, int rounding,
+                                                       int64_t n, const float* __restrict__ absmax_part,
+                                                       int n_part, int kg, int kh, uint32_t seed_lo,
+                                                       uint32_t seed_hi, uint32_t iteration, int rounding,
                                                        int16_t* __restrict__ gh, float* delta_out,
-                                                       int64_t* totals) {
-    const float dg = __uint_as_float(absmax[0]) / (float)kg;
-    const float dh = __uint_as_float(absmax[1]) / (float)kh;
+                                                       int64_t* __restrict__ totals_part /*[gridDim.x][3]*/) {
+    float mg, mh;
+    reduce_absmax(absmax_part, n_part, mg, mh);
+    const float dg = mg / (float)kg;
+    const float dh = mh / (float)kh;
     if (blockIdx.x == 0 && threadIdx.x == 0) { delta_out[0] = dg; delta_out[1] = dh; }
     int64_t sg = 0, sh = 0, sa = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -137,23 +154,34 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
         for (int64_t i = t0; i < n; i += stride)
             gh[i] = (int16_t)quantize_row(g[i], h[i], i, dg, dh, kg, kh, seed_lo, seed_hi, iteration, rounding, sg, sh, sa);
     }
-    if (totals) {
-        for (int o = 32; o > 0; o >>= 1) {
-            sg += __shfl_xor(sg, o);
-            sh += __shfl_xor(sh, o);
-            sa += __shfl_xor(sa, o);
-        }
-        __shared__ int64_t tg[4], th[4], ta[4];
-        const int w = threadIdx.x >> 6;
-        if ((threadIdx.x & 63) == 0) { tg[w] = sg; th[w] = sh; ta[w] = sa; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int k = 1; k < 4; ++k) { sg += tg[k]; sh += th[k]; sa += ta[k]; }
-            atomicAdd((unsigned long long*)&totals[0], (unsigned long long)sg);
-            atomicAdd((unsigned long long*)&totals[1], (unsigned long long)sh);
-            atomicAdd((unsigned long long*)&totals[2], (unsigned long long)sa);
-        }
+    for (int o = 32; o > 0; o >>= 1) {
+        sg += __shfl_xor(sg, o);
+        sh += __shfl_xor(sh, o);
+        sa += __shfl_xor(sa, o);
     }
+    __shared__ int64_t tg[4], th[4], ta[4];
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { tg[w] = sg; th[w] = sh; ta[w] = sa; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k) { sg += tg[k]; sh += th[k]; sa += ta[k]; }
+        totals_part[3 * blockIdx.x] = sg; totals_part[3 * blockIdx.x + 1] = sh; totals_part[3 * blockIdx.x + 2] = sa;
+    }
+}
+
+// Sums the workgroups' partial totals: sum g~, sum h~, sum |g~|.
+__global__ __launch_bounds__(256) void quantize_totals_kernel(const int64_t* __restrict__ part, int n_part,
+                                                              int64_t* totals) {
+    int64_t s[3] = {0, 0, 0};
+    for (int i = threadIdx.x; i < n_part; i += blockDim.x)
+        for (int k = 0; k < 3; ++k) s[k] += part[3 * i + k];
+    __shared__ int64_t t[3][4];
+    for (int k = 0; k < 3; ++k) {
+        for (int o = 32; o > 0; o >>= 1) s[k] += __shfl_xor(s[k], o);
+        if ((threadIdx.x & 63) == 0) t[k][threadIdx.x >> 6] = s[k];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) totals[threadIdx.x] = t[threadIdx.x][0] + t[threadIdx.x][1] + t[threadIdx.x][2] + t[threadIdx.x][3];
 }
 
 int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int bits_g, int bits_h,
@@ -161,20 +189,22 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
                     int64_t* totals_out) {
     const int kg = (1 << (bits_g - 1)) - 1, kh = (1 << bits_h) - 2;
     int64_t* totals = totals_out ? totals_out : ctx->qtotals;
-    hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->absmax, totals);
     const bool vec = (((uintptr_t)g | (uintptr_t)h) & 15) == 0 && ((uintptr_t)gh & 7) == 0;
     int blocks = (int)(((vec ? (n + 3) / 4 : n) + 255) / 256);
-    if (blocks > 4096) blocks = 4096;
+    if (blocks > QUANT_PARTS) blocks = QUANT_PARTS;
     if (blocks < 1) blocks = 1;
     if (vec) {
-        hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax);
-        hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax, kg, kh,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out, totals);
+        hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part);
+        hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part,
+                           blocks, kg, kh, (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out,
+                           ctx->qtotals_part);
     } else {
-        hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax);
-        hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax, kg,
-                           kh, (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out, totals);
+        hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part);
+        hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part,
+                           blocks, kg, kh, (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out,
+                           ctx->qtotals_part);
     }
+    hipLaunchKernelGGL(quantize_totals_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->qtotals_part, blocks, totals);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
