@@ -231,7 +231,9 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
     __shared__ int s_dpos[PART_SEG];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int dpr = F / 4;
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // Segments are taken from the last to the first: the count kernel has just streamed the same
+    // rows front to back, so the tail of that stream is what the memory-side cache still holds.
+    for (int item = n_items - 1 - (int)blockIdx.x; item >= 0; item -= (int)gridDim.x) {
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
         const int cbuf = child_buffer(nd.buf);
