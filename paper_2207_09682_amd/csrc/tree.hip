@@ -372,14 +372,30 @@ __global__ __launch_bounds__(1024) void tree_mid_kernel(StepState* step, Node* n
     __shared__ int s_tmp[16];
     const int tid = threadIdx.x;
     const int n_items = step->n_part_items, n_batch = step->n_batch;
-    // prefix over all segments: every thread owns a contiguous run
+    // prefix over all segments: every thread owns a contiguous run (loaded in blocks of eight
+    // independent loads: one dependent load per segment would cost a memory latency each)
     const int per = (n_items + blockDim.x - 1) / blockDim.x;
     const int a = min(tid * per, n_items), b = min(a + per, n_items);
     int local = 0;
-    for (int i = a; i < b; ++i) local += seg_counts[i];
+    for (int i0 = a; i0 < b; i0 += 8) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (i0 + u < b) ? seg_counts[i0 + u] : 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) local += v[u];
+    }
     const int incl = block_scan_incl(local, s_tmp);
     int run = incl - local;
-    for (int i = a; i < b; ++i) { seg_prefix[i] = run; run += seg_counts[i]; }
+    for (int i0 = a; i0 < b; i0 += 8) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (i0 + u < b) ? seg_counts[i0 + u] : 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (i0 + u < b) seg_prefix[i0 + u] = run;
+            run += v[u];
+        }
+    }
     if (tid == (int)blockDim.x - 1) seg_prefix[n_items] = incl;
     __syncthreads();
     __threadfence_block();
