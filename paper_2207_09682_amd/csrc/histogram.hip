@@ -19,11 +19,19 @@
 // so the LDS bank is the feature; the order in which a lane issues the atomics of
 // the four features of a dword is rotated per row so that lanes of one instruction
 // spread over the features.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace qgbdt {
+
+// Workgroup size of the histogram kernels, and the wavefronts per SIMD their register
+// budgets are sized for (second launch-bound: 4 -> at most 128 VGPRs, 8 -> at most 64).
+constexpr int HIST_THREADS = 512;
+#ifndef QG_HK_WAVES
+#define QG_HK_WAVES 4
+#endif
+#ifndef QG_HF_WAVES
+#define QG_HF_WAVES 4
+#endif
 
 __global__ void fill_zero_kernel(int64_t* p, int64_t n) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -84,14 +92,35 @@ __device__ __forceinline__ void count_profile(const HistEntry* __restrict__ entr
     step->prof_builds += n_entries;
 }
 
+// Workgroup -> (feature tile, row-group lane) for launches with several feature tiles.  The
+// hardware deals consecutive workgroups round-robin to the 8 XCDs (each with its own L2), so
+// the T workgroups that read the T tiles of the same rows are made consecutive *within one
+// XCD*: they then run at about the same time behind the same L2, every cache line of a row is
+// fetched once, and a DRAM page is swept once instead of once per tile.
+__device__ __forceinline__ void tile_and_lane(int n_tiles, int& tile, int& glane) {
+    const int id = blockIdx.x;
+    const int xcd = id & 7, s = id >> 3;
+    tile = s % n_tiles;
+    glane = (s / n_tiles) * 8 + xcd;
+}
+
 // Merge of the local bins into the total histogram and reset of the local bins.
 // Both are [bin][feature], so LDS is walked linearly (no bank conflicts) and the
 // atomics of a wavefront fall into consecutive words.
+// Column of a tile's local bins -> feature of the tile when the layout keeps 4 unused words
+// after every 16 features (-1: padding).
+__device__ __forceinline__ int unpad16(int col) {
+    const int g = col / 20, o = col - 20 * g;
+    return o < 16 ? 16 * g + o : -1;
+}
+
 template <int W>
 __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_words, int ftp, int ft, int f0, int F,
-                                            int64_t* hist) {
+                                            int64_t* hist, bool pad16 = false) {
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
-        const int b = w / ftp, f = w - b * ftp;
+        const int b = w / ftp;
+        int f = w - b * ftp;
+        if (pad16) { f = unpad16(f); if (f < 0) continue; }
         const typename Acc<W>::word v = lds[w];
         if (v != 0 && f < ft) {
             lds[w] = 0;
@@ -132,7 +161,7 @@ __device__ __forceinline__ void store_partial(typename Acc<W>::word* lds, int ld
 // cost ~5 VALU instructions: one bit-field extract and one 24-bit multiply-add
 // into the byte address of its LDS word, plus its share of the per-row work.
 template <int W, bool IDX, int U>
-__global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
+__global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
                                                     unsigned char* partials, int F, int nb, HistPlan plan,
@@ -142,10 +171,13 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
     word* lds = reinterpret_cast<word*>(lds_raw);
 
     const int n_entries = table_counts[0], n_items = table_counts[1];
-    if ((int)blockIdx.x >= n_items) return;
-    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) count_profile(entries, n_entries, IDX, step);
+    int tile, glane;
+    tile_and_lane(plan.n_tiles, tile, glane);
+    const int n_lanes = (int)gridDim.x / plan.n_tiles;  // row-group lanes (a multiple of 8)
+    if (glane >= n_items) return;
+    if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, IDX, step);
 
-    const int f0 = blockIdx.y * plan.ft;
+    const int f0 = tile * plan.ft;
     const int ft = min(plan.ft, F - f0);
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
@@ -164,18 +196,18 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
     for (int k = 0; k < 4; ++k) {
         const int c = (k + rot) & 3;
         sh[k] = 8 * c;
-        fl4[k] = (uint32_t)(4 * q + c) * (uint32_t)sizeof(word);
+        fl4[k] = (uint32_t)(4 * q + c + (plan.pad16 ? 4 * (q >> 2) : 0)) * (uint32_t)sizeof(word);
     }
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);  // LDS bytes per bin row
     const int S = U * rpi;                                          // rows per block of one wavefront
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    for (int item = glane; item < n_items; item += n_lanes) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
         const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        unsigned char* slot = partials + ((size_t)item * gridDim.y + blockIdx.y) * (size_t)plan.slot_bytes;
+        unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
@@ -240,7 +272,136 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
-            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.pad16 != 0);
+        }
+    }
+}
+
+// Wide rows (F a multiple of 16, several feature tiles, 16-byte aligned matrix): like hist_kernel,
+// but a lane reads 16 bytes -- lane -> (row r of the iteration, 16-byte piece c of the tile row) --
+// so a wavefront instruction brings 1 KB, four times the bytes in flight per register-resident
+// load and a quarter of the address arithmetic per bin.  Local bins keep 4 unused words after
+// every 16 features (pitch 20 words per piece): piece c then starts at bank 20c mod 32, the
+// pieces of a row tile fall on distinct multiples of 4, and with the per-row byte rotation the
+// 64 lanes of every instruction spread over all 32 banks, two lanes each.
+template <int W, bool IDX, int U>
+__global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource src, IdxSet idxs,
+                                                                    const HistEntry* __restrict__ entries,
+                                                                    const int32_t* __restrict__ table_counts,
+                                                                    int64_t* hist_base, unsigned char* partials, int F,
+                                                                    int nb, HistPlan plan, StepState* step) {
+    using word = typename Acc<W>::word;
+    extern __shared__ unsigned char lds_raw[];
+    word* lds = reinterpret_cast<word*>(lds_raw);
+
+    const int n_entries = table_counts[0], n_items = table_counts[1];
+    int tile, glane;
+    tile_and_lane(plan.n_tiles, tile, glane);
+    const int n_lanes = (int)gridDim.x / plan.n_tiles;
+    if (glane >= n_items) return;
+    if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, IDX, step);
+
+    const int f0 = tile * plan.ft;
+    const int ft = min(plan.ft, F - f0);  // a multiple of 16
+    const int ftp = plan.ftp;
+    const int lds_words = nb * ftp;
+    for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const int P = plan.ft >> 4;  // 16-byte pieces per tile row (a power of two <= 64)
+    const int rpi = 64 / P;      // rows per wavefront instruction
+    int c = lane % P;
+    const int r = lane / P;
+    const bool lane_on = 16 * c < ft;
+    if (!lane_on) c = 0;
+    const int rot = r & 3;
+    uint32_t sh[4], flk[4];  // bit offset of the k-th bin in a dword, byte offset of its column in dword 0 of the piece
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int cc = (k + rot) & 3;
+        sh[k] = 8 * cc;
+        flk[k] = (uint32_t)(20 * c + cc) * (uint32_t)sizeof(word);
+    }
+    const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);
+    const int S = U * rpi;
+
+    for (int item = glane; item < n_items; item += n_lanes) {
+        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
+        const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
+        const int64_t gend = min(en.count, gbegin + rows_per_group);
+        int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
+        unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
+        const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
+        const int sb = IDX ? BUF_ORIGINAL : en.buf;
+        const uint8_t* colbase = src.bins[sb] + f0 + 16 * c;
+        const int16_t* gh = src.gh[sb];
+
+        for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
+            const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
+            const int crow = (int)(cend - cbegin);
+            __syncthreads();
+            const int32_t* ib = IDX ? idx + cbegin : nullptr;
+            const int64_t row_base = IDX ? 0 : en.begin + cbegin;
+            if (wave * S < crow) {
+                // three stages in flight: row ids of block n+2, bin pieces and packed gradients of
+                // block n+1, LDS atomics of block n; rows past the end re-read the last row and add zero
+                int64_t rown[U];
+                uint4 d[U], dn[U];
+                int gv[U], gn[U];
+                {
+                    int64_t rows[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int p = min(wave * S + u * rpi + r, crow - 1);
+                        rows[u] = IDX ? (int64_t)ib[p] : row_base + p;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        d[u] = *reinterpret_cast<const uint4*>(colbase + rows[u] * F);
+                        gv[u] = gh[rows[u]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int p = min((wave + n_waves) * S + u * rpi + r, crow - 1);
+                        rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
+                    }
+                }
+                for (int ro = wave * S; ro < crow; ro += n_waves * S) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        dn[u] = *reinterpret_cast<const uint4*>(colbase + rown[u] * F);
+                        gn[u] = gh[rown[u]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int p = min(ro + 2 * n_waves * S + u * rpi + r, crow - 1);
+                        rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const bool ok = lane_on && (ro + u * rpi + r < crow);
+                        const word v = Acc<W>::expand(ok ? gv[u] : 0);
+                        const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
+                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k]) +
+                                                                    (uint32_t)(4 * i) * (uint32_t)sizeof(word)), v);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) { d[u] = dn[u]; gv[u] = gn[u]; }
+                }
+            }
+            __syncthreads();
+            if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, true);
         }
     }
 }
@@ -252,7 +413,7 @@ __global__ __launch_bounds__(1024) void hist_kernel(RowSource src, IdxSet idxs,
 // whole kernel; they lie in at most two consecutive rows.  Blocks of U iterations
 // are software-pipelined like in hist_kernel.
 template <int W, int U>
-__global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
+__global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(RowSource src,
                                                          const HistEntry* __restrict__ entries,
                                                          const int32_t* __restrict__ table_counts,
                                                          int64_t* hist_base, unsigned char* partials, int F, int nb,
@@ -389,7 +550,7 @@ __global__ __launch_bounds__(1024) void hist_flat_kernel(RowSource src,
 
 // Any feature count (no alignment assumption): one byte load per (row, feature).
 template <int W>
-__global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSet idxs, int use_idx,
+__global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource src, IdxSet idxs, int use_idx,
                                                             const HistEntry* __restrict__ entries,
                                                             const int32_t* __restrict__ table_counts,
                                                             int64_t* hist_base, unsigned char* partials, int F,
@@ -398,20 +559,22 @@ __global__ __launch_bounds__(1024) void hist_generic_kernel(RowSource src, IdxSe
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
     const int n_entries = table_counts[0], n_items = table_counts[1];
-    if ((int)blockIdx.x >= n_items) return;
-    if (step && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
-        count_profile(entries, n_entries, use_idx != 0, step);
-    const int f0 = blockIdx.y * plan.ft;
+    int tile, glane;
+    tile_and_lane(plan.n_tiles, tile, glane);
+    const int n_lanes = (int)gridDim.x / plan.n_tiles;
+    if (glane >= n_items) return;
+    if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, use_idx != 0, step);
+    const int f0 = tile * plan.ft;
     const int ft = min(plan.ft, F - f0);
     const int lds_words = ft * nb;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    for (int item = glane; item < n_items; item += n_lanes) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
         const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
-        unsigned char* slot = partials + ((size_t)item * gridDim.y + blockIdx.y) * (size_t)plan.slot_bytes;
+        unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
         const int32_t* idx = use_idx ? (idxs.p[en.buf] + en.begin) : nullptr;
         const uint8_t* bins = src.bins[use_idx ? BUF_ORIGINAL : en.buf];
         const int16_t* gh = src.gh[use_idx ? BUF_ORIGINAL : en.buf];
@@ -452,8 +615,10 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
     const int ft = min(plan.ft, F - f0);
     const int pitch = generic ? ft : plan.ftp;
     const int w = blockIdx.x * blockDim.x + threadIdx.x;
-    const int b = w / pitch, f = w - b * pitch;
-    if (b >= nb || f >= ft) return;
+    const int b = w / pitch;
+    int f = w - b * pitch;
+    if (!generic && plan.pad16) f = unpad16(f);
+    if (b >= nb || f < 0 || f >= ft) return;
     const size_t stride = (size_t)gridDim.y * (size_t)plan.slot_bytes;  // bytes from one item's slot to the next
     const unsigned char* base = partials + (size_t)blockIdx.y * (size_t)plan.slot_bytes + (size_t)w * sizeof(word);
     const int64_t hoff = (int64_t)b * F + f0 + f;
@@ -504,7 +669,20 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     const int wbytes = (w == 16) ? 4 : 8;
     const int lds_budget = 64 * 1024;
     const bool fast = (F % 4 == 0);
-    if (fast) {
+    int wide_ft = 0;
+    if (F % 16 == 0 && F > 64) {
+        // wide rows: 16-byte pieces, padded local bins (20 words per 16 features)
+        for (int ft = 256; ft >= 32 && !wide_ft; ft >>= 1)
+            if ((int64_t)(ft + ft / 4) * nb * wbytes <= lds_budget) wide_ft = ft;
+    }
+    if (wide_ft) {
+        p.ft = wide_ft;
+        p.ftp = wide_ft + wide_ft / 4;
+        p.pad16 = 1;
+        p.dpr = wide_ft / 4;
+        p.rows_per_it = 64 / p.dpr > 0 ? 64 / p.dpr : 1;
+        p.lds_bytes = p.ftp * nb * wbytes;
+    } else if (fast) {
         // candidates in order of preference: the whole row when it is narrow, then wide tiles
         // (whole cache lines per row), small tiles only when nothing else fits the LDS budget
         const int cands[] = {(F <= 64) ? F : 0, 128, 96, 64, 48, 40, 32, 24, 16, 8, 4};
@@ -542,7 +720,7 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.chunk_rows = (int32_t)((lim > 0x40000000LL) ? 0x40000000LL : lim);
     if (p.chunk_rows < 1) p.chunk_rows = 1;
     p.min_rows_per_group = 2048;
-    p.threads = 512;
+    p.threads = HIST_THREADS;
     int per_cu = (160 * 1024) / (p.lds_bytes > 0 ? p.lds_bytes : 1);
     const int by_waves = 32 / (p.threads / 64);  // 32 wavefronts per CU
     if (per_cu > by_waves) per_cu = by_waves;
@@ -562,11 +740,6 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (p.max_items < 2 * s.max_leaves + 64) p.max_items = 2 * s.max_leaves + 64;
     p.single_rows = p.chunk_rows >= 1024 ? p.chunk_rows - 320 : p.chunk_rows / 2;
     if (p.single_rows < 1) p.single_rows = 1;
-    if (const char* e = getenv("QGBDT_NOFLAT")) { if (atoi(e)) p.flat_lanes = 0; }
-    if (const char* e = getenv("QGBDT_FLAT_U")) p.flat_unroll = atoi(e);
-    if (const char* e = getenv("QGBDT_MAX_GROUPS")) p.max_groups = atoi(e);
-    if (const char* e = getenv("QGBDT_MIN_ROWS")) p.min_rows_per_group = atoi(e);
-    if (const char* e = getenv("QGBDT_THREADS")) p.threads = atoi(e);
     return p;
 }
 
@@ -601,7 +774,9 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     int64_t groups = grid_items;
     if (groups > plan.max_groups) groups = plan.max_groups;
     if (groups < 1) groups = 1;
-    dim3 grid((unsigned)groups, (unsigned)plan.n_tiles), block(plan.threads);
+    // row-group lanes in multiples of 8 (one per XCD), times the feature tiles, as one flat grid
+    const int64_t lanes = (groups + 7) / 8 * 8;
+    dim3 grid((unsigned)(lanes * plan.n_tiles)), block(plan.threads);
     const bool fast = (F % 4 == 0);
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (ctx->profiling && ctx->ev_used + 2 <= ctx->ev_cap) {
@@ -609,6 +784,8 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         QG_HIP(ctx, hipEventRecord(e0, ctx->stream));
     }
     const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_ok;
+    bool wide_ok = true;  // 16-byte loads need 16-byte aligned matrices (F is a multiple of 16 in that mode)
+    for (int b = 0; b < 4; ++b) wide_ok = wide_ok && (((uintptr_t)rows.bins[b] & 15) == 0);
     if (flat) {
 #define QG_LAUNCH_FLAT(W_, U_)                                                                                   \
     hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, entries, \
@@ -623,6 +800,16 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
             else QG_LAUNCH_FLAT(32, 1);
         }
 #undef QG_LAUNCH_FLAT
+    } else if (fast && plan.pad16 && wide_ok) {
+#define QG_LAUNCH_WIDE(W_, IDX_)                                                                                  \
+    hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, 4>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
+                       entries, table_counts, hist_base, partials, F, nb, plan, step)
+        if (plan.acc_width == 16) {
+            if (use_idx) QG_LAUNCH_WIDE(16, true); else QG_LAUNCH_WIDE(16, false);
+        } else {
+            if (use_idx) QG_LAUNCH_WIDE(32, true); else QG_LAUNCH_WIDE(32, false);
+        }
+#undef QG_LAUNCH_WIDE
     } else if (fast) {
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
