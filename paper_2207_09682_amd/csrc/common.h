@@ -98,6 +98,7 @@ struct HistPlan {
     int32_t slot_bytes;   // bytes of one (item, tile) slot: the tile's local bins, padded to 16 bytes
     int32_t single_rows;  // a group of at most this many rows is accumulated in one chunk by every kernel variant
     int32_t pad16;        // local bins keep 4 unused words after every 16 features (wide rows, 16-byte loads)
+    int32_t wide_v;       // > 0: wide rows are read in pieces of this many bytes per lane (8 or 16)
 };
 
 // Rows per row group when `total` rows of `n_entries` builds are shared out: about max_groups

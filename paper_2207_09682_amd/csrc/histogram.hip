@@ -19,6 +19,8 @@
 // so the LDS bank is the feature; the order in which a lane issues the atomics of
 // the four features of a dword is rotated per row so that lanes of one instruction
 // spread over the features.
+#include <type_traits>
+
 #include "common.h"
 
 namespace qgbdt {
@@ -256,14 +258,18 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
                         const int p = min(ro + 2 * n_waves * S + u * rpi + r, crow - 1);
                         rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
                     }
+                    // lanes without a place in the tile sit out (their loads alias lane 0's: atomics on the
+                    // same words would serialize); rows past the end are not branched around, they add zero
+                    if (lane_on) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const bool ok = lane_on && (ro + u * rpi + r < crow);
-                        const word v = Acc<W>::expand(ok ? gv[u] : 0);
+                        for (int u = 0; u < U; ++u) {
+                            const bool ok = ro + u * rpi + r < crow;
+                            const word v = Acc<W>::expand(ok ? gv[u] : 0);
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
-                            Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
+                            for (int k = 0; k < 4; ++k) {
+                                const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
+                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
+                            }
                         }
                     }
 #pragma unroll
@@ -277,20 +283,25 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
     }
 }
 
-// Wide rows (F a multiple of 16, several feature tiles, 16-byte aligned matrix): like hist_kernel,
-// but a lane reads 16 bytes -- lane -> (row r of the iteration, 16-byte piece c of the tile row) --
-// so a wavefront instruction brings 1 KB, four times the bytes in flight per register-resident
-// load and a quarter of the address arithmetic per bin.  Local bins keep 4 unused words after
-// every 16 features (pitch 20 words per piece): piece c then starts at bank 20c mod 32, the
-// pieces of a row tile fall on distinct multiples of 4, and with the per-row byte rotation the
-// 64 lanes of every instruction spread over all 32 banks, two lanes each.
-template <int W, bool IDX, int U>
+// Wide rows (several feature tiles; F and the matrix address multiples of V = 16 or 8 bytes):
+// like hist_kernel, but a lane reads V bytes -- lane -> (row r of the iteration, V-byte piece c
+// of the tile row) -- so a wavefront instruction brings 1 KB (512 B), several times the bytes in
+// flight per register-resident load and a fraction of the address arithmetic per bin.
+//  V = 16: local bins keep 4 unused words after every 16 features (pitch 20 words per piece):
+//          piece c then starts at bank 20c mod 32, the pieces of a tile row fall on distinct
+//          multiples of 4, and with the per-row byte rotation the 64 lanes of every instruction
+//          spread over all 32 banks, two lanes each.
+//  V = 8:  (tiles of at most 64 features, unpadded) half of the rows swap the two dwords of their
+//          piece, which together with the byte rotation spreads an instruction over 32 columns.
+template <int W, bool IDX, int V, int U>
 __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource src, IdxSet idxs,
                                                                     const HistEntry* __restrict__ entries,
                                                                     const int32_t* __restrict__ table_counts,
                                                                     int64_t* hist_base, unsigned char* partials, int F,
                                                                     int nb, HistPlan plan, StepState* step) {
     using word = typename Acc<W>::word;
+    using vec = typename std::conditional<V == 16, uint4, uint2>::type;
+    constexpr int NV = V / 4;  // dwords per lane
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
 
@@ -302,7 +313,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
     if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, IDX, step);
 
     const int f0 = tile * plan.ft;
-    const int ft = min(plan.ft, F - f0);  // a multiple of 16
+    const int ft = min(plan.ft, F - f0);  // a multiple of V
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
@@ -310,20 +321,24 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
-    const int P = plan.ft >> 4;  // 16-byte pieces per tile row (a power of two <= 64)
-    const int rpi = 64 / P;      // rows per wavefront instruction
+    const int P = plan.ft / V;  // pieces per tile row (a power of two <= 64)
+    const int rpi = 64 / P;     // rows per wavefront instruction
     int c = lane % P;
     const int r = lane / P;
-    const bool lane_on = 16 * c < ft;
+    const bool lane_on = V * c < ft;
     if (!lane_on) c = 0;
     const int rot = r & 3;
-    uint32_t sh[4], flk[4];  // bit offset of the k-th bin in a dword, byte offset of its column in dword 0 of the piece
+    const bool swap = (V == 8) && ((r >> 2) & 1);  // this lane handles its two dwords in the other order
+    uint32_t sh[4], flk[4];  // bit offset of the k-th bin in a dword, byte offset of its column for the first dword
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int cc = (k + rot) & 3;
         sh[k] = 8 * cc;
-        flk[k] = (uint32_t)(20 * c + cc) * (uint32_t)sizeof(word);
+        const int col0 = (V == 16) ? 20 * c : 8 * c + (swap ? 4 : 0);
+        flk[k] = (uint32_t)(col0 + cc) * (uint32_t)sizeof(word);
     }
+    // byte offset from the first to the second handled dword's columns (V = 8: -4 columns when swapped)
+    const uint32_t step2 = (uint32_t)((swap ? -4 : 4) * (int)sizeof(word));
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);
     const int S = U * rpi;
 
@@ -336,7 +351,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
         unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
-        const uint8_t* colbase = src.bins[sb] + f0 + 16 * c;
+        const uint8_t* colbase = src.bins[sb] + f0 + V * c;
         const int16_t* gh = src.gh[sb];
 
         for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
@@ -349,7 +364,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
                 // three stages in flight: row ids of block n+2, bin pieces and packed gradients of
                 // block n+1, LDS atomics of block n; rows past the end re-read the last row and add zero
                 int64_t rown[U];
-                uint4 d[U], dn[U];
+                vec d[U], dn[U];
                 int gv[U], gn[U];
                 {
                     int64_t rows[U];
@@ -360,7 +375,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        d[u] = *reinterpret_cast<const uint4*>(colbase + rows[u] * F);
+                        d[u] = *reinterpret_cast<const vec*>(colbase + rows[u] * F);
                         gv[u] = gh[rows[u]];
                     }
 #pragma unroll
@@ -372,7 +387,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
                 for (int ro = wave * S; ro < crow; ro += n_waves * S) {
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        dn[u] = *reinterpret_cast<const uint4*>(colbase + rown[u] * F);
+                        dn[u] = *reinterpret_cast<const vec*>(colbase + rown[u] * F);
                         gn[u] = gh[rown[u]];
                     }
 #pragma unroll
@@ -380,20 +395,27 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
                         const int p = min(ro + 2 * n_waves * S + u * rpi + r, crow - 1);
                         rown[u] = IDX ? (int64_t)ib[p] : row_base + p;
                     }
+                    if (lane_on) {  // lanes beyond the tile's width sit out (their loads alias piece 0)
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const bool ok = lane_on && (ro + u * rpi + r < crow);
+                        const bool ok = ro + u * rpi + r < crow;
                         const word v = Acc<W>::expand(ok ? gv[u] : 0);
-                        const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
+                        uint32_t dw[4];
+                        if constexpr (V == 16) {
+                            dw[0] = d[u].x; dw[1] = d[u].y; dw[2] = d[u].z; dw[3] = d[u].w;
+                        } else {
+                            dw[0] = swap ? d[u].y : d[u].x; dw[1] = swap ? d[u].x : d[u].y; dw[2] = 0; dw[3] = 0;
+                        }
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
+                        for (int i = 0; i < NV; ++i) {
+                            const uint32_t ioff = (V == 16) ? (uint32_t)(4 * i) * (uint32_t)sizeof(word) : (i ? step2 : 0u);
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
-                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k]) +
-                                                                    (uint32_t)(4 * i) * (uint32_t)sizeof(word)), v);
+                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k] + ioff)), v);
                             }
                         }
+                    }
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) { d[u] = dn[u]; gv[u] = gn[u]; }
@@ -401,7 +423,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
-            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, true);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.pad16 != 0);
         }
     }
 }
@@ -504,10 +526,11 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
                         gan[u] = gb[row0 + rA];
                         gbn[u] = gb[row0 + rB];
                     }
+                    if (lane_on) {  // the lanes beyond the last whole row of an iteration sit out
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const word va = Acc<W>::expand(lane_on ? ga[u] : 0);
-                        const word vb = Acc<W>::expand(lane_on ? gbv[u] : 0);
+                        const word va = Acc<W>::expand(ga[u]);
+                        const word vb = Acc<W>::expand(gbv[u]);
                         const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -518,6 +541,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
                                 Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[i][k])), v);
                             }
                         }
+                    }
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) { d[u] = dn[u]; ga[u] = gan[u]; gbv[u] = gbn[u]; }
@@ -674,11 +698,16 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
         // wide rows: 16-byte pieces, padded local bins (20 words per 16 features)
         for (int ft = 256; ft >= 32 && !wide_ft; ft >>= 1)
             if ((int64_t)(ft + ft / 4) * nb * wbytes <= lds_budget) wide_ft = ft;
+        if (wide_ft) { p.wide_v = 16; p.pad16 = 1; }
+    } else if (F % 8 == 0 && F > 64) {
+        // 8-byte pieces, at most 64 features per tile, unpadded
+        for (int ft = 64; ft >= 32 && !wide_ft; ft >>= 1)
+            if ((int64_t)ft * nb * wbytes <= lds_budget) wide_ft = ft;
+        if (wide_ft) p.wide_v = 8;
     }
     if (wide_ft) {
         p.ft = wide_ft;
-        p.ftp = wide_ft + wide_ft / 4;
-        p.pad16 = 1;
+        p.ftp = p.pad16 ? wide_ft + wide_ft / 4 : wide_ft;
         p.dpr = wide_ft / 4;
         p.rows_per_it = 64 / p.dpr > 0 ? 64 / p.dpr : 1;
         p.lds_bytes = p.ftp * nb * wbytes;
@@ -800,15 +829,18 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
             else QG_LAUNCH_FLAT(32, 1);
         }
 #undef QG_LAUNCH_FLAT
-    } else if (fast && plan.pad16 && wide_ok) {
-#define QG_LAUNCH_WIDE(W_, IDX_)                                                                                  \
-    hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, 4>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
+    } else if (fast && plan.wide_v > 0 && wide_ok) {
+#define QG_LAUNCH_WIDE(W_, IDX_, V_, U_)                                                                              \
+    hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
                        entries, table_counts, hist_base, partials, F, nb, plan, step)
+#define QG_LAUNCH_WIDE_V(W_, IDX_) \
+    if (plan.wide_v == 16) QG_LAUNCH_WIDE(W_, IDX_, 16, 4); else QG_LAUNCH_WIDE(W_, IDX_, 8, 4)
         if (plan.acc_width == 16) {
-            if (use_idx) QG_LAUNCH_WIDE(16, true); else QG_LAUNCH_WIDE(16, false);
+            if (use_idx) { QG_LAUNCH_WIDE_V(16, true); } else { QG_LAUNCH_WIDE_V(16, false); }
         } else {
-            if (use_idx) QG_LAUNCH_WIDE(32, true); else QG_LAUNCH_WIDE(32, false);
+            if (use_idx) { QG_LAUNCH_WIDE_V(32, true); } else { QG_LAUNCH_WIDE_V(32, false); }
         }
+#undef QG_LAUNCH_WIDE_V
 #undef QG_LAUNCH_WIDE
     } else if (fast) {
         const int cap = 64 / plan.rows_per_it;
