@@ -194,6 +194,15 @@ def main():
                "library_tree_equals_oracle_tree": bool(c_match)}
 
     achieved = (hist_bytes / hist_launches) / (hist_ms / hist_launches * 1e-3) / 1e9 if hist_launches and hist_ms > 0 else 0.0
+    # HBM bytes per histogram launch from the rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE scaled by a plain
+    # copy; see profiles/): measured offline on this workload, so only reported for it
+    traffic, root_traffic = None, None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg3.json")
+    if args.config == 2 and not args.rows and args.bits == 3 and os.path.exists(tpath):
+        with open(tpath) as fh:
+            tj = json.load(fh)
+        traffic, root_traffic = tj.get("tree_launch_traffic_bytes"), tj.get("root_pass_traffic_bytes")
+    root["traffic"] = root_traffic
     out = {
         "metric": "histogram build rows*features/s over whole trees (quantize+hist+subtract+scan+partition+refit), "
                   f"{bits_g}-bit gradients",
@@ -210,8 +219,8 @@ def main():
                    "acc_width": args.acc_width or "auto", "leaves_last_tree": n_leaves_last,
                    "hist_units_per_tree": total_units / K},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "hist_kernel (all launches of the timed trees)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "histogram build = hist_*_kernel + hist_reduce_kernel (all launches of the timed trees)",
                      "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
                      "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1)},
         "root_pass": root,

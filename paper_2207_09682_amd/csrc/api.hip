@@ -336,9 +336,5 @@ int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4) {
     return QGBDT_OK;
 }
 
-__attribute__((visibility("default"))) int qgbdt_debug_rounds(const qgbdt_ctx* ctx, int64_t* rows96, int32_t* batch96) {
-    for (int i = 0; i < 96; ++i) { rows96[i] = ctx->host_state->round_rows[i]; batch96[i] = ctx->host_state->round_batch[i]; }
-    return 0;
-}
 
 }  // extern "C"

@@ -41,8 +41,6 @@ struct StepState {
     int64_t prof_rows_contig, prof_rows_idx;  // rows seen by histogram launches
     int64_t prof_launches;                    // histogram launches that had rows
     int64_t prof_builds;                      // histogram builds served by those launches
-    int64_t round_rows[96];                   // rows partitioned per round (diagnostics)
-    int32_t round_batch[96];                  // nodes expanded per round (diagnostics)
 };
 
 // One node expanded in the current round.
