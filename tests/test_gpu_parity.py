@@ -245,14 +245,15 @@ def _compare_tree(t, e, N):
     assert int(t.hist_units.item()) == e.hist_units
 
 
-def _lockstep(cfg, N, F, n_trees, num_leaves, acc=0, bits=None):
+def _lockstep(cfg, N, F, n_trees, num_leaves, acc=0, bits=None, device="cpu"):
     """Boosting in lock step: every tree of both sides is grown from the same fp32 g, h
-    (computed from the GPU side's scores), then compared."""
-    wl = workloads.make_workload(cfg, n_rows=N, n_features=F)
+    (computed from the GPU side's scores), then compared.  `device` is where the inputs are
+    generated (the full-size cases generate on the GPU and copy to the host for the oracle)."""
+    wl = workloads.make_workload(cfg, n_rows=N, n_features=F, device=device)
     N = wl.n_rows
     bins_np = workloads.to_numpy(wl.bins)
     dbins = wl.bins.cuda()
-    score = torch.zeros(N)
+    score = torch.zeros(N, device=device)
     ctx = _ctx(N, F, cfg.n_bins, L=num_leaves)
     bg, bh = bits or (cfg.bits_g, cfg.bits_h)
     for it in range(n_trees):
@@ -268,7 +269,7 @@ def _lockstep(cfg, N, F, n_trees, num_leaves, acc=0, bits=None):
         ridx = t.row_idx.cpu().long(); lb = t.leaf_begin.cpu(); lc = t.leaf_count.cpu()
         for l in range(n):
             leaf_of_row[ridx[lb[l]: lb[l] + lc[l]]] = l
-        score = score + cfg.learning_rate * t.leaf_value.cpu()[leaf_of_row].float()
+        score = score + (cfg.learning_rate * t.leaf_value.cpu()[leaf_of_row].float()).to(score.device)
     return ctx
 
 
@@ -297,6 +298,32 @@ def test_grow_tree_cfg4_reduced_wide():
 def test_grow_tree_cfg5_reduced_ranking():
     cfg = workloads.CONFIGS[4]
     _lockstep(cfg, 60_000, cfg.n_features, 2, 127)
+
+
+# The five configurations at their full sizes, in the launch configuration bench.py times
+# (same context shape, same entry point): whole trees against the oracle, every split, every
+# row position and every leaf.
+
+def test_full_size_cfg2():
+    cfg = workloads.CONFIGS[1]
+    _lockstep(cfg, cfg.n_rows, cfg.n_features, 3, cfg.num_leaves, device="cuda")
+
+
+@pytest.mark.parametrize("bits,acc", [((3, 3), 0), ((2, 2), 16), ((5, 5), 32)])
+def test_full_size_cfg3(bits, acc):
+    cfg = workloads.CONFIGS[2]
+    _lockstep(cfg, cfg.n_rows, cfg.n_features, 2, cfg.num_leaves, acc=acc, bits=bits, device="cuda")
+
+
+def test_full_size_cfg4():
+    cfg = workloads.CONFIGS[3]
+    _lockstep(cfg, cfg.n_rows, cfg.n_features, 2, cfg.num_leaves, device="cuda")
+
+
+def test_full_size_cfg5():
+    cfg = workloads.CONFIGS[4]
+    _lockstep(cfg, cfg.n_rows, cfg.n_features, 1, cfg.num_leaves, device="cuda")
+    torch.cuda.empty_cache()
 
 
 def test_grow_tree_cfg5_full_leaf_budget():
