@@ -751,7 +751,10 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.min_rows_per_group = 2048;
     p.threads = HIST_THREADS;
     int per_cu = (160 * 1024) / (p.lds_bytes > 0 ? p.lds_bytes : 1);
-    const int by_waves = 32 / (p.threads / 64);  // 32 wavefronts per CU
+    // one-tile launches: the flat kernel needs ~100 VGPRs, so 16 wavefronts per CU are resident at once and
+    // twice as many row groups would only double the slots to write and reduce; tiled launches measured
+    // better with the groups of 32 wavefronts per CU
+    const int by_waves = (p.n_tiles == 1 ? 16 : 32) / (p.threads / 64);
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
     int groups = (256 * per_cu) / p.n_tiles;
