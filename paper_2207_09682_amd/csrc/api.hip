@@ -51,7 +51,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->gh, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->idx[2], c->gh, c->ghf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -116,6 +116,7 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[2], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->ghf, (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (c->max_expand + 1)));
     if (rc == QGBDT_OK) {
         // slots of the row groups' local bins, for either accumulator width
@@ -197,7 +198,7 @@ int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const float* h, int
         return set_error(ctx, QGBDT_E_INVALID_ARG, "rounding=%d", rounding);
     int rc = check_bits(ctx, bits_g, bits_h);
     if (rc != QGBDT_OK) return rc;
-    return launch_quantize(ctx, g, h, n, bits_g, bits_h, seed, iteration, rounding, gh_out, delta_out, nullptr);
+    return launch_quantize(ctx, g, h, n, bits_g, bits_h, seed, iteration, rounding, gh_out, delta_out, nullptr, nullptr);
 }
 
 int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, const int32_t* row_idx,
@@ -270,7 +271,7 @@ int qgbdt_refit_leaves(qgbdt_ctx* ctx, const float* g, const float* h, const int
         return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
     if (n_leaves < 0 || n_leaves > ctx->shape.max_leaves)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "n_leaves=%d outside 0..max_leaves", n_leaves);
-    return launch_refit(ctx, g, h, row_idx, leaf_begin, leaf_count, n_leaves, nullptr, value_out);
+    return launch_refit(ctx, g, h, nullptr, row_idx, leaf_begin, leaf_count, n_leaves, nullptr, value_out);
 }
 
 int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const float* h, const qgbdt_params* p,

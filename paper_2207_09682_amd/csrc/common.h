@@ -154,6 +154,7 @@ struct qgbdt_ctx {
     int16_t* ogh[3];       // [N] each (ordered mode)
     int32_t* idx[3];       // [N] each
     int16_t* gh;           // [N]
+    float2* ghf;           // [N] (g, h) interleaved, written by the quantizer for the refit's gather
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
     void* hist_partials;   // [max_items][n_tiles] local bins of the row groups, summed by the reduce kernel
     uint8_t* flags;        // [N] partition flags
@@ -204,7 +205,7 @@ int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...);
 // launchers (each defined next to its kernels)
 int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int bits_g, int bits_h,
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
-                    int64_t* totals_out);
+                    int64_t* totals_out, float2* pairs_out);
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
@@ -223,7 +224,7 @@ int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, in
                        int feature, int bin, int64_t* n_left_out);
 int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows);
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows);
-int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
+int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);
 int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const float* h,

@@ -125,7 +125,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
                                                        int n_part, int kg, int kh, uint32_t seed_lo,
                                                        uint32_t seed_hi, uint32_t iteration, int rounding,
                                                        int16_t* __restrict__ gh, float* delta_out,
-                                                       int64_t* __restrict__ totals_part /*[gridDim.x][3]*/) {
+                                                       int64_t* __restrict__ totals_part /*[gridDim.x][3]*/,
+                                                       float2* __restrict__ pairs /*[n] (g, h) interleaved, or null*/) {
     float mg, mh;
     reduce_absmax(absmax_part, n_part, mg, mh);
     const float dg = mg / (float)kg;
@@ -146,13 +147,22 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
             const uint32_t q0 = QG_Q(a.x, b.x, 0), q1 = QG_Q(a.y, b.y, 1), q2 = QG_Q(a.z, b.z, 2), q3 = QG_Q(a.w, b.w, 3);
 #undef QG_Q
             o4[i] = make_uint2(q0 | (q1 << 16), q2 | (q3 << 16));
+            if (pairs) {
+                float4* p4 = reinterpret_cast<float4*>(pairs + r);
+                p4[0] = make_float4(a.x, b.x, a.y, b.y);
+                p4[1] = make_float4(a.z, b.z, a.w, b.w);
+            }
         }
         const int64_t r = (n4 << 2) + t0;
-        if (r < n)
+        if (r < n) {
             gh[r] = (int16_t)quantize_row(g[r], h[r], r, dg, dh, kg, kh, seed_lo, seed_hi, iteration, rounding, sg, sh, sa);
+            if (pairs) pairs[r] = make_float2(g[r], h[r]);
+        }
     } else {
-        for (int64_t i = t0; i < n; i += stride)
+        for (int64_t i = t0; i < n; i += stride) {
             gh[i] = (int16_t)quantize_row(g[i], h[i], i, dg, dh, kg, kh, seed_lo, seed_hi, iteration, rounding, sg, sh, sa);
+            if (pairs) pairs[i] = make_float2(g[i], h[i]);
+        }
     }
     for (int o = 32; o > 0; o >>= 1) {
         sg += __shfl_xor(sg, o);
@@ -186,7 +196,7 @@ __global__ __launch_bounds__(256) void quantize_totals_kernel(const int64_t* __r
 
 int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int bits_g, int bits_h,
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
-                    int64_t* totals_out) {
+                    int64_t* totals_out, float2* pairs_out) {
     const int kg = (1 << (bits_g - 1)) - 1, kh = (1 << bits_h) - 2;
     int64_t* totals = totals_out ? totals_out : ctx->qtotals;
     const bool vec = (((uintptr_t)g | (uintptr_t)h) & 15) == 0 && ((uintptr_t)gh & 7) == 0;
@@ -197,12 +207,12 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
         hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part);
         hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part,
                            blocks, kg, kh, (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out,
-                           ctx->qtotals_part);
+                           ctx->qtotals_part, pairs_out);
     } else {
         hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part);
         hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, g, h, n, ctx->absmax_part,
                            blocks, kg, kh, (uint32_t)seed, (uint32_t)(seed >> 32), iteration, rounding, gh, delta_out,
-                           ctx->qtotals_part);
+                           ctx->qtotals_part, pairs_out);
     }
     hipLaunchKernelGGL(quantize_totals_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->qtotals_part, blocks, totals);
     QG_HIP(ctx, hipGetLastError());

@@ -5,7 +5,11 @@
 
 namespace qgbdt {
 
+// PAIR: (g, h) of a row are read as one 8-byte pair from an interleaved copy (half the sectors
+// of two separate 4-byte gathers).
+template <bool PAIR>
 __global__ __launch_bounds__(256) void refit_partial_kernel(const float* __restrict__ g, const float* __restrict__ h,
+                                                            const float2* __restrict__ pairs,
                                                             const int32_t* __restrict__ row_idx,
                                                             const int64_t* __restrict__ leaf_begin,
                                                             const int64_t* __restrict__ leaf_count,
@@ -18,8 +22,14 @@ __global__ __launch_bounds__(256) void refit_partial_kernel(const float* __restr
     double G = 0.0, H = 0.0;
     for (int64_t j = a + threadIdx.x; j < b; j += blockDim.x) {
         const int64_t i = row_idx[begin + j];
-        G += (double)g[i];
-        H += (double)h[i];
+        if (PAIR) {
+            const float2 v = pairs[i];
+            G += (double)v.x;
+            H += (double)v.y;
+        } else {
+            G += (double)g[i];
+            H += (double)h[i];
+        }
     }
     for (int o = 32; o > 0; o >>= 1) { G += __shfl_xor(G, o); H += __shfl_xor(H, o); }
     __shared__ double sg[4], sh[4];
@@ -45,12 +55,16 @@ __global__ void refit_final_kernel(const double* __restrict__ partial, int parts
     value[l] = (H > 0.0) ? -G / H : 0.0;
 }
 
-int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const int32_t* row_idx,
+int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out) {
     if (n_leaves <= 0) return QGBDT_OK;
-    hipLaunchKernelGGL(refit_partial_kernel, dim3(REFIT_PARTS, n_leaves), dim3(256), 0, ctx->stream, g, h, row_idx,
-                       leaf_begin, leaf_count, n_leaves_dev, ctx->refit_partial);
+    if (pairs)
+        hipLaunchKernelGGL(refit_partial_kernel<true>, dim3(REFIT_PARTS, n_leaves), dim3(256), 0, ctx->stream, g, h,
+                           pairs, row_idx, leaf_begin, leaf_count, n_leaves_dev, ctx->refit_partial);
+    else
+        hipLaunchKernelGGL(refit_partial_kernel<false>, dim3(REFIT_PARTS, n_leaves), dim3(256), 0, ctx->stream, g, h,
+                           pairs, row_idx, leaf_begin, leaf_count, n_leaves_dev, ctx->refit_partial);
     hipLaunchKernelGGL(refit_final_kernel, dim3((n_leaves + 63) / 64), dim3(64), 0, ctx->stream, ctx->refit_partial,
                        REFIT_PARTS, n_leaves, n_leaves_dev, value_out);
     QG_HIP(ctx, hipGetLastError());

@@ -501,7 +501,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     out.max_leaves = ctx->shape.max_leaves;
 
     int rc = launch_quantize(ctx, g, h, N, p->bits_g, p->bits_h, p->seed, iteration, p->rounding, ctx->gh,
-                             ctx->delta, ctx->qtotals);
+                             ctx->delta, ctx->qtotals, ctx->ghf);
     if (rc != QGBDT_OK) return rc;
     // 32|32 words of the total histograms must hold the root's sums
     if (N > max_rows_for_width(p->bits_g, p->bits_h, 32)) {
@@ -609,7 +609,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     hipLaunchKernelGGL(tree_gather_rows_kernel, dim3(gx, ctx->shape.max_leaves), dim3(256), 0, ctx->stream, ctx->step,
                        ctx->nodes, ctx->leaf_node, idxs, row_idx_out);
     QG_HIP(ctx, hipGetLastError());
-    return launch_refit(ctx, g, h, row_idx_out, out.t.leaf_begin, out.t.leaf_count, ctx->shape.max_leaves,
+    return launch_refit(ctx, g, h, ctx->ghf, row_idx_out, out.t.leaf_begin, out.t.leaf_count, ctx->shape.max_leaves,
                         out.t.n_leaves, out.t.leaf_value);
 }
 
