@@ -193,6 +193,32 @@ QGBDT_API int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, 
                     const qgbdt_params* params, uint32_t iteration, const qgbdt_tree* tree_out,
                     int32_t* row_idx_out);
 
+/* ---- around the tree: one boosting iteration on the device ------------------ */
+
+/* g_i, h_i = first and second derivative of the loss w.r.t. the current prediction (Sec. 3)
+ * for the binary cross-entropy loss: p = 1/(1+exp(-score)), g = p - label, h = p (1 - p),
+ * evaluated in fp64 and rounded once to fp32.  All dev float[n]; n <= shape.n_rows. */
+QGBDT_API int qgbdt_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n,
+                             float* g_out, float* h_out);
+
+/* Prediction update with a tree (Sec. 3; the learning rate scales the leaf values):
+ * score[row] += (float)(learning_rate * leaf_value[l]) for the rows of every leaf l, one fp32
+ * addition per row.  Leaves are slices of the leaf-ordered row list as grow_tree returns
+ * them.  score: dev float[n_rows], updated in place; leaf_begin, leaf_count: dev int64
+ * [n_leaves]; leaf_value: dev double[n_leaves]. */
+QGBDT_API int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, const int64_t* leaf_begin,
+                        const int64_t* leaf_count, const double* leaf_value, int32_t n_leaves,
+                        double learning_rate);
+
+/* One boosting iteration for the binary cross-entropy loss without any host arithmetic:
+ * loss derivatives of `score`, one tree (qgbdt_grow_tree with these derivatives), score
+ * update with learning_rate times the refit leaf values.  label: dev float[n_rows] (0 / 1);
+ * score: dev float[n_rows], updated in place; the rest as in qgbdt_grow_tree.  The library
+ * keeps the derivatives in its workspace (2 x 4 bytes per row, allocated at the first call). */
+QGBDT_API int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score,
+                          const qgbdt_params* params, uint32_t iteration, double learning_rate,
+                          const qgbdt_tree* tree_out, int32_t* row_idx_out);
+
 /* ---- measurement ---------------------------------------------------------- */
 
 /* When on, every histogram-kernel launch is bracketed by HIP events on the

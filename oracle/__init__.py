@@ -190,6 +190,23 @@ def refit_leaves(g, h, row_idx, leaf_begin, leaf_count):
     return out
 
 
+def logistic_gradients(score, label):
+    score = _c(score, np.float32); label = _c(label, np.float32)
+    g = np.empty(score.size, np.float32); h = np.empty(score.size, np.float32)
+    _chk(lib().qgbdt_ref_logistic_gradients(_p(score), _p(label), C.c_int64(score.size), _p(g), _p(h)), "logistic_gradients")
+    return g, h
+
+
+def update_scores(score, row_idx, leaf_begin, leaf_count, leaf_value, lr: float):
+    """Returns the updated copy of `score`."""
+    out = np.array(score, dtype=np.float32, copy=True)
+    row_idx = _c(row_idx, np.int32); leaf_begin = _c(leaf_begin, np.int64); leaf_count = _c(leaf_count, np.int64)
+    leaf_value = _c(leaf_value, np.float64)
+    _chk(lib().qgbdt_ref_update_scores(_p(out), _p(row_idx), _p(leaf_begin), _p(leaf_count), _p(leaf_value),
+                                       int(leaf_begin.size), C.c_double(lr)), "update_scores")
+    return out
+
+
 def quantized_leaf_value(G: int, H: int, delta_g, delta_h) -> float:
     return float(lib().qgbdt_ref_quantized_leaf_value(G, H, C.c_float(delta_g), C.c_float(delta_h)))
 

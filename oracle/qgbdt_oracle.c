@@ -20,6 +20,7 @@
  *   packed word       Sec. 6.2
  *   width rule        Sec. 7.4.3 (minimum width with no overflow)
  *   growth            Sec. 3 (greedy splitting) and Sec. 7 (leaf-wise)
+ *   loss derivatives  Sec. 3 (g_i, h_i of the loss; binary cross-entropy), score update Sec. 3
  * The random numbers of stochastic rounding come from Philox-4x32-10 (Salmon et
  * al., "Parallel random numbers: as easy as 1, 2, 3", SC'11), written here from
  * that paper's description; it is pinned by the published known-answer vectors.
@@ -314,6 +315,35 @@ int qgbdt_ref_refit_leaves(const float* g, const float* h, const int32_t* row_id
 double qgbdt_ref_quantized_leaf_value(int64_t G, int64_t H, float delta_g, float delta_h) {
     if (H <= 0 || !(delta_h > 0.0f)) return 0.0;
     return -((double)G * (double)delta_g) / ((double)H * (double)delta_h);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Around the tree: loss derivatives and score update (Sec. 3)                */
+/* ------------------------------------------------------------------------ */
+
+/* g_i, h_i = first and second derivative of the loss w.r.t. the current prediction
+ * (Sec. 3), for the binary cross-entropy loss l(s, y) = -y log p - (1-y) log(1-p),
+ * p = 1 / (1 + exp(-s)):  g = p - y,  h = p (1 - p).  Evaluated in fp64 from the fp32
+ * inputs and rounded once to fp32, so the values are the correctly rounded ones. */
+int qgbdt_ref_logistic_gradients(const float* score, const float* label, int64_t n, float* g, float* h) {
+    for (int64_t i = 0; i < n; ++i) {
+        const double p = 1.0 / (1.0 + exp(-(double)score[i]));
+        g[i] = (float)(p - (double)label[i]);
+        h[i] = (float)(p * (1.0 - p));
+    }
+    return QREF_OK;
+}
+
+/* Prediction update after a tree (Sec. 3: the tree's leaf values are added to the current
+ * predictions; the learning rate scales them):  score_i += (float)(lr * value[leaf(i)]),
+ * one fp32 addition per row.  Leaves are slices of the leaf-ordered row list. */
+int qgbdt_ref_update_scores(float* score, const int32_t* row_idx, const int64_t* leaf_begin,
+                            const int64_t* leaf_count, const double* leaf_value, int n_leaves, double lr) {
+    for (int l = 0; l < n_leaves; ++l) {
+        const float d = (float)(lr * leaf_value[l]);
+        for (int64_t j = leaf_begin[l]; j < leaf_begin[l] + leaf_count[l]; ++j) score[row_idx[j]] += d;
+    }
+    return QREF_OK;
 }
 
 /* ------------------------------------------------------------------------ */

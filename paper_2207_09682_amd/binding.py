@@ -23,6 +23,7 @@ EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
     "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
     "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
+    "qgbdt_logistic_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats",
 ]
 
@@ -75,6 +76,11 @@ def load_library() -> C.CDLL:
                                            C.c_int32, C.c_void_p]
         lib.qgbdt_grow_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_uint32,
                                         C.POINTER(TreePtrs), C.c_void_p]
+        lib.qgbdt_logistic_gradients.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.qgbdt_update_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_int32, C.c_double]
+        lib.qgbdt_boost_iteration.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params),
+                                              C.c_uint32, C.c_double, C.POINTER(TreePtrs), C.c_void_p]
         lib.qgbdt_set_profiling.argtypes = [C.c_void_p, C.c_int32]
         lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         lib.qgbdt_tree_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
@@ -247,6 +253,42 @@ class Context:
         self._chk(self.lib.qgbdt_grow_tree(self._h, _dev(bins, torch.uint8, "bins"), _dev(g, torch.float32, "g"),
                                            _dev(h, torch.float32, "h"), C.byref(p), iteration, C.byref(tp),
                                            _dev(tree.row_idx, torch.int32, "row_idx")))
+        return tree
+
+    # -- around the tree ---------------------------------------------------------
+    def logistic_gradients(self, score, label):
+        self._sync_stream()
+        n = score.numel()
+        g = torch.empty(n, dtype=torch.float32, device=self.device)
+        h = torch.empty(n, dtype=torch.float32, device=self.device)
+        self._chk(self.lib.qgbdt_logistic_gradients(self._h, _dev(score, torch.float32, "score"),
+                                                    _dev(label, torch.float32, "label"), n, g.data_ptr(), h.data_ptr()))
+        return g, h
+
+    def update_scores(self, score, row_idx, leaf_begin, leaf_count, leaf_value, learning_rate):
+        """Updates `score` in place."""
+        self._sync_stream()
+        self._chk(self.lib.qgbdt_update_scores(self._h, _dev(score, torch.float32, "score"),
+                                               _dev(row_idx, torch.int32, "row_idx"),
+                                               _dev(leaf_begin, torch.int64, "leaf_begin"),
+                                               _dev(leaf_count, torch.int64, "leaf_count"),
+                                               _dev(leaf_value, torch.float64, "leaf_value"), leaf_begin.numel(),
+                                               float(learning_rate)))
+        return score
+
+    def boost_iteration(self, bins, label, score, bits_g, bits_h, seed, iteration, num_leaves, learning_rate,
+                        min_data_in_leaf=20, min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0,
+                        tree: Tree | None = None) -> Tree:
+        """Loss derivatives, one tree and the score update on the device; `score` is updated in place."""
+        self._sync_stream()
+        tree = tree if tree is not None else self.new_tree()
+        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
+        tp = tree.ptrs()
+        self._chk(self.lib.qgbdt_boost_iteration(self._h, _dev(bins, torch.uint8, "bins"),
+                                                 _dev(label, torch.float32, "label"),
+                                                 _dev(score, torch.float32, "score"), C.byref(p), iteration,
+                                                 float(learning_rate), C.byref(tp),
+                                                 _dev(tree.row_idx, torch.int32, "row_idx")))
         return tree
 
     # -- measurement -------------------------------------------------------------

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libqgbdt.so")
-SOURCES = ["api.hip", "quantize.hip", "histogram.hip", "split.hip", "partition.hip", "refit.hip", "tree.hip"]
+SOURCES = ["api.hip", "quantize.hip", "histogram.hip", "split.hip", "partition.hip", "refit.hip", "tree.hip", "boost.hip"]
 HEADERS = ["common.h", "split_device.h", os.path.join("..", "..", "include", "qgbdt.h")]
 
 # -ffp-contract=off: the split gain is evaluated operation by operation (no FMA), like its definition.

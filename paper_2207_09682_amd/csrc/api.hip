@@ -51,7 +51,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->gh, c->ghf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->idx[2], c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -292,6 +292,42 @@ int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const floa
     int rc = check_bits(ctx, p->bits_g, p->bits_h);
     if (rc != QGBDT_OK) return rc;
     return run_grow_tree(ctx, (const uint8_t*)bins, g, h, p, iteration, t, row_idx_out);
+}
+
+int qgbdt_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, float* g_out,
+                             float* h_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!score || !label || !g_out || !h_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
+    return launch_logistic_gradients(ctx, score, label, n, g_out, h_out);
+}
+
+int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, const int64_t* leaf_begin,
+                        const int64_t* leaf_count, const double* leaf_value, int32_t n_leaves, double learning_rate) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!score || !row_idx || !leaf_begin || !leaf_count || !leaf_value)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n_leaves < 0 || n_leaves > ctx->shape.max_leaves)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "n_leaves=%d outside 0..max_leaves", n_leaves);
+    return launch_update_scores(ctx, score, row_idx, leaf_begin, leaf_count, leaf_value, n_leaves, nullptr, learning_rate);
+}
+
+int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score, const qgbdt_params* p,
+                          uint32_t iteration, double learning_rate, const qgbdt_tree* t, int32_t* row_idx_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!label || !score) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    const int64_t N = ctx->shape.n_rows;
+    if (!ctx->gbuf) {
+        int rc = ws_alloc(ctx, &ctx->gbuf, (size_t)N);
+        if (rc == QGBDT_OK) rc = ws_alloc(ctx, &ctx->hbuf, (size_t)N);
+        if (rc != QGBDT_OK) return rc;
+    }
+    int rc = launch_logistic_gradients(ctx, score, label, N, ctx->gbuf, ctx->hbuf);
+    if (rc != QGBDT_OK) return rc;
+    rc = qgbdt_grow_tree(ctx, bins, ctx->gbuf, ctx->hbuf, p, iteration, t, row_idx_out);  // validates the rest
+    if (rc != QGBDT_OK) return rc;
+    return launch_update_scores(ctx, score, row_idx_out, t->leaf_begin, t->leaf_count, t->leaf_value,
+                                ctx->shape.max_leaves, t->n_leaves, learning_rate);
 }
 
 int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on) {

@@ -1,0 +1,79 @@
+// The two steps around a tree that close the boosting loop on the device (Sec. 3): the loss
+// derivatives g_i, h_i of the current predictions (binary cross-entropy) and the prediction
+// update with the new tree's leaf values.  Both are HBM-bound streaming / gather kernels.
+#include "common.h"
+
+namespace qgbdt {
+
+// p = 1 / (1 + exp(-s)) in fp64 from the fp32 score, g = p - y, h = p (1 - p), each rounded
+// once to fp32: 16 bytes of traffic per row hide the fp64 arithmetic.
+__device__ __forceinline__ void logistic_one(float s, float y, float& g, float& h) {
+    const double p = 1.0 / (1.0 + exp(-(double)s));
+    g = (float)(p - (double)y);
+    h = (float)(p * (1.0 - p));
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void logistic_grad_kernel(const float* __restrict__ score,
+                                                            const float* __restrict__ label, int64_t n,
+                                                            float* __restrict__ g, float* __restrict__ h) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (VEC) {  // all four arrays 16-byte aligned
+        const int64_t n4 = n >> 2;
+        for (int64_t i = t0; i < n4; i += stride) {
+            const float4 s = reinterpret_cast<const float4*>(score)[i], y = reinterpret_cast<const float4*>(label)[i];
+            float4 go, ho;
+            logistic_one(s.x, y.x, go.x, ho.x); logistic_one(s.y, y.y, go.y, ho.y);
+            logistic_one(s.z, y.z, go.z, ho.z); logistic_one(s.w, y.w, go.w, ho.w);
+            reinterpret_cast<float4*>(g)[i] = go;
+            reinterpret_cast<float4*>(h)[i] = ho;
+        }
+        const int64_t r = (n4 << 2) + t0;
+        if (r < n) logistic_one(score[r], label[r], g[r], h[r]);
+    } else {
+        for (int64_t i = t0; i < n; i += stride) logistic_one(score[i], label[i], g[i], h[i]);
+    }
+}
+
+// score[row] += (float)(lr * value[leaf]) for the rows of every leaf: block (part, leaf) takes
+// a contiguous part of the leaf's slice of the leaf-ordered row list.
+__global__ __launch_bounds__(256) void update_scores_kernel(float* __restrict__ score,
+                                                            const int32_t* __restrict__ row_idx,
+                                                            const int64_t* __restrict__ leaf_begin,
+                                                            const int64_t* __restrict__ leaf_count,
+                                                            const double* __restrict__ leaf_value,
+                                                            const int32_t* __restrict__ n_leaves_dev, double lr) {
+    const int l = blockIdx.y;
+    if (n_leaves_dev && l >= *n_leaves_dev) return;
+    const int64_t begin = leaf_begin[l], count = leaf_count[l];
+    const float d = (float)(lr * leaf_value[l]);
+    const int64_t a = count * blockIdx.x / gridDim.x, b = count * (blockIdx.x + 1) / gridDim.x;
+    for (int64_t j = a + threadIdx.x; j < b; j += blockDim.x) {
+        const int64_t i = row_idx[begin + j];
+        score[i] += d;  // every row belongs to exactly one leaf: no two threads touch the same element
+    }
+}
+
+int launch_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, float* g, float* h) {
+    if (n <= 0) return QGBDT_OK;
+    const bool vec = ((((uintptr_t)score | (uintptr_t)label | (uintptr_t)g | (uintptr_t)h) & 15) == 0);
+    int blocks = (int)(((vec ? (n + 3) / 4 : n) + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    if (vec) hipLaunchKernelGGL(logistic_grad_kernel<true>, dim3(blocks), dim3(256), 0, ctx->stream, score, label, n, g, h);
+    else hipLaunchKernelGGL(logistic_grad_kernel<false>, dim3(blocks), dim3(256), 0, ctx->stream, score, label, n, g, h);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+int launch_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, const int64_t* leaf_begin,
+                         const int64_t* leaf_count, const double* leaf_value, int n_leaves,
+                         const int32_t* n_leaves_dev, double lr) {
+    if (n_leaves <= 0) return QGBDT_OK;
+    hipLaunchKernelGGL(update_scores_kernel, dim3(REFIT_PARTS, n_leaves), dim3(256), 0, ctx->stream, score, row_idx,
+                       leaf_begin, leaf_count, leaf_value, n_leaves_dev, lr);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+}  // namespace qgbdt

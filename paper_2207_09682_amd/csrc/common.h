@@ -155,6 +155,8 @@ struct qgbdt_ctx {
     int32_t* idx[3];       // [N] each
     int16_t* gh;           // [N]
     float2* ghf;           // [N] (g, h) interleaved, written by the quantizer for the refit's gather
+    float* gbuf;           // [N] loss derivatives of a boosting iteration run by the library (allocated on first use)
+    float* hbuf;           // [N]
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
     void* hist_partials;   // [max_items][n_tiles] local bins of the row groups, summed by the reduce kernel
     uint8_t* flags;        // [N] partition flags
@@ -227,6 +229,10 @@ int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);
+int launch_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, float* g, float* h);
+int launch_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, const int64_t* leaf_begin,
+                         const int64_t* leaf_count, const double* leaf_value, int n_leaves,
+                         const int32_t* n_leaves_dev, double lr);
 int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const float* h,
                   const qgbdt_params* p, uint32_t iteration, const qgbdt_tree* out, int32_t* row_idx_out);
 

@@ -378,3 +378,67 @@ def test_errors_are_reported_not_crashes():
         ctx.build_histograms(bins, gh, begin=10, count=995)              # slice outside the rows
     with pytest.raises(QgbdtError):
         ctx.build_histograms(bins, gh, acc_width=8)
+
+
+# ----------------------------------------------------------------------------
+# around the tree: loss derivatives, score update, one boosting iteration on the device
+# ----------------------------------------------------------------------------
+
+def _ulp_diff(a, b):
+    ia = a.view(np.int32).astype(np.int64); ib = b.view(np.int32).astype(np.int64)
+    ia = np.where(ia < 0, -(ia & 0x7fffffff), ia); ib = np.where(ib < 0, -(ib & 0x7fffffff), ib)
+    return np.abs(ia - ib)
+
+
+@pytest.mark.parametrize("n,offset", [(1, 0), (1003, 0), (262147, 0), (70001, 1)])
+def test_logistic_gradients_match_oracle(n, offset):
+    # both sides evaluate in fp64 and round once; a last-place difference of the two exp routines can
+    # at most move the rounded result by one unit in the last place
+    rng = np.random.default_rng(n)
+    s = (rng.normal(size=n + offset) * 4).astype(np.float32); y = (rng.random(n + offset) < 0.4).astype(np.float32)
+    s[: min(n, 4)] = np.array([0.0, 90.0, -90.0, 1e-20], np.float32)[: min(n, 4)]
+    ctx = _ctx(n, 4, 16)
+    g, h = ctx.logistic_gradients(torch.from_numpy(s).cuda()[offset:], torch.from_numpy(y).cuda()[offset:])
+    eg, eh = oracle.logistic_gradients(s[offset:], y[offset:])
+    assert _ulp_diff(g.cpu().numpy(), eg).max() <= 1
+    assert _ulp_diff(h.cpu().numpy(), eh).max() <= 1
+    assert (g.cpu().numpy() != eg).mean() < 1e-3 and (h.cpu().numpy() != eh).mean() < 1e-3
+
+
+def test_update_scores_bit_exact():
+    rng = np.random.default_rng(8)
+    N, L = 300_000, 33
+    perm = rng.permutation(N).astype(np.int32)
+    cuts = np.sort(rng.choice(np.arange(1, N), L - 1, replace=False))
+    begin = np.concatenate([[0], cuts]).astype(np.int64); count = np.diff(np.concatenate([begin, [N]])).astype(np.int64)
+    count[3] = 0
+    value = rng.normal(size=L)
+    score = rng.normal(size=N).astype(np.float32)
+    ctx = _ctx(N, 4, 16, L=64)
+    d = torch.from_numpy(score.copy()).cuda()
+    ctx.update_scores(d, torch.from_numpy(perm).cuda(), torch.from_numpy(begin).cuda(), torch.from_numpy(count).cuda(),
+                      torch.from_numpy(value).cuda(), 0.1)
+    # rows of the emptied leaf keep their score on both sides
+    assert np.array_equal(d.cpu().numpy(), oracle.update_scores(score, perm, begin, count, value, 0.1))
+
+
+def test_boost_iterations_on_device_lock_step():
+    # three iterations run entirely by the library; the oracle follows in lock step from the library's
+    # own derivatives of every iteration (the exp routines may differ in the last place)
+    cfg = workloads.CONFIGS[1]
+    N, F, L, lr = 200_000, cfg.n_features, 63, 0.1
+    wl = workloads.make_workload(cfg, n_rows=N, n_features=F)
+    bins_np = workloads.to_numpy(wl.bins); dbins = wl.bins.cuda(); label = wl.label.cuda()
+    ctx = _ctx(N, F, cfg.n_bins, L=L)
+    score = torch.zeros(N, device="cuda")
+    for it in range(3):
+        before = score.clone()
+        g, h = ctx.logistic_gradients(before, label)            # what the iteration will compute internally
+        t = ctx.boost_iteration(dbins, label, score, 3, 3, cfg.seed, it, L, lr, min_data_in_leaf=cfg.min_data_in_leaf)
+        e = oracle.grow_tree(bins_np, cfg.n_bins, g.cpu().numpy(), h.cpu().numpy(), 3, 3, cfg.seed, it, L,
+                             min_data=cfg.min_data_in_leaf)
+        _compare_tree(t, e, N)
+        n = int(t.n_leaves.item())
+        exp = oracle.update_scores(before.cpu().numpy(), e.row_idx, e.leaf_begin, e.leaf_count,
+                                   t.leaf_value.cpu().numpy()[:n], lr)
+        assert np.array_equal(score.cpu().numpy(), exp)

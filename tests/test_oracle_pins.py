@@ -427,3 +427,52 @@ def test_appendix_d_worked_number():
     d_h = float(oracle.scales(np.zeros(2, np.float32), np.array([0.25, 0.1], np.float32), 3, 3)[1])
     val = 8 * d_h ** 2 * math.log(8 / 0.01) / 0.01 ** 2
     assert round(val) == int(c["min_rows_example"])
+
+
+# ----------------------------------------------------------------------------
+# loss derivatives and score update (the steps around the tree)
+# ----------------------------------------------------------------------------
+
+def test_logistic_gradients_closed_forms():
+    # score 0: p = 1/2, so g = 1/2 - y and h = 1/4 exactly
+    y = np.array([0.0, 1.0, 0.0, 1.0], np.float32)
+    g, h = oracle.logistic_gradients(np.zeros(4, np.float32), y)
+    assert np.array_equal(g, np.array([0.5, -0.5, 0.5, -0.5], np.float32))
+    assert np.array_equal(h, np.full(4, 0.25, np.float32))
+    # symmetry sigma(-s) = 1 - sigma(s): g(s, 0) + g(-s, 0) = 1, h even in s
+    s = np.linspace(-12, 12, 97).astype(np.float32)
+    g0, h0 = oracle.logistic_gradients(s, np.zeros_like(s))
+    g1, h1 = oracle.logistic_gradients(-s, np.zeros_like(s))
+    assert np.allclose(g0 + g1, 1.0, atol=2e-7)
+    assert np.allclose(h0, h1, rtol=1e-6, atol=1e-12)
+    # g is the derivative of the loss, h the derivative of g (central differences in fp64)
+    def loss(sv, yv):
+        p = 1.0 / (1.0 + np.exp(-sv)); return -(yv * np.log(p) + (1 - yv) * np.log(1 - p))
+    sv = np.linspace(-4, 4, 33); eps = 1e-4
+    for yv in (0.0, 1.0):
+        gg, hh = oracle.logistic_gradients(sv.astype(np.float32), np.full(sv.size, yv, np.float32))
+        sv32 = sv.astype(np.float32).astype(np.float64)
+        num_g = (loss(sv32 + eps, yv) - loss(sv32 - eps, yv)) / (2 * eps)
+        num_h = (loss(sv32 + eps, yv) - 2 * loss(sv32, yv) + loss(sv32 - eps, yv)) / eps ** 2
+        assert np.allclose(gg, num_g, atol=1e-6)
+        assert np.allclose(hh, num_h, atol=1e-5)
+    # saturation: bounded in [-1, 1] (Sec. 5 remark on cross-entropy), h -> 0
+    g, h = oracle.logistic_gradients(np.array([80.0, -80.0], np.float32), np.array([0.0, 1.0], np.float32))
+    assert g[0] == 1.0 and g[1] == -1.0 and h[0] >= 0.0 and h[0] < 1e-30 and h[1] < 1e-30
+
+
+def test_update_scores_adds_each_rows_leaf_value_once():
+    rng = np.random.default_rng(2)
+    N, L = 1000, 7
+    perm = rng.permutation(N).astype(np.int32)
+    cuts = np.sort(rng.choice(np.arange(1, N), L - 1, replace=False))
+    begin = np.concatenate([[0], cuts]).astype(np.int64); count = np.diff(np.concatenate([begin, [N]])).astype(np.int64)
+    value = rng.normal(size=L)
+    score = rng.normal(size=N).astype(np.float32)
+    out = oracle.update_scores(score, perm, begin, count, value, 0.1)
+    leaf_of_row = np.empty(N, np.int64)
+    for l in range(L):
+        leaf_of_row[perm[begin[l]: begin[l] + count[l]]] = l
+    exp = score + (0.1 * value[leaf_of_row]).astype(np.float32)      # one fp32 addition per row
+    assert np.array_equal(out, exp)
+    assert np.array_equal(oracle.update_scores(score, perm, begin, count, np.zeros(L), 0.1), score)
