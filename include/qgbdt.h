@@ -60,7 +60,8 @@ typedef struct {
 /* Training parameters of one tree. */
 typedef struct {
     int32_t bits_g;           /* B for gradients, 2..8 (Sec. 4.1) */
-    int32_t bits_h;           /* B for hessians, 2..8 */
+    int32_t bits_h;           /* B for hessians, 2..8; 0: the hessians are one constant and are not
+                                 quantized (Sec. 4.1): every h~ is 1, delta_h is the constant */
     int32_t rounding;         /* QGBDT_ROUND_* */
     int32_t num_leaves;       /* leaf budget of leaf-wise growth */
     int32_t min_data_in_leaf; /* minimum (hessian-share estimated) rows per child */
@@ -130,7 +131,8 @@ QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
  * [0, 2^bits_h-2], fp32 arithmetic.  Stochastic rounding draws its uniform numbers
  * from Philox-4x32-10 keyed by `seed` with counter (row, iteration): output word 0
  * rounds g, word 1 rounds h, top 24 bits each.  g, h: dev float[n]; gh_out: dev
- * int16[n]; delta_out: dev float[2].  n <= shape.n_rows. */
+ * int16[n]; delta_out: dev float[2].  n <= shape.n_rows.  bits_h = 0 (constant hessians,
+ * the caller's precondition): h~ = 1 for every row and delta_h = max h. */
 QGBDT_API int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n,
                              int32_t bits_g, int32_t bits_h, uint64_t seed, uint32_t iteration,
                              int32_t rounding, int16_t* gh_out, float* delta_out);

@@ -81,13 +81,13 @@ float qgbdt_ref_uniform24(uint64_t seed, uint32_t iteration, uint64_t row, int s
 /* ------------------------------------------------------------------------ */
 
 static int level_g(int bits) { return (1 << (bits - 1)) - 1; } /* 2^(B-1) - 1 */
-static int level_h(int bits) { return (1 << bits) - 2; }       /* 2^B - 2     */
+static int level_h(int bits) { return bits == 0 ? 1 : (1 << bits) - 2; } /* 2^B - 2; 1 when h is not quantized */
 
 /* delta[0] = max|g| / (2^(B_g-1)-1), delta[1] = max(h) / (2^B_h - 2), fp32 division.
  * The maximum runs over all n rows.  max(h) is taken as 0 when every h is negative. */
 int qgbdt_ref_scales(const float* g, const float* h, int64_t n, int bits_g, int bits_h,
                      float* delta) {
-    if (bits_g < 2 || bits_g > 8 || bits_h < 2 || bits_h > 8 || n < 0) return QREF_E_ARG;
+    if (bits_g < 2 || bits_g > 8 || !(bits_h == 0 || (bits_h >= 2 && bits_h <= 8)) || n < 0) return QREF_E_ARG;
     float mg = 0.0f, mh = 0.0f;
     for (int64_t i = 0; i < n; ++i) {
         const float a = fabsf(g[i]);
@@ -95,7 +95,9 @@ int qgbdt_ref_scales(const float* g, const float* h, int64_t n, int bits_g, int 
         if (h[i] > mh) mh = h[i];
     }
     delta[0] = mg / (float)level_g(bits_g);
-    delta[1] = mh / (float)level_h(bits_h);
+    /* bits_h == 0: the hessians are one constant and are not quantized (Sec. 4.1, remark after
+     * eq. (scale)): every h~_i is 1 and delta_h is the constant itself */
+    delta[1] = (bits_h == 0) ? mh : mh / (float)level_h(bits_h);
     return QREF_OK;
 }
 
@@ -129,7 +131,8 @@ int qgbdt_ref_quantize_gradients(const float* g, const float* h, int64_t n, int 
             uh = qgbdt_ref_uniform24(seed, iteration, (uint64_t)i, 1);
         }
         gq[i] = (int8_t)round_one(g[i], delta[0], -kg, kg, ug, rounding);
-        hq[i] = (uint8_t)round_one(h[i], delta[1], 0, kh, uh, rounding);
+        hq[i] = (bits_h == 0) ? (uint8_t)(delta[1] > 0.0f ? 1 : 0)
+                              : (uint8_t)round_one(h[i], delta[1], 0, kh, uh, rounding);
     }
     return QREF_OK;
 }

@@ -66,8 +66,8 @@ static void free_all(qgbdt_ctx* c) {
 }
 
 static int check_bits(qgbdt_ctx* ctx, int bits_g, int bits_h) {
-    if (bits_g < 2 || bits_g > 8 || bits_h < 2 || bits_h > 8)
-        return set_error(ctx, QGBDT_E_INVALID_ARG, "bits_g=%d, bits_h=%d outside 2..8", bits_g, bits_h);
+    if (bits_g < 2 || bits_g > 8 || !(bits_h == 0 || (bits_h >= 2 && bits_h <= 8)))
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "bits_g=%d, bits_h=%d outside 2..8 (bits_h = 0: constant hessians)", bits_g, bits_h);
     return QGBDT_OK;
 }
 

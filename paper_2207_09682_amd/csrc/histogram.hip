@@ -675,7 +675,7 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
 }
 
 static int64_t rows_fitting(int bits_g, int bits_h, int w) {
-    const int64_t kg = (1 << (bits_g - 1)) - 1, kh = (1 << bits_h) - 2;
+    const int64_t kg = (1 << (bits_g - 1)) - 1, kh = bits_h == 0 ? 1 : (1 << bits_h) - 2;  // bits_h 0: h~ = 1
     const int64_t a = (((int64_t)1 << (w - 1)) - 1) / kg;
     const int64_t b = (((int64_t)1 << w) - 1) / kh;
     return a < b ? a : b;

@@ -114,7 +114,7 @@ __device__ __forceinline__ int quantize_row(float gv, float hv, int64_t row, flo
     if (rounding == QGBDT_ROUND_STOCHASTIC)
         philox4x32_10((uint32_t)row, (uint32_t)((uint64_t)row >> 32), iteration, 0u, seed_lo, seed_hi, r0, r1);
     const int qg = round_one(gv, dg, -kg, kg, r0, rounding);
-    const int qh = round_one(hv, dh, 0, kh, r1, rounding);
+    const int qh = kh > 0 ? round_one(hv, dh, 0, kh, r1, rounding) : (dh > 0.0f ? 1 : 0);
     sg += qg; sh += qh; sa += abs(qg);
     return ((qg << 8) | qh) & 0xffff;
 }
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
     float mg, mh;
     reduce_absmax(absmax_part, n_part, mg, mh);
     const float dg = mg / (float)kg;
-    const float dh = mh / (float)kh;
+    const float dh = kh > 0 ? mh / (float)kh : mh;
     if (blockIdx.x == 0 && threadIdx.x == 0) { delta_out[0] = dg; delta_out[1] = dh; }
     int64_t sg = 0, sh = 0, sa = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -197,7 +197,8 @@ __global__ __launch_bounds__(256) void quantize_totals_kernel(const int64_t* __r
 int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int bits_g, int bits_h,
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
                     int64_t* totals_out, float2* pairs_out) {
-    const int kg = (1 << (bits_g - 1)) - 1, kh = (1 << bits_h) - 2;
+    // bits_h == 0: constant hessians are not quantized (kh = 0 tells the kernel: h~ = 1, delta_h = max h)
+    const int kg = (1 << (bits_g - 1)) - 1, kh = bits_h == 0 ? 0 : (1 << bits_h) - 2;
     int64_t* totals = totals_out ? totals_out : ctx->qtotals;
     const bool vec = (((uintptr_t)g | (uintptr_t)h) & 15) == 0 && ((uintptr_t)gh & 7) == 0;
     int blocks = (int)(((vec ? (n + 3) / 4 : n) + 255) / 256);

@@ -326,6 +326,13 @@ def test_full_size_cfg5():
     torch.cuda.empty_cache()
 
 
+def test_constant_hessian_regression_full_size():
+    # squared error on a 463,715 x 90 matrix: bits_h = 0 (hessians not quantized), F % 4 == 2 takes the
+    # byte-wise histogram kernel; three trees in lock step
+    cfg = workloads.EXTRA_CONFIGS[0]
+    _lockstep(cfg, cfg.n_rows, cfg.n_features, 3, cfg.num_leaves, device="cuda")
+
+
 def test_grow_tree_cfg5_full_leaf_budget():
     # 511 leaves: the growth bookkeeping needs more than 64 KB of LDS
     cfg = workloads.CONFIGS[4]

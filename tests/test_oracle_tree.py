@@ -174,3 +174,31 @@ def test_single_leaf_and_stopping():
     # all-zero gradients: delta = 0, single leaf, value 0
     t = oracle.grow_tree(bins, 8, np.zeros(N, np.float32), np.zeros(N, np.float32), 3, 3, 0, 0, 8)
     assert t.n_leaves == 1 and t.leaf_value[0] == 0.0
+
+
+def test_constant_hessians_not_quantized():
+    """bits_h = 0 (Sec. 4.1: constant hessians need no quantization): h~ = 1, delta_h = the constant,
+    so the integer hessian sums are row counts, the count estimate is the true count, and on on-grid
+    gradients the tree is the exact-histogram tree of the constant-hessian loss."""
+    N, F, nb, L = 2500, 5, 12, 12
+    bins, g, _ = _on_grid_problem(5, N, F, nb, True)
+    h = np.full(N, 0.75, np.float32)
+    gq, hq, delta = oracle.quantize_gradients(g, h, 4, 0, 9, 1)
+    assert np.all(hq == 1) and delta[1] == np.float32(0.75) and delta[0] == 0.125
+    t = oracle.grow_tree(bins, nb, g, h, 4, 0, 9, 1, L, min_data=20, verify_sibling=True)
+    splits, leaves, values = _exact_gbdt_tree(bins, nb, g, h, L, 20)
+    assert t.n_leaves == len(leaves) and t.n_leaves > 4
+    for k, (s, f, b, gain, nl) in enumerate(splits):
+        assert (t.split_leaf[k], t.split_feature[k], t.split_bin[k]) == (s, f, b)
+        assert t.split_gain[k] == pytest.approx(gain, rel=1e-12)
+        assert t.split_n_left[k] == nl
+        assert t.split_stats[k][1] == nl                      # H~ of the left child is its row count
+    assert np.array_equal(t.leaf_H[: t.n_leaves], t.leaf_count[: t.n_leaves])
+    for l, rows in enumerate(leaves):
+        assert np.array_equal(t.row_idx[t.leaf_begin[l]: t.leaf_begin[l] + t.leaf_count[l]], rows)
+        assert t.leaf_value[l] == pytest.approx(values[l], rel=1e-12)
+    # the width rule with k_h = 1
+    assert oracle.max_rows_for_width(2, 0, 16) == 32767 and oracle.max_rows_for_width(5, 0, 16) == 32767 // 15
+    # all-zero hessians: nothing to split on
+    t0 = oracle.grow_tree(bins, nb, g, np.zeros(N, np.float32), 4, 0, 9, 1, L)
+    assert t0.n_leaves == 1

@@ -44,6 +44,13 @@ CONFIGS = [
     Config("cfg5_20M_x200_255bins_rank", 20_000_000, 200, 255, 3, 8, 511, 10, "lambdarank", "skewed_bins_rank"),
 ]
 
+# Workloads of the rows that widen the path (not benchmark configurations): a regression task with the
+# shape of the paper's year-prediction dataset (463,715 x 90), squared error loss, whose hessians are
+# constant and therefore not quantized (bits_h = 0).
+EXTRA_CONFIGS = [
+    Config("regression_464k_x90_255bins_l2", 463_715, 90, 255, 3, 0, 255, 10, "l2", "linear_regression"),
+]
+
 
 @dataclass
 class Workload:
@@ -117,6 +124,12 @@ def make_workload(cfg: Config, n_rows: int | None = None, n_features: int | None
                 y = torch.where(flip, 1.0 - y, y)
         bins = quantile_bins(X, cfg.n_bins)
         return Workload(cfg, bins, y)
+    if cfg.kind == "linear_regression":
+        X = torch.randn((N, F), generator=gen, device=dev)
+        w = torch.randn(F, generator=gen, device=dev) / math.sqrt(F)
+        y = torch.tanh(X @ w) + 0.3 * torch.randn(N, generator=gen, device=dev)   # targets of order 1
+        bins = quantile_bins(X, cfg.n_bins)
+        return Workload(cfg, bins, y.float())
     if cfg.kind == "wide_sparse_linear":
         X = torch.rand((N, F), generator=gen, device=dev)
         nnz = min(50, F)
@@ -191,9 +204,16 @@ def lambdarank_grad(score: torch.Tensor, rel: torch.Tensor, group_size: int, chu
     return g.view(-1).contiguous(), h.view(-1).contiguous()
 
 
+def l2_grad(score: torch.Tensor, y: torch.Tensor):
+    """Squared error 1/2 (score - y)^2: g = score - y, h = 1."""
+    return (score.float() - y).contiguous(), torch.ones_like(y)
+
+
 def gradients(wl: Workload, score: torch.Tensor):
     if wl.cfg.loss == "logistic":
         return logistic_grad(score, wl.label)
+    if wl.cfg.loss == "l2":
+        return l2_grad(score, wl.label)
     return lambdarank_grad(score, wl.label, wl.extra["group_size"])
 
 
