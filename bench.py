@@ -159,22 +159,21 @@ def main():
     total_units = int(units.item())
     n_leaves_last = int(tree.n_leaves.item())
 
-    # ---- whole boosting iterations on the device (derivatives + tree + score update), logistic loss only ----
-    boost = None
-    if cfg.loss == "logistic":
-        sc = torch.zeros(N, device=dev)
-        label = wl.label.to(dev).float().contiguous()
-        for it in range(W):
-            ctx.boost_iteration(bins, label, sc, bits_g, bits_h, cfg.seed, it, L, cfg.learning_rate,
-                                min_data_in_leaf=cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
-        torch.cuda.synchronize()
-        b0 = time.perf_counter()
-        for it in range(W, W + K):
-            ctx.boost_iteration(bins, label, sc, bits_g, bits_h, cfg.seed, it, L, cfg.learning_rate,
-                                min_data_in_leaf=cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
-        torch.cuda.synchronize()
-        boost = {"ms_per_iteration": (time.perf_counter() - b0) / K * 1e3, "iterations": K,
-                 "what": "qgbdt_boost_iteration: loss derivatives + grow_tree + score update, no host arithmetic"}
+    # ---- whole boosting iterations on the device (derivatives + tree + score update) ----
+    sc = torch.zeros(N, device=dev)
+    label = wl.label.to(dev).float().contiguous()
+    gs_rank = wl.extra.get("group_size", 0) if cfg.loss == "lambdarank" else 0
+    for it in range(W):
+        ctx.boost_iteration(bins, label, sc, bits_g, bits_h, cfg.seed, it, L, cfg.learning_rate,
+                            min_data_in_leaf=cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree, group_size=gs_rank)
+    torch.cuda.synchronize()
+    b0 = time.perf_counter()
+    for it in range(W, W + K):
+        ctx.boost_iteration(bins, label, sc, bits_g, bits_h, cfg.seed, it, L, cfg.learning_rate,
+                            min_data_in_leaf=cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree, group_size=gs_rank)
+    torch.cuda.synchronize()
+    boost = {"ms_per_iteration": (time.perf_counter() - b0) / K * 1e3, "iterations": K,
+             "what": f"qgbdt_boost_iteration ({cfg.loss}): loss derivatives + grow_tree + score update, no host arithmetic"}
 
     # ---- root pass alone (contiguous rows): the kernel at its full-size launch -----------------
     root = root_pass(ctx, torch, bins, gs[W], hs[W], bits_g, bits_h, cfg, args, W, N, F, nb)

@@ -203,6 +203,16 @@ QGBDT_API int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, 
 QGBDT_API int qgbdt_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n,
                              float* g_out, float* h_out);
 
+/* The same for the pairwise ranking loss with NDCG weights (lambdarank, the objective of the
+ * paper's ranking experiments, Sec. 7).  Rows form consecutive queries of group_size rows (the
+ * last may be shorter); relevance holds integer grades.  Inside a query documents are ranked by
+ * score, descending, ties by position; gain = 2^rel - 1, discount = 1/log2(rank+2), maxDCG the
+ * DCG of the gains in descending order.  Every pair (a, b) with rel_a > rel_b contributes
+ * rho = 1/(1+exp(s_a-s_b)), w = |gain_a-gain_b| |disc_a-disc_b| / maxDCG:  g_a -= rho w,
+ * g_b += rho w, h_a and h_b += rho (1-rho) w.  fp64, rounded once to fp32.  1 <= group_size <= 1024. */
+QGBDT_API int qgbdt_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float* relevance, int64_t n,
+                               int32_t group_size, float* g_out, float* h_out);
+
 /* Prediction update with a tree (Sec. 3; the learning rate scales the leaf values):
  * score[row] += (float)(learning_rate * leaf_value[l]) for the rows of every leaf l, one fp32
  * addition per row.  Leaves are slices of the leaf-ordered row list as grow_tree returns
@@ -220,6 +230,12 @@ QGBDT_API int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* r
 QGBDT_API int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score,
                           const qgbdt_params* params, uint32_t iteration, double learning_rate,
                           const qgbdt_tree* tree_out, int32_t* row_idx_out);
+
+/* One boosting iteration for the lambdarank loss (qgbdt_lambdarank_gradients, then as above). */
+QGBDT_API int qgbdt_boost_iteration_lambdarank(qgbdt_ctx* ctx, const void* bins, const float* relevance,
+                                     int32_t group_size, float* score, const qgbdt_params* params,
+                                     uint32_t iteration, double learning_rate, const qgbdt_tree* tree_out,
+                                     int32_t* row_idx_out);
 
 /* ---- measurement ---------------------------------------------------------- */
 

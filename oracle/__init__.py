@@ -197,6 +197,14 @@ def logistic_gradients(score, label):
     return g, h
 
 
+def lambdarank_gradients(score, label, group: int):
+    score = _c(score, np.float32); label = _c(label, np.float32)
+    g = np.empty(score.size, np.float32); h = np.empty(score.size, np.float32)
+    _chk(lib().qgbdt_ref_lambdarank_gradients(_p(score), _p(label), C.c_int64(score.size), int(group), _p(g), _p(h)),
+         "lambdarank_gradients")
+    return g, h
+
+
 def update_scores(score, row_idx, leaf_begin, leaf_count, leaf_value, lr: float):
     """Returns the updated copy of `score`."""
     out = np.array(score, dtype=np.float32, copy=True)

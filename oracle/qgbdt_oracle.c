@@ -337,6 +337,55 @@ int qgbdt_ref_logistic_gradients(const float* score, const float* label, int64_t
     return QREF_OK;
 }
 
+/* Pairwise ranking loss with NDCG weights (the lambdarank objective the paper's ranking
+ * experiments name in its parameter tables; the textbook LambdaRank of Burges et al.).  Rows come
+ * in consecutive queries of `group` rows (the last may be shorter); label = integer relevance.
+ * Inside a query: documents are ranked by score, descending, ties by position; gain = 2^rel - 1,
+ * discount(rank) = 1 / log2(rank + 2), maxDCG = DCG of the gains sorted descending.  For every
+ * pair (a, b) with rel_a > rel_b:
+ *     rho = 1 / (1 + exp(s_a - s_b)),  w = |gain_a - gain_b| * |disc_a - disc_b| / maxDCG,
+ *     g_a -= rho w,  g_b += rho w,  h_a += rho (1 - rho) w,  h_b += rho (1 - rho) w.
+ * fp64 throughout, pairs in (a ascending, b ascending) order, rounded once to fp32. */
+int qgbdt_ref_lambdarank_gradients(const float* score, const float* label, int64_t n, int group,
+                                   float* g, float* h) {
+    if (group < 1 || n < 0) return QREF_E_ARG;
+    double* G = (double*)malloc(sizeof(double) * (size_t)group);
+    double* H = (double*)malloc(sizeof(double) * (size_t)group);
+    double* gain = (double*)malloc(sizeof(double) * (size_t)group);
+    double* disc = (double*)malloc(sizeof(double) * (size_t)group);
+    if (!G || !H || !gain || !disc) { free(G); free(H); free(gain); free(disc); return QREF_E_ALLOC; }
+    for (int64_t q0 = 0; q0 < n; q0 += group) {
+        const int m = (int)((n - q0 < group) ? (n - q0) : group);
+        const float* s = score + q0;
+        const float* r = label + q0;
+        double max_dcg = 0.0;
+        for (int k = 0; k < m; ++k) {
+            int rank = 0, irank = 0;
+            gain[k] = exp2((double)r[k]) - 1.0;
+            for (int j = 0; j < m; ++j) {
+                if (s[j] > s[k] || (s[j] == s[k] && j < k)) ++rank;
+                if (r[j] > r[k] || (r[j] == r[k] && j < k)) ++irank; /* position among the gains sorted descending */
+            }
+            disc[k] = 1.0 / log2((double)rank + 2.0);
+            max_dcg += gain[k] / log2((double)irank + 2.0);
+            G[k] = 0.0; H[k] = 0.0;
+        }
+        if (max_dcg > 0.0) {
+            for (int a = 0; a < m; ++a)
+                for (int b = 0; b < m; ++b) {
+                    if (!(r[a] > r[b])) continue;
+                    const double rho = 1.0 / (1.0 + exp((double)s[a] - (double)s[b]));
+                    const double w = fabs(gain[a] - gain[b]) * fabs(disc[a] - disc[b]) / max_dcg;
+                    G[a] -= rho * w; G[b] += rho * w;
+                    H[a] += rho * (1.0 - rho) * w; H[b] += rho * (1.0 - rho) * w;
+                }
+        }
+        for (int k = 0; k < m; ++k) { g[q0 + k] = (float)G[k]; h[q0 + k] = (float)H[k]; }
+    }
+    free(G); free(H); free(gain); free(disc);
+    return QREF_OK;
+}
+
 /* Prediction update after a tree (Sec. 3: the tree's leaf values are added to the current
  * predictions; the learning rate scales them):  score_i += (float)(lr * value[leaf(i)]),
  * one fp32 addition per row.  Leaves are slices of the leaf-ordered row list. */

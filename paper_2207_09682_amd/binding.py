@@ -23,7 +23,8 @@ EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
     "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
     "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
-    "qgbdt_logistic_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
+    "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
+    "qgbdt_boost_iteration_lambdarank",
     "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats",
 ]
 
@@ -77,6 +78,11 @@ def load_library() -> C.CDLL:
         lib.qgbdt_grow_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_uint32,
                                         C.POINTER(TreePtrs), C.c_void_p]
         lib.qgbdt_logistic_gradients.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.qgbdt_lambdarank_gradients.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                                   C.c_void_p]
+        lib.qgbdt_boost_iteration_lambdarank.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                                         C.POINTER(Params), C.c_uint32, C.c_double,
+                                                         C.POINTER(TreePtrs), C.c_void_p]
         lib.qgbdt_update_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int32, C.c_double]
         lib.qgbdt_boost_iteration.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params),
@@ -265,6 +271,16 @@ class Context:
                                                     _dev(label, torch.float32, "label"), n, g.data_ptr(), h.data_ptr()))
         return g, h
 
+    def lambdarank_gradients(self, score, relevance, group_size):
+        self._sync_stream()
+        n = score.numel()
+        g = torch.empty(n, dtype=torch.float32, device=self.device)
+        h = torch.empty(n, dtype=torch.float32, device=self.device)
+        self._chk(self.lib.qgbdt_lambdarank_gradients(self._h, _dev(score, torch.float32, "score"),
+                                                      _dev(relevance, torch.float32, "relevance"), n, int(group_size),
+                                                      g.data_ptr(), h.data_ptr()))
+        return g, h
+
     def update_scores(self, score, row_idx, leaf_begin, leaf_count, leaf_value, learning_rate):
         """Updates `score` in place."""
         self._sync_stream()
@@ -278,17 +294,24 @@ class Context:
 
     def boost_iteration(self, bins, label, score, bits_g, bits_h, seed, iteration, num_leaves, learning_rate,
                         min_data_in_leaf=20, min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0,
-                        tree: Tree | None = None) -> Tree:
-        """Loss derivatives, one tree and the score update on the device; `score` is updated in place."""
+                        tree: Tree | None = None, group_size: int = 0) -> Tree:
+        """Loss derivatives, one tree and the score update on the device; `score` is updated in place.
+        group_size > 0 selects the lambdarank loss (label = relevance), else binary cross-entropy."""
         self._sync_stream()
         tree = tree if tree is not None else self.new_tree()
         p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
         tp = tree.ptrs()
-        self._chk(self.lib.qgbdt_boost_iteration(self._h, _dev(bins, torch.uint8, "bins"),
-                                                 _dev(label, torch.float32, "label"),
-                                                 _dev(score, torch.float32, "score"), C.byref(p), iteration,
-                                                 float(learning_rate), C.byref(tp),
-                                                 _dev(tree.row_idx, torch.int32, "row_idx")))
+        if group_size > 0:
+            self._chk(self.lib.qgbdt_boost_iteration_lambdarank(
+                self._h, _dev(bins, torch.uint8, "bins"), _dev(label, torch.float32, "relevance"), int(group_size),
+                _dev(score, torch.float32, "score"), C.byref(p), iteration, float(learning_rate), C.byref(tp),
+                _dev(tree.row_idx, torch.int32, "row_idx")))
+        else:
+            self._chk(self.lib.qgbdt_boost_iteration(self._h, _dev(bins, torch.uint8, "bins"),
+                                                     _dev(label, torch.float32, "label"),
+                                                     _dev(score, torch.float32, "score"), C.byref(p), iteration,
+                                                     float(learning_rate), C.byref(tp),
+                                                     _dev(tree.row_idx, torch.int32, "row_idx")))
         return tree
 
     # -- measurement -------------------------------------------------------------

@@ -312,22 +312,48 @@ int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, co
     return launch_update_scores(ctx, score, row_idx, leaf_begin, leaf_count, leaf_value, n_leaves, nullptr, learning_rate);
 }
 
-int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score, const qgbdt_params* p,
-                          uint32_t iteration, double learning_rate, const qgbdt_tree* t, int32_t* row_idx_out) {
+int qgbdt_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float* relevance, int64_t n,
+                               int32_t group_size, float* g_out, float* h_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!score || !relevance || !g_out || !h_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
+    if (group_size < 1 || group_size > 1024)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "group_size=%d outside 1..1024", group_size);
+    return launch_lambdarank_gradients(ctx, score, relevance, n, group_size, g_out, h_out);
+}
+
+// loss: 0 binary cross-entropy, 1 lambdarank with queries of group_size rows
+static int boost_iteration(qgbdt_ctx* ctx, int loss, int group_size, const void* bins, const float* label, float* score,
+                           const qgbdt_params* p, uint32_t iteration, double learning_rate, const qgbdt_tree* t,
+                           int32_t* row_idx_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!label || !score) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (loss == 1 && (group_size < 1 || group_size > 1024))
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "group_size=%d outside 1..1024", group_size);
     const int64_t N = ctx->shape.n_rows;
     if (!ctx->gbuf) {
         int rc = ws_alloc(ctx, &ctx->gbuf, (size_t)N);
         if (rc == QGBDT_OK) rc = ws_alloc(ctx, &ctx->hbuf, (size_t)N);
         if (rc != QGBDT_OK) return rc;
     }
-    int rc = launch_logistic_gradients(ctx, score, label, N, ctx->gbuf, ctx->hbuf);
+    int rc = loss == 0 ? launch_logistic_gradients(ctx, score, label, N, ctx->gbuf, ctx->hbuf)
+                       : launch_lambdarank_gradients(ctx, score, label, N, group_size, ctx->gbuf, ctx->hbuf);
     if (rc != QGBDT_OK) return rc;
     rc = qgbdt_grow_tree(ctx, bins, ctx->gbuf, ctx->hbuf, p, iteration, t, row_idx_out);  // validates the rest
     if (rc != QGBDT_OK) return rc;
     return launch_update_scores(ctx, score, row_idx_out, t->leaf_begin, t->leaf_count, t->leaf_value,
                                 ctx->shape.max_leaves, t->n_leaves, learning_rate);
+}
+
+int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score, const qgbdt_params* p,
+                          uint32_t iteration, double learning_rate, const qgbdt_tree* t, int32_t* row_idx_out) {
+    return boost_iteration(ctx, 0, 0, bins, label, score, p, iteration, learning_rate, t, row_idx_out);
+}
+
+int qgbdt_boost_iteration_lambdarank(qgbdt_ctx* ctx, const void* bins, const float* relevance, int32_t group_size,
+                                     float* score, const qgbdt_params* p, uint32_t iteration, double learning_rate,
+                                     const qgbdt_tree* t, int32_t* row_idx_out) {
+    return boost_iteration(ctx, 1, group_size, bins, relevance, score, p, iteration, learning_rate, t, row_idx_out);
 }
 
 int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on) {

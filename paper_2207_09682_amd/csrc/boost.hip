@@ -55,6 +55,84 @@ __global__ __launch_bounds__(256) void update_scores_kernel(float* __restrict__ 
     }
 }
 
+// Pairwise ranking loss with NDCG weights (lambdarank): one workgroup per query of `group`
+// consecutive rows.  Ranks (by score, ties by position), discounts, gains and the ideal DCG are
+// formed in LDS; then every thread owns documents and walks all partners, so its sums need no
+// atomics and have a fixed order.  For a pair (a, b) with rel_a > rel_b:
+//   rho = 1 / (1 + exp(s_a - s_b)),  w = |gain_a - gain_b| |disc_a - disc_b| / maxDCG,
+//   g_a -= rho w, g_b += rho w, h_a += rho (1 - rho) w, h_b += rho (1 - rho) w;  fp64, rounded once.
+__global__ __launch_bounds__(128) void lambdarank_grad_kernel(const float* __restrict__ score,
+                                                              const float* __restrict__ label, int64_t n, int group,
+                                                              float* __restrict__ g, float* __restrict__ h) {
+    extern __shared__ double lr_lds[];
+    double* s = lr_lds;
+    double* r = s + group;
+    double* gain = r + group;
+    double* disc = gain + group;
+    __shared__ double wsum[2];
+    const int tid = threadIdx.x;
+    const int64_t n_queries = (n + group - 1) / group;
+    for (int64_t q = blockIdx.x; q < n_queries; q += gridDim.x) {
+        const int64_t q0 = q * group;
+        const int m = (int)min((int64_t)group, n - q0);
+        __syncthreads();  // the previous query's values are no longer read
+        for (int k = tid; k < m; k += blockDim.x) {
+            s[k] = (double)score[q0 + k];
+            r[k] = (double)label[q0 + k];
+            gain[k] = exp2(r[k]) - 1.0;
+        }
+        __syncthreads();
+        double part = 0.0;
+        for (int k = tid; k < m; k += blockDim.x) {
+            int rank = 0, irank = 0;
+            const double sk = s[k], rk = r[k];
+            for (int j = 0; j < m; ++j) {
+                rank += (s[j] > sk || (s[j] == sk && j < k)) ? 1 : 0;
+                irank += (r[j] > rk || (r[j] == rk && j < k)) ? 1 : 0;
+            }
+            disc[k] = 1.0 / log2((double)rank + 2.0);
+            part += gain[k] / log2((double)irank + 2.0);
+        }
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+        if ((tid & 63) == 0) wsum[tid >> 6] = part;
+        __syncthreads();
+        const double max_dcg = wsum[0] + wsum[1];
+        for (int k = tid; k < m; k += blockDim.x) {
+            double G = 0.0, H = 0.0;
+            if (max_dcg > 0.0) {
+                const double sk = s[k], rk = r[k], gk = gain[k], dk = disc[k];
+                for (int j = 0; j < m; ++j) {
+                    const double rj = r[j];
+                    if (rj == rk) continue;
+                    const double w = fabs(gk - gain[j]) * fabs(dk - disc[j]) / max_dcg;
+                    if (rk > rj) {  // k is the more relevant one of the pair
+                        const double rho = 1.0 / (1.0 + exp(sk - s[j]));
+                        G -= rho * w;
+                        H += rho * (1.0 - rho) * w;
+                    } else {
+                        const double rho = 1.0 / (1.0 + exp(s[j] - sk));
+                        G += rho * w;
+                        H += rho * (1.0 - rho) * w;
+                    }
+                }
+            }
+            g[q0 + k] = (float)G;
+            h[q0 + k] = (float)H;
+        }
+    }
+}
+
+int launch_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, int group,
+                                float* g, float* h) {
+    if (n <= 0) return QGBDT_OK;
+    const int64_t n_queries = (n + group - 1) / group;
+    const int blocks = (int)(n_queries < 65536 ? n_queries : 65536);
+    hipLaunchKernelGGL(lambdarank_grad_kernel, dim3(blocks), dim3(128), sizeof(double) * 4 * (size_t)group, ctx->stream,
+                       score, label, n, group, g, h);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
 int launch_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, float* g, float* h) {
     if (n <= 0) return QGBDT_OK;
     const bool vec = ((((uintptr_t)score | (uintptr_t)label | (uintptr_t)g | (uintptr_t)h) & 15) == 0);

@@ -230,6 +230,8 @@ int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* p
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);
 int launch_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, float* g, float* h);
+int launch_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float* label, int64_t n, int group,
+                                float* g, float* h);
 int launch_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, const int64_t* leaf_begin,
                          const int64_t* leaf_count, const double* leaf_value, int n_leaves,
                          const int32_t* n_leaves_dev, double lr);

@@ -449,3 +449,41 @@ def test_boost_iterations_on_device_lock_step():
         exp = oracle.update_scores(before.cpu().numpy(), e.row_idx, e.leaf_begin, e.leaf_count,
                                    t.leaf_value.cpu().numpy()[:n], lr)
         assert np.array_equal(score.cpu().numpy(), exp)
+
+
+@pytest.mark.parametrize("n,gs", [(13, 13), (1300, 100), (1037, 100), (4096, 1024), (50, 1)])
+def test_lambdarank_gradients_match_oracle(n, gs):
+    # both sides sum fp64 terms (in different orders) and round once to fp32
+    rng = np.random.default_rng(n + gs)
+    s = rng.normal(size=n).astype(np.float32); rel = rng.integers(0, 5, n).astype(np.float32)
+    if n > 8:
+        s[3] = s[6]                                       # a tie in score: ranked by position on both sides
+    ctx = _ctx(n, 4, 16)
+    g, h = ctx.lambdarank_gradients(torch.from_numpy(s).cuda(), torch.from_numpy(rel).cuda(), gs)
+    eg, eh = oracle.lambdarank_gradients(s, rel, gs)
+    scale = max(float(np.abs(eg).max()), 1e-30)
+    assert np.allclose(g.cpu().numpy(), eg, rtol=1e-6, atol=1e-7 * scale)
+    assert np.allclose(h.cpu().numpy(), eh, rtol=1e-6, atol=1e-7 * scale)
+
+
+def test_boost_iterations_lambdarank_lock_step():
+    cfg = workloads.CONFIGS[4]
+    N, F, L, lr = 60_000, 40, 63, 0.1
+    wl = workloads.make_workload(cfg, n_rows=N, n_features=F)
+    N = wl.n_rows
+    gs = wl.extra["group_size"]
+    bins_np = workloads.to_numpy(wl.bins); dbins = wl.bins.cuda(); rel = wl.label.cuda()
+    ctx = _ctx(N, F, cfg.n_bins, L=L)
+    score = torch.zeros(N, device="cuda")
+    for it in range(2):
+        before = score.clone()
+        g, h = ctx.lambdarank_gradients(before, rel, gs)
+        t = ctx.boost_iteration(dbins, rel, score, cfg.bits_g, cfg.bits_h, cfg.seed, it, L, lr,
+                                min_data_in_leaf=cfg.min_data_in_leaf, group_size=gs)
+        e = oracle.grow_tree(bins_np, cfg.n_bins, g.cpu().numpy(), h.cpu().numpy(), cfg.bits_g, cfg.bits_h, cfg.seed, it,
+                             L, min_data=cfg.min_data_in_leaf)
+        _compare_tree(t, e, N)
+        n = int(t.n_leaves.item())
+        exp = oracle.update_scores(before.cpu().numpy(), e.row_idx, e.leaf_begin, e.leaf_count,
+                                   t.leaf_value.cpu().numpy()[:n], lr)
+        assert np.array_equal(score.cpu().numpy(), exp)

@@ -476,3 +476,43 @@ def test_update_scores_adds_each_rows_leaf_value_once():
     exp = score + (0.1 * value[leaf_of_row]).astype(np.float32)      # one fp32 addition per row
     assert np.array_equal(out, exp)
     assert np.array_equal(oracle.update_scores(score, perm, begin, count, np.zeros(L), 0.1), score)
+
+
+def test_lambdarank_gradients_pins():
+    # two documents, relevance 1 and 0, equal scores: ranks 0 and 1, gains 1 and 0, maxDCG = 1,
+    # |disc_0 - disc_1| = 1 - 1/log2(3), rho = 1/2
+    d = 1.0 - 1.0 / np.log2(3.0)
+    g, h = oracle.lambdarank_gradients(np.zeros(2, np.float32), np.array([1.0, 0.0], np.float32), 2)
+    assert np.allclose(g, [-0.5 * d, 0.5 * d], rtol=1e-7) and np.allclose(h, [0.25 * d, 0.25 * d], rtol=1e-7)
+    # ... and with the relevant document scored s higher: rho = 1 / (1 + e^s)
+    s = 1.5
+    g, h = oracle.lambdarank_gradients(np.array([s, 0.0], np.float32), np.array([1.0, 0.0], np.float32), 2)
+    rho = 1.0 / (1.0 + np.exp(s))
+    assert np.allclose(g, [-rho * d, rho * d], rtol=1e-7) and np.allclose(h, [rho * (1 - rho) * d] * 2, rtol=1e-7)
+    # brute force in numpy on random queries (independent of the C loops: vectorised over pairs)
+    rng = np.random.default_rng(4)
+    Q, gs = 7, 13
+    sc = rng.normal(size=Q * gs).astype(np.float32); rel = rng.integers(0, 5, Q * gs).astype(np.float32)
+    sc[3] = sc[5]                                                  # a tie inside the first query: ranked by position
+    g, h = oracle.lambdarank_gradients(sc, rel, gs)
+    for q in range(Q):
+        s64 = sc[q * gs:(q + 1) * gs].astype(np.float64); r = rel[q * gs:(q + 1) * gs]
+        order = np.lexsort((np.arange(gs), -s64)); rank = np.empty(gs, int); rank[order] = np.arange(gs)
+        disc = 1.0 / np.log2(rank + 2.0); gain = 2.0 ** r - 1.0
+        max_dcg = (np.sort(gain)[::-1] / np.log2(np.arange(gs) + 2.0)).sum()
+        better = r[:, None] > r[None, :]
+        rho = 1.0 / (1.0 + np.exp(s64[:, None] - s64[None, :]))
+        w = np.abs(gain[:, None] - gain[None, :]) * np.abs(disc[:, None] - disc[None, :]) / max_dcg
+        lam = np.where(better, rho * w, 0.0); hes = np.where(better, rho * (1 - rho) * w, 0.0)
+        assert np.allclose(g[q * gs:(q + 1) * gs], -lam.sum(1) + lam.sum(0), rtol=1e-6, atol=1e-9)
+        assert np.allclose(h[q * gs:(q + 1) * gs], hes.sum(1) + hes.sum(0), rtol=1e-6, atol=1e-9)
+        assert abs(g[q * gs:(q + 1) * gs].astype(np.float64).sum()) < 1e-6          # every pair adds +x and -x
+    assert (h >= 0).all()
+    # a common offset of a query's scores changes nothing; a query of equal relevance has no pairs
+    g2, h2 = oracle.lambdarank_gradients(sc + np.float32(2.0), rel, gs)
+    assert np.allclose(g2, g, rtol=1e-4, atol=1e-7)
+    g0, h0 = oracle.lambdarank_gradients(sc[:gs], np.full(gs, 2.0, np.float32), gs)
+    assert not g0.any() and not h0.any()
+    # a shorter last query
+    g3, h3 = oracle.lambdarank_gradients(sc[:gs + 5], rel[:gs + 5], gs)
+    assert np.array_equal(g3[:gs], g[:gs]) and abs(g3[gs:].astype(np.float64).sum()) < 1e-6
