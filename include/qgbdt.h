@@ -11,6 +11,8 @@
  *    the call's enqueued work.  Pointers marked "host" are host memory.
  *  - All work is enqueued on the context's HIP stream and is asynchronous; no
  *    entry point synchronises unless it says so.
+ *  - A context belongs to the device that was current when it was created; calls on it must be
+ *    made with that device current.  A context is not thread-safe: one call at a time.
  *  - Every function returns 0 (QGBDT_OK) or a negative QGBDT_E_* code;
  *    qgbdt_last_error() gives a message.  No exception crosses the boundary.
  *  - Layouts
@@ -54,7 +56,8 @@ typedef struct {
     int32_t n_features; /* J of Algorithm 1 */
     int32_t n_bins;     /* bins per feature, 2 .. 256 */
     int32_t bin_bytes;  /* 1 (uint8 bins) */
-    int32_t max_leaves; /* largest num_leaves grow_tree will be asked for */
+    int32_t max_leaves; /* largest num_leaves grow_tree will be asked for (at most ~680: the growth
+                           bookkeeping of all nodes lives in one workgroup's LDS) */
 } qgbdt_shape;
 
 /* Training parameters of one tree. */

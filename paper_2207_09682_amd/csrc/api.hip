@@ -53,7 +53,7 @@ static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
                     c->idx[2], c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
-                    c->hist_counts, c->pwork, c->scan_items, c->scan_counters, c->leaf_node, c->refit_partial,
+                    c->hist_counts, c->pwork, c->scan_items, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -103,6 +103,16 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     c->max_nodes = 2 * c->max_expand + 1;
     c->max_seg = (int)(N / PART_SEG) + c->batch_max + 2;
     c->rounds_hint = 10;
+    {
+        // the plan kernel keeps its sort and replay state of all nodes in LDS
+        int p_max = 64;
+        while (p_max < c->max_nodes) p_max <<= 1;
+        const size_t plan_lds = (size_t)p_max * 12 + (size_t)c->max_nodes * 12 + (size_t)(4 * L + 8) * 4;
+        if (plan_lds > 160 * 1024) {
+            delete c;
+            return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 680 leaves)", L, plan_lds);
+        }
+    }
     int rc = QGBDT_OK;
     // narrow rows: moving a row costs less than gathering it twice per level
     c->ordered = (shape->n_features % 4 == 0 && shape->n_features >= 16 && shape->n_features <= 64) ? 1 : 0;
@@ -146,13 +156,10 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_counts, 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->pwork, 1);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->scan_items, (size_t)2 * c->batch_max);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->scan_counters, (size_t)2 * c->batch_max);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->leaf_node, (size_t)L);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->refit_partial, (size_t)L * REFIT_PARTS * 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_i64, 8);
     if (rc == QGBDT_OK && hipMemset(c->step, 0, sizeof(StepState)) != hipSuccess)
-        rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
-    if (rc == QGBDT_OK && hipMemset(c->scan_counters, 0, sizeof(int32_t) * 2 * c->batch_max) != hipSuccess)
         rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
     if (rc == QGBDT_OK && hipHostMalloc(reinterpret_cast<void**>(&c->host_state), sizeof(StepState), hipHostMallocDefault) != hipSuccess)
         rc = set_error(c, QGBDT_E_ALLOC, "hipHostMalloc failed");

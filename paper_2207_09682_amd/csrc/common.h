@@ -175,7 +175,6 @@ struct qgbdt_ctx {
     int32_t* hist_counts;        // [2] entries, items
     qgbdt::PartWork* pwork;      // [1]
     qgbdt::ScanItem* scan_items; // [2*batch_max]
-    int32_t* scan_counters;      // [2*batch_max]
     int32_t* leaf_node;          // [max_leaves]
     double* refit_partial;       // [max_leaves][REFIT_PARTS][2]
     int64_t* tmp_i64;            // [8]

@@ -23,13 +23,12 @@ int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child,
 }
 
 __global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n, ScanItem* items, qgbdt_split* out,
-                                             int32_t* n_items, int32_t* counters) {
+                                             int32_t* n_items) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
         ScanItem it;
         it.slot = i; it.sub_parent = -1; it.sub_child = -1; it.valid = 1; it.stat = stats[i]; it.out = out + i;
         items[i] = it;
-        counters[i] = 0;
     }
     if (i == 0) *n_items = n;
 }
@@ -154,7 +153,7 @@ int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const
     for (int h0 = 0; h0 < n_hists; h0 += cap) {
         const int n = (n_hists - h0 < cap) ? (n_hists - h0) : cap;
         hipLaunchKernelGGL(scan_items_from_stats_kernel, dim3((n + 63) / 64), dim3(64), 0, ctx->stream, stats + h0, n,
-                           ctx->scan_items, out + h0, n_items, ctx->scan_counters);
+                           ctx->scan_items, out + h0, n_items);
         int rc = launch_scan_items(ctx, const_cast<int64_t*>(hist) + h0 * W, ctx->scan_items, n_items, n, delta,
                                    min_data, min_sum_hess);
         if (rc != QGBDT_OK) return rc;

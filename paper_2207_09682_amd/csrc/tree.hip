@@ -43,7 +43,7 @@ __device__ __forceinline__ int hist_groups(int64_t count, const HistPlan& plan) 
 
 __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, int F, StepState* step, Node* nodes,
                                                         const int64_t* qtotals, int root_buf, HistEntry* hist_entries,
-                                                        int32_t* hist_counts, ScanItem* items, int32_t* scan_counters,
+                                                        int32_t* hist_counts, ScanItem* items,
                                                         int64_t* hist0, int64_t hist_words, HistPlan plan) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -67,7 +67,6 @@ __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N
         it.stat.n_rows = N; it.stat.sum_g = r.sum_g; it.stat.sum_h = r.sum_h;
         it.out = &nodes[0].best;
         items[0] = it;
-        scan_counters[0] = 0;
     }
 }
 
@@ -161,7 +160,7 @@ __device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
 //  3. All threads write the outputs of the committed splits.
 //  4. The batch is chosen by walking the sorted order (prefix sums over sorted positions).
 __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
-                                                         int32_t* hist_counts, int32_t* scan_counters, int F,
+                                                         int32_t* hist_counts, int F,
                                                          int num_leaves, int batch_max, int max_expand, int p_max,
                                                          TreeOut out) {
     if (step->done) return;
@@ -348,7 +347,6 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         batch[tid].new_slot = n_slots + tid;
         nodes[i].expanded = 1;
         nodes[i].child = n_nodes + 2 * tid;
-        scan_counters[2 * tid] = 0; scan_counters[2 * tid + 1] = 0;
     }
     if (tid == n_batch - 1) step->n_part_items = incl;
     __syncthreads();
@@ -531,7 +529,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
-                       ctx->scan_counters, ctx->hist_pool, W, plan);
+                       ctx->hist_pool, W, plan);
     rc = launch_hist(ctx, plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
                      (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
@@ -556,7 +554,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     for (;;) {
         for (int r = 0; r < to_launch; ++r) {
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
-                               ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
+                               ctx->batch, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                                ctx->max_expand, p_max, out);
             rc = launch_batch_partition_count(ctx, rows);
             if (rc != QGBDT_OK) return rc;
@@ -575,7 +573,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         launched += to_launch;
         // one more plan: commits what the last round made known and tells whether the tree is finished
         hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
-                           ctx->batch, ctx->hist_counts, ctx->scan_counters, F, p->num_leaves, ctx->batch_max,
+                           ctx->batch, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                            ctx->max_expand, p_max, out);
         QG_HIP(ctx, hipGetLastError());
         QG_HIP(ctx, hipMemcpyAsync(ctx->host_state, ctx->step, sizeof(StepState), hipMemcpyDeviceToHost, ctx->stream));

@@ -487,3 +487,22 @@ def test_boost_iterations_lambdarank_lock_step():
         exp = oracle.update_scores(before.cpu().numpy(), e.row_idx, e.leaf_begin, e.leaf_count,
                                    t.leaf_value.cpu().numpy()[:n], lr)
         assert np.array_equal(score.cpu().numpy(), exp)
+
+
+def test_create_rejects_leaf_budgets_beyond_the_bookkeeping():
+    from paper_2207_09682_amd import QgbdtError
+    with pytest.raises(QgbdtError):
+        _ctx(1000, 8, 32, L=4096)
+    ctx = _ctx(1000, 8, 32, L=600)            # fits
+    assert ctx.workspace_bytes > 0
+
+
+def test_tree_stats_after_a_tree():
+    cfg = workloads.CONFIGS[0]
+    wl = workloads.make_workload(cfg)
+    ctx = _ctx(wl.n_rows, cfg.n_features, cfg.n_bins, L=cfg.num_leaves)
+    g, h = workloads.gradients(wl, torch.zeros(wl.n_rows))
+    t = ctx.grow_tree(wl.bins.cuda(), g.cuda(), h.cuda(), 2, 2, 0, 0, cfg.num_leaves)
+    rounds, expanded, committed, nodes = ctx.tree_stats()
+    n = int(t.n_leaves.item())
+    assert committed == n - 1 and expanded >= committed and nodes == 2 * expanded + 1 and 1 <= rounds <= expanded + 1
