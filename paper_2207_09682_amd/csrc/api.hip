@@ -52,7 +52,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
                     c->idx[2], c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
-                    c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->step, c->batch, c->cand, c->hist_entries,
+                    c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->sorted_idx, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
     for (void* p : ptrs)
@@ -105,12 +105,11 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     c->rounds_hint = 10;
     {
         // the plan kernel keeps its sort and replay state of all nodes in LDS
-        int p_max = 64;
-        while (p_max < c->max_nodes) p_max <<= 1;
-        const size_t plan_lds = (size_t)p_max * 12 + (size_t)c->max_nodes * 12 + (size_t)(4 * L + 8) * 4;
+        const size_t p_max = (size_t)c->max_nodes + (c->max_nodes & 1);
+        const size_t plan_lds = p_max * 24 + (size_t)c->batch_max * 16 + (size_t)c->max_nodes * 12 + (size_t)(4 * L + 8) * 4;
         if (plan_lds > 160 * 1024) {
             delete c;
-            return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 680 leaves)", L, plan_lds);
+            return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 690 leaves)", L, plan_lds);
         }
     }
     int rc = QGBDT_OK;
@@ -149,6 +148,7 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals, 4);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->delta, 2);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->nodes, (size_t)c->max_nodes);
+    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->sorted_idx, (size_t)c->max_nodes);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->step, 1);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->batch, (size_t)c->batch_max);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->cand, (size_t)2 * c->batch_max * shape->n_features);

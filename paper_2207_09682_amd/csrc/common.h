@@ -36,7 +36,8 @@ struct StepState {
     int32_t rounds;
     int32_t n_part_items;  // row segments of the current round's partitions
     int32_t n_scan_items;  // histograms to scan in the current round
-    int32_t pad[2];
+    int32_t n_sorted;      // nodes in the kept gain order (see tree_plan_kernel)
+    int32_t pad[1];
     int64_t hist_units;    // rows*features of the histogram builds the sequential algorithm performs
     int64_t prof_rows_contig, prof_rows_idx;  // rows seen by histogram launches
     int64_t prof_launches;                    // histogram launches that had rows
@@ -168,6 +169,7 @@ struct qgbdt_ctx {
     int64_t* qtotals;      // [3] sum g~, sum h~, sum |g~|
     float* delta;          // [2]
     qgbdt::Node* nodes;          // [max_nodes]
+    int32_t* sorted_idx;         // [max_nodes] node ids by descending gain, kept from round to round
     qgbdt::StepState* step;      // [1]
     qgbdt::BatchEntry* batch;    // [batch_max]
     qgbdt::FeatCand* cand;       // [2*batch_max][F]

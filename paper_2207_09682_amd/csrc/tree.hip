@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N
     for (int64_t i = t; i < N; i += stride) idx0[i] = (int32_t)i;
     for (int64_t i = t; i < hist_words; i += stride) hist0[i] = 0;
     if (t == 0) {
-        step->done = 0; step->n_nodes = 1; step->n_leaves = 1; step->n_commits = 0; step->n_expanded = 0;
+        step->done = 0; step->n_sorted = 0; step->n_nodes = 1; step->n_leaves = 1; step->n_commits = 0; step->n_expanded = 0;
         step->n_slots = 1; step->n_batch = 0; step->rounds = 0; step->n_part_items = 0; step->n_scan_items = 1;
         step->hist_units = N * (int64_t)F;
         Node r;
@@ -99,34 +99,6 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Sorts P (a power of two) 64-bit keys in LDS into descending order with their payloads:
-// bitonic network, one compare-exchange per thread and step.  A wavefront's 64 threads own
-// 128 consecutive elements in every step with a distance of at most 64, so only the steps
-// with a larger distance need a workgroup barrier.
-__device__ inline void bitonic_sort_desc(unsigned long long* key, int* val, int P) {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    __syncthreads();
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += nt) {
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int q = i | j;
-                const bool desc = (i & k) == 0;
-                const unsigned long long a = key[i], b = key[q];
-                if ((a < b) == desc) {
-                    key[i] = b; key[q] = a;
-                    const int va = val[i], vb = val[q];
-                    val[i] = vb; val[q] = va;
-                }
-            }
-            if (j > 64) __syncthreads();
-            else __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        }
-        if (k >= 128) __syncthreads();  // the next phase starts with a distance its wavefronts do not own
-    }
-    __syncthreads();
-}
-
 // Exclusive prefix sum over P values in LDS (in place); every thread owns a contiguous run.
 // Returns the total.
 __device__ inline int block_scan_array(int* v, int P, int* tmp /*[16]*/) {
@@ -150,8 +122,10 @@ __device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
 }
 
 // Commit phase and choice of the round's batch.  One workgroup of 1024 threads.
-//  1. All known nodes that can still be split are sorted by gain (LDS, bitonic); a node's rank
-//     is the number of nodes with a strictly larger gain.
+//  1. All known nodes are kept sorted by the gain of their best split: a node's gain never changes, so
+//     the order of the previous call is read back and last round's children are merged in (each
+//     finds its place by a binary search and a count; old entries shift by the number of new ones
+//     in front of them).  A node's rank is the number of nodes with a strictly larger gain.
 //  2. One wavefront replays best-first selection: the open leaves are kept in an array indexed
 //     by leaf id whose entries combine (rank, leaf id), so the leaf with the largest gain (ties:
 //     lowest leaf id) is one wavefront-wide maximum; it is committed if it has been expanded
@@ -160,58 +134,96 @@ __device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
 //  3. All threads write the outputs of the committed splits.
 //  4. The batch is chosen by walking the sorted order (prefix sums over sorted positions).
 __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
-                                                         int32_t* hist_counts, int F,
+                                                         int32_t* __restrict__ sorted_idx, int32_t* hist_counts, int F,
                                                          int num_leaves, int batch_max, int max_expand, int p_max,
                                                          TreeOut out) {
     if (step->done) return;
     extern __shared__ unsigned char plan_lds[];
     const int n_nodes0 = step->n_nodes;
+    const int n_old = step->n_sorted;        // nodes already in the sorted order (all but last round's children)
+    const int m_new = n_nodes0 - n_old;
     const int cap = 2 * max_expand + 1;  // nodes
-    int P = 64;
-    while (P < n_nodes0) P <<= 1;
+    const int P = n_nodes0;              // sorted positions in use
     unsigned long long* skey = reinterpret_cast<unsigned long long*>(plan_lds);  // [p_max] gain bits, sorted
     int* sidx = reinterpret_cast<int*>(skey + p_max);                            // [p_max] node at a sorted position
-    int* rankof = sidx + p_max;                                                  // [cap] -1: cannot be split
+    unsigned long long* okeys = reinterpret_cast<unsigned long long*>(sidx + p_max);  // [p_max] the order so far
+    int* oidx = reinterpret_cast<int*>(okeys + p_max);                                // [p_max]
+    unsigned long long* nkey = reinterpret_cast<unsigned long long*>(oidx + p_max);   // [2*batch_max] keys of the new nodes
+    int* rankof = reinterpret_cast<int*>(nkey + 2 * batch_max);                  // [cap] -1: cannot be split, -2: split
     int* posof = rankof + cap;                                                   // [cap] sorted position
     int* child = posof + cap;                                                    // [cap] left child, -1 if not expanded
     uint32_t* okey = reinterpret_cast<uint32_t*>(child + cap);                   // [num_leaves+1] by leaf id, 0: no gain
     int* onode = reinterpret_cast<int*>(okey + num_leaves + 1);                  // [num_leaves+1] node of a leaf id
     int* commit = onode + num_leaves + 1;                                        // [num_leaves] nodes committed, in order
     int* commit_lid = commit + num_leaves;                                       // [num_leaves] their leaf ids
-    int* flag = reinterpret_cast<int*>(skey);  // [P] per sorted position, reuses the keys once the ranks are known
-    int* flag2 = flag + p_max;                 // [P]
+    int* flag = reinterpret_cast<int*>(okeys);  // [P] per sorted position, reuses the old order once it is merged
+    int* flag2 = flag + p_max;                  // [P]
     __shared__ int s_tmp[16];
-    __shared__ int s_done, s_ncommit, s_commits0, s_leaves0, s_nleaves;
+    __shared__ int s_done, s_ncommit, s_nleaves;
     __shared__ unsigned long long s_units;
     const int tid = threadIdx.x;
     const int commits0 = step->n_commits, leaves0 = step->n_leaves;
     if (tid == 0) { s_done = 0; s_ncommit = 0; s_units = 0ull; }
-    for (int i = tid; i < P; i += blockDim.x) {
-        unsigned long long kb = 0ull;
-        if (i < n_nodes0) {
-            const Node* nd = &nodes[i];
-            const int st = nd->state;
-            const double kg = (nd->best.feature >= 0 && st != 2) ? nd->best.gain : -1.0;
-            if (kg > 0.0) kb = (unsigned long long)__double_as_longlong(kg);  // positive doubles order like their bits
-            child[i] = nd->expanded ? nd->child : -1;
-            if (st == 1) onode[nd->leaf_id] = i;
-        }
-        skey[i] = kb;
-        sidx[i] = i;
+    // A node's sort key never changes: the gain of its best split (0 bits when it has none).  The order of
+    // the nodes known at the previous call is kept in global memory; only last round's children are new.
+    for (int i = tid; i < n_nodes0; i += blockDim.x) {
+        const Node* nd = &nodes[i];
+        const int st = nd->state;
+        const bool splittable = nd->best.feature >= 0 && nd->best.gain > 0.0;
+        const unsigned long long kb = splittable ? (unsigned long long)__double_as_longlong(nd->best.gain) : 0ull;
+        child[i] = nd->expanded ? nd->child : -1;
+        if (st == 1) onode[nd->leaf_id] = i;
+        rankof[i] = st == 2 ? -2 : (splittable ? 0 : -1);  // ranks are filled in below
+        if (i >= n_old) nkey[i - n_old] = kb;
+        else skey[i] = kb;  // by node id for now; gathered into the kept order next
     }
-    bitonic_sort_desc(skey, sidx, P);
+    __syncthreads();
+    for (int p = tid; p < n_old; p += blockDim.x) {
+        const int i = sorted_idx[p];
+        oidx[p] = i;
+        okeys[p] = skey[i];
+    }
+    __syncthreads();
+    // merge: old entries keep their order and come first among equal keys; new ones follow by node id
+    for (int p = tid; p < n_old; p += blockDim.x) {
+        const unsigned long long kb = okeys[p];
+        int c = 0;
+        for (int u = 0; u < m_new; ++u) c += nkey[u] > kb ? 1 : 0;
+        posof[oidx[p]] = p + c;
+    }
+    for (int t = tid; t < m_new; t += blockDim.x) {
+        const unsigned long long kb = nkey[t];
+        int lo = 0, hi = n_old;  // first old position with a smaller key
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (okeys[mid] >= kb) lo = mid + 1; else hi = mid;
+        }
+        int b = 0;
+        for (int u = 0; u < m_new; ++u) b += (nkey[u] > kb || (nkey[u] == kb && u < t)) ? 1 : 0;
+        posof[n_old + t] = lo + b;
+    }
+    __syncthreads();
+    for (int p = tid; p < n_old; p += blockDim.x) {
+        const int q = posof[oidx[p]];
+        skey[q] = okeys[p]; sidx[q] = oidx[p];
+    }
+    __syncthreads();  // (the loop above read skey-by-id only through okeys; new entries may now overwrite it)
+    for (int t = tid; t < m_new; t += blockDim.x) {
+        const int q = posof[n_old + t];
+        skey[q] = nkey[t]; sidx[q] = n_old + t;
+    }
+    __syncthreads();
     for (int p = tid; p < P; p += blockDim.x) {
         const int i = sidx[p];
-        if (i >= n_nodes0) continue;
-        const unsigned long long kb = skey[p];
-        posof[i] = p;
-        int r = -1;
-        if (kb != 0ull) {
-            r = p;
+        sorted_idx[p] = i;
+        if (rankof[i] == 0) {
+            const unsigned long long kb = skey[p];
+            int r = p;
             while (r > 0 && skey[r - 1] == kb) --r;  // equal gains share a rank
+            rankof[i] = r;
         }
-        rankof[i] = r;
     }
+    if (tid == 0) step->n_sorted = n_nodes0;
     __syncthreads();
     for (int l = tid; l < leaves0; l += blockDim.x) {
         const int r = rankof[onode[l]];
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         }
         if (tid == 0) {
-            s_ncommit = n_commits - commits0; s_commits0 = commits0; s_leaves0 = leaves0; s_nleaves = n_leaves;
+            s_ncommit = n_commits - commits0; s_nleaves = n_leaves;
             step->n_commits = n_commits; step->n_leaves = n_leaves;
         }
     }
@@ -287,10 +299,12 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     // the leaf the replay stopped at is the best of them) and, one level ahead, the not yet
     // expanded children of expanded open leaves (class 1).  A node's rows outlive the expansion of
     // its children, so expanding the children of a leaf whose split is not committed yet is safe.
-    // flag: 1 = committed in this call, 1<<16 = class 0 candidate;  flag2: class (1 or 2), 0 none.
+    // flag: 1 = committed (in this call or before), 1<<16 = class 0 candidate;  flag2: class (1 or 2), 0 none.
     for (int p = tid; p < P; p += blockDim.x) { flag[p] = 0; flag2[p] = 0; }
     __syncthreads();
     for (int c = tid; c < n_commit; c += blockDim.x) flag[posof[commit[c]]] = 1;
+    for (int i = tid; i < n_nodes0; i += blockDim.x)
+        if (rankof[i] == -2) flag[posof[i]] = 1;  // split in an earlier call
     const int n_leaves_now = s_nleaves;
     for (int l = tid; l < n_leaves_now; l += blockDim.x) {
         if (okey[l] == 0u) continue;
@@ -538,10 +552,9 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                            p->min_data_in_leaf, p->min_sum_hessian);
     if (rc != QGBDT_OK) return rc;
 
-    int p_max = 64;
-    while (p_max < ctx->max_nodes) p_max <<= 1;
-    const size_t plan_lds = (size_t)p_max * (sizeof(unsigned long long) + sizeof(int)) +
-                            (size_t)ctx->max_nodes * 3 * sizeof(int) + (size_t)(4 * p->num_leaves + 8) * sizeof(int);
+    const int p_max = ctx->max_nodes + (ctx->max_nodes & 1);  // even: 8-byte arrays follow 4-byte ones
+    const size_t plan_lds = (size_t)p_max * 24 + (size_t)ctx->batch_max * 16 + (size_t)ctx->max_nodes * 12 +
+                            (size_t)(4 * p->num_leaves + 8) * sizeof(int);
     if (plan_lds > 160 * 1024)
         return set_error(ctx, QGBDT_E_UNSUPPORTED, "max_leaves=%d needs %zu bytes of LDS for the growth bookkeeping (limit 160 KB)",
                          ctx->shape.max_leaves, plan_lds);
@@ -554,7 +567,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     for (;;) {
         for (int r = 0; r < to_launch; ++r) {
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
-                               ctx->batch, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
+                               ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                                ctx->max_expand, p_max, out);
             rc = launch_batch_partition_count(ctx, rows);
             if (rc != QGBDT_OK) return rc;
@@ -573,7 +586,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         launched += to_launch;
         // one more plan: commits what the last round made known and tells whether the tree is finished
         hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
-                           ctx->batch, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
+                           ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                            ctx->max_expand, p_max, out);
         QG_HIP(ctx, hipGetLastError());
         QG_HIP(ctx, hipMemcpyAsync(ctx->host_state, ctx->step, sizeof(StepState), hipMemcpyDeviceToHost, ctx->stream));
