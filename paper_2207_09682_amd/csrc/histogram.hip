@@ -1,24 +1,30 @@
 // Histogram construction (Algorithm 1 with quantized gradients, Sec. 4.1) with
-// workgroup-local packed accumulators in LDS merged into the leaf's total
-// histogram by 64-bit integer atomics (hierarchical buffers of Sec. 6.1, packed
-// gradient|hessian words of Sec. 6.2, width rule of Sec. 7.4.3).
+// workgroup-local packed accumulators in LDS that are combined into the leaf's total
+// histogram (hierarchical buffers of Sec. 6.1, packed gradient|hessian words of
+// Sec. 6.2, width rule of Sec. 7.4.3).
 //
 // Bound by HBM traffic on one side -- per row one F-byte bin row, one 2-byte packed
 // (g~,h~) and, for a gathered leaf, one 4-byte row id are read once -- and by the
-// LDS atomic rate on the other: one 64-lane ds_add takes about 5.7 clocks per CU
-// whatever the (<= 4-way) bank conflicts, i.e. ~7e12 bin updates/s on the chip,
-// the same order as the ~6e12 bin bytes/s that HBM streams.
+// LDS atomic rate on the other: an LDS atomic costs ~5 clocks per wavefront instruction
+// and CU (64-bit ones ~6.5), whatever the number of active lanes and the (<= 4-way) bank
+// conflicts, i.e. ~7e12 bin updates/s on the chip, the same order as the ~6e12 bin
+// bytes/s that HBM streams.
 //
 // Work decomposition.  A launch serves a table of histogram builds (one per leaf);
 // every build is cut into row groups and the (build, group) pairs are the work
 // items the workgroups loop over.  A workgroup accumulates a group chunk by chunk
-// (a chunk is as many rows as a 16|16 packed accumulator can take) and merges each
-// chunk into the build's [bin][feature] histogram.
+// (a chunk is as many rows as a 16|16 packed accumulator can take).  The last chunk of
+// a group -- the only one when the group fits a chunk, which the group sizing aims
+// for -- is handed over as it is: the local bins are copied to the group's slot with plain
+// stores and hist_reduce_kernel adds the slots of a build to its histogram.  Earlier
+// chunks are merged with 64-bit global atomics (same-address atomics from a thousand
+// workgroups serialize at the memory side: four times the cost of the slots).
 //
-// Local histogram layout: [bin][feature] with a pitch of 32 words for narrow tiles,
+// Local histogram layout: [bin][feature column]; for narrow rows the pitch is 32 words,
 // so the LDS bank is the feature; the order in which a lane issues the atomics of
 // the four features of a dword is rotated per row so that lanes of one instruction
-// spread over the features.
+// spread over the features.  Lanes that have no place in a tile are masked for the
+// atomics (they would otherwise hit one word together and serialize).
 #include <type_traits>
 
 #include "common.h"

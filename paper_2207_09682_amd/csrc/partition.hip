@@ -1,7 +1,12 @@
 // Stable row partition of a leaf's index slice (the set I_s of Algorithm 1) by
-// bins[row][feature] <= bin.  Two passes over a fixed grid: per-workgroup counts
-// of left-going rows (flags kept as bytes), then an order-preserving scatter into
-// the other index buffer with offsets from the counts.  No inter-workgroup waits.
+// bins[row][feature] <= bin.  Two passes: counts of left-going rows per segment
+// (flags kept as bytes), a prefix over the segments, then an order-preserving scatter
+// into another buffer.  No inter-workgroup waits: signalling between workgroups goes
+// through the memory side on this chip (~1-2 us per hop), which a single-pass
+// partition with look-back could not hide.  First the stand-alone form behind
+// qgbdt_partition_rows (row ids only), then the batched form of grow_tree, which serves
+// all nodes of a round at once and, for narrow rows, also moves the bin rows and packed
+// gradients into leaf order.
 #include "common.h"
 
 namespace qgbdt {

@@ -9,14 +9,16 @@
 //      with the largest gain is committed as the next split if it has already been
 //      expanded, and its children become open leaves; the replay stops at the first
 //      leaf that has not been expanded;
-//   2. expands that leaf and, speculatively, the other open leaves with the largest
-//      gains (as many as the leaf budget still allows): one batched partition, one
-//      batched histogram build for the smaller children, one batched subtraction and
-//      split search for all children.
+//   2. expands that leaf and, speculatively, other nodes with large gains -- open leaves
+//      and, one level ahead, children of open leaves that are already expanded -- as
+//      far as the leaf budget can still reach them: one batched partition, one batched
+//      histogram build for the smaller children, one batched subtraction and split
+//      search for all children.
 // A speculative expansion that the replay never reaches is simply not part of the
 // tree: its node stays a leaf and its row slice is untouched, because children are
-// always written to the other index buffer.  Split numbers and leaf ids are assigned
-// at commit time, so the result equals the sequential one bit for bit.
+// always written to another buffer (three buffers rotate with the depth, so a node's
+// rows survive the expansion of its children).  Split numbers and leaf ids are
+// assigned at commit time, so the result equals the sequential one bit for bit.
 //
 // The host enqueues whole rounds without reading anything back; after the expected
 // number of rounds it reads one status word to learn whether more are needed.
