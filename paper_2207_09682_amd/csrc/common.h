@@ -79,9 +79,9 @@ struct PartWork {
 };
 
 struct HistPlan {
-    int32_t ft;          // features per workgroup tile (multiple of 4)
+    int32_t ft;          // features per workgroup tile (a multiple of 4 unless the tile is the whole row)
     int32_t ftp;         // padded tile width in LDS words
-    int32_t dpr;         // dwords per row per tile = ft/4
+    int32_t dpr;         // dwords per row per tile = ceil(ft/4)
     int32_t rows_per_it; // rows one wavefront covers per iteration
     int32_t n_tiles;     // feature tiles
     int32_t threads;     // workgroup size
@@ -98,6 +98,8 @@ struct HistPlan {
     int32_t single_rows;  // a group of at most this many rows is accumulated in one chunk by every kernel variant
     int32_t pad16;        // local bins keep 4 unused words after every 16 features (wide rows, 16-byte loads)
     int32_t wide_v;       // > 0: wide rows are read in pieces of this many bytes per lane (8 or 16)
+    int32_t ragged;       // feature count not a multiple of 4: unaligned dword loads, last dword of a tile row partial
+    int32_t bytewise;     // no dword kernel applies (rows or a tile narrower than 4 bytes): one byte load per bin
 };
 
 // Rows per row group when `total` rows of `n_entries` builds are shared out: about max_groups

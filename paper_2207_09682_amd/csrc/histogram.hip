@@ -168,7 +168,22 @@ __device__ __forceinline__ void store_partial(typename Acc<W>::word* lds, int ld
 // between them and the LDS takes one 64-lane atomic per ~5.7 clocks, so a bin may
 // cost ~5 VALU instructions: one bit-field extract and one 24-bit multiply-add
 // into the byte address of its LDS word, plus its share of the per-row work.
-template <int W, bool IDX, int U>
+//
+// RAG (feature count not a multiple of 4): rows start at any byte, so the dwords are read
+// unaligned, and the last dword of a tile row is moved back to end with the tile row (it then
+// overlaps its neighbour and only its upper bytes count), so that no load leaves the row.
+// Tiles are at least 4 features wide in this mode.
+template <bool RAG>
+__device__ __forceinline__ uint32_t load_bins4(const uint8_t* p) {
+    if (RAG) {
+        uint32_t v;
+        __builtin_memcpy(&v, p, 4);
+        return v;
+    }
+    return *reinterpret_cast<const uint32_t*>(p);
+}
+
+template <int W, bool IDX, int U, bool RAG>
 __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
@@ -199,12 +214,16 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
     const bool lane_on = (r < rpi) && (4 * q < ft);
     if (!lane_on) { q = 0; r = 0; }
     const int rot = (q >> 3) + r;
+    const int nval = RAG ? min(4, ft - 4 * q) : 4;  // features in the lane's dword
+    const int back = 4 - nval;                      // bytes its load is moved back
     uint32_t sh[4], fl4[4];  // bit offset of the k-th bin in the dword, byte offset of its feature column in LDS
+    bool okk[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int c = (k + rot) & 3;
-        sh[k] = 8 * c;
-        fl4[k] = (uint32_t)(4 * q + c + (plan.pad16 ? 4 * (q >> 2) : 0)) * (uint32_t)sizeof(word);
+        okk[k] = c < nval;
+        sh[k] = 8 * (okk[k] ? c + back : 0);
+        fl4[k] = (uint32_t)(4 * q + (okk[k] ? c : 0) + (plan.pad16 ? 4 * (q >> 2) : 0)) * (uint32_t)sizeof(word);
     }
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);  // LDS bytes per bin row
     const int S = U * rpi;                                          // rows per block of one wavefront
@@ -219,7 +238,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
-        const uint8_t* colbase = src.bins[sb] + f0 + 4 * q;
+        const uint8_t* colbase = src.bins[sb] + f0 + 4 * q - back;
         const int16_t* gh = src.gh[sb];
 
         // a group without rows still hands over its (empty) bins
@@ -244,7 +263,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        d[u] = *reinterpret_cast<const uint32_t*>(colbase + rows[u] * F);
+                        d[u] = load_bins4<RAG>(colbase + rows[u] * F);
                         gv[u] = gh[rows[u]];
                     }
 #pragma unroll
@@ -256,7 +275,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
                 for (int ro = wave * S; ro < crow; ro += n_waves * S) {
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        dn[u] = *reinterpret_cast<const uint32_t*>(colbase + rown[u] * F);
+                        dn[u] = load_bins4<RAG>(colbase + rown[u] * F);
                         gn[u] = gh[rown[u]];
                     }
 #pragma unroll
@@ -274,7 +293,8 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
-                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
+                                if (!RAG || okk[k])
+                                    Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
                             }
                         }
                     }
@@ -698,7 +718,8 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (w == 0) w = (n16 >= 1024) ? 16 : 32;  // a 16|16 chunk must amortise its merge
     const int wbytes = (w == 16) ? 4 : 8;
     const int lds_budget = 64 * 1024;
-    const bool fast = (F % 4 == 0);
+    const bool aligned = (F % 4 == 0);
+    bool fast = aligned || F >= 4;  // dword kernels; rows of any width >= 4 bytes (unaligned loads)
     int wide_ft = 0;
     if (F % 16 == 0 && F > 64) {
         // wide rows: 16-byte pieces, padded local bins (20 words per 16 features)
@@ -726,24 +747,27 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
             double best_score = -1.0;
             for (int c = 0; c < 11; ++c) {
                 const int ft = cands[c];
-                if (ft <= 0 || ft > F || ft % 4) continue;
+                if (ft <= 0 || ft > F || (ft % 4 && ft != F)) continue;
                 if (pass == 0 && ft < 32 && ft != F) continue;
-                const int ftp = (ft <= 32) ? 32 : ft;
+                const int ftp = (ft <= 32) ? 32 : (ft + 3) / 4 * 4;
                 if ((int64_t)ftp * nb * wbytes > lds_budget) continue;
-                const int dpr = ft / 4;
+                const int dpr = (ft + 3) / 4;
                 const int rpi = 64 / dpr;
                 const int tiles = (F + ft - 1) / ft;
+                if (F - (tiles - 1) * ft < 4) continue;  // every tile row holds at least one dword
                 const double score = ((double)(rpi * dpr) / 64.0) * ((double)F / ((double)tiles * ft));
                 if (score > best_score + 1e-9) { best_score = score; best_ft = ft; }
             }
         }
-        if (best_ft == 0) best_ft = 4;
+        if (best_ft == 0 && aligned) best_ft = 4;
+        if (best_ft == 0) fast = false;
         p.ft = best_ft;
-        p.ftp = (best_ft <= 32) ? 32 : best_ft;
-        p.dpr = best_ft / 4;
-        p.rows_per_it = 64 / p.dpr;
+        p.ftp = (best_ft <= 32) ? 32 : (best_ft + 3) / 4 * 4;
+        p.dpr = (best_ft + 3) / 4;
+        p.rows_per_it = p.dpr > 0 ? 64 / p.dpr : 0;
         p.lds_bytes = p.ftp * nb * wbytes;
-    } else {
+    }
+    if (!wide_ft && !fast) {
         int ft = lds_budget / (nb * wbytes);
         if (ft > F) ft = F;
         if (ft < 1) ft = 1;
@@ -767,8 +791,10 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (groups < 1) groups = 1;
     p.max_groups = groups;
     p.acc_width = w;
+    p.ragged = (fast && !aligned) ? 1 : 0;
+    p.bytewise = fast ? 0 : 1;
     p.flat_lanes = 0; p.flat_rows = 0;
-    if (fast && p.n_tiles == 1 && F >= 16 && F <= 64) {
+    if (aligned && p.n_tiles == 1 && F >= 16 && F <= 64) {
         for (int l = 64; l >= 32; --l)
             if ((16 * l) % F == 0) { p.flat_lanes = l; p.flat_rows = 16 * l / F; break; }
     }
@@ -815,7 +841,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     // row-group lanes in multiples of 8 (one per XCD), times the feature tiles, as one flat grid
     const int64_t lanes = (groups + 7) / 8 * 8;
     dim3 grid((unsigned)(lanes * plan.n_tiles)), block(plan.threads);
-    const bool fast = (F % 4 == 0);
+    const bool fast = !plan.bytewise;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (ctx->profiling && ctx->ev_used + 2 <= ctx->ev_cap) {
         e0 = ctx->ev[ctx->ev_used++]; e1 = ctx->ev[ctx->ev_used++];
@@ -854,9 +880,16 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     } else if (fast) {
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
-#define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                              \
-    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
-                       entries, table_counts, hist_base, partials, F, nb, plan, step)
+#define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                               \
+    do {                                                                                                           \
+        if (plan.ragged)                                                                                           \
+            hipLaunchKernelGGL((hist_kernel<W_, IDX_, (U_ > 4 ? 4 : U_), true>), grid, block, plan.lds_bytes,      \
+                               ctx->stream, rows, idx, entries, table_counts, hist_base, partials, F, nb, plan,    \
+                               step);                                                                              \
+        else                                                                                                       \
+            hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_, false>), grid, block, plan.lds_bytes, ctx->stream, rows, \
+                               idx, entries, table_counts, hist_base, partials, F, nb, plan, step);                \
+    } while (0)
 #define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
     switch (U) {                                                                        \
         case 8: QG_LAUNCH_HIST(W_, IDX_, 8); break;                                     \

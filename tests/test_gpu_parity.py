@@ -80,7 +80,12 @@ HIST_SHAPES = [
     (30011, 28, 63, 2, 2),
     (20000, 200, 255, 3, 8),     # tiled features, 8-bit hessians
     (6000, 2000, 63, 3, 3),      # wide
-    (9000, 5, 16, 3, 3),         # feature count not a multiple of 4: generic kernel
+    (9000, 5, 16, 3, 3),         # feature count not a multiple of 4: unaligned rows, partial last dword
+    (4000, 3, 256, 3, 3),        # rows narrower than a dword: one byte load per bin
+    (8000, 90, 255, 3, 3),       # two ragged tiles
+    (6000, 30, 63, 4, 4),
+    (5000, 65, 255, 3, 3),       # 64 + 1 features: the tiles are cut so that none is narrower than a dword
+    (5000, 7, 255, 2, 2),
     (7000, 64, 256, 4, 4),
     (5000, 36, 100, 3, 3),
 ]
