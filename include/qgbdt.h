@@ -16,7 +16,8 @@
  *  - Every function returns 0 (QGBDT_OK) or a negative QGBDT_E_* code;
  *    qgbdt_last_error() gives a message.  No exception crosses the boundary.
  *  - Layouts
- *      bins   uint8 [n_rows][n_features], row-major, values in [0, n_bins)
+ *      bins   uint8 (uint16 when shape.bin_bytes = 2) [n_rows][n_features], row-major,
+ *             values in [0, n_bins)
  *      gh     int16 [n_rows]: quantized gradient (signed) in the high byte,
  *             quantized hessian (unsigned) in the low byte
  *      hist   int64 [n_bins][n_features] (bin-major: the order in which the kernels
@@ -54,8 +55,8 @@ typedef struct qgbdt_ctx qgbdt_ctx;
 typedef struct {
     int64_t n_rows;     /* N, 1 .. 2^31-1 */
     int32_t n_features; /* J of Algorithm 1 */
-    int32_t n_bins;     /* bins per feature, 2 .. 256 */
-    int32_t bin_bytes;  /* 1 (uint8 bins) */
+    int32_t n_bins;     /* bins per feature, 2 .. 256 (uint8 bins) or 2 .. 1024 (uint16 bins) */
+    int32_t bin_bytes;  /* 1: uint8 bins; 2: uint16 bins (every `bins` argument is then uint16 [n_rows][n_features]) */
     int32_t max_leaves; /* largest num_leaves grow_tree will be asked for (at most ~680: the growth
                            bookkeeping of all nodes lives in one workgroup's LDS) */
 } qgbdt_shape;

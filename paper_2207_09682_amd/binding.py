@@ -155,6 +155,10 @@ class Context:
             raise QgbdtError(rc, self.lib.qgbdt_last_error(None).decode())
 
     # -- helpers ---------------------------------------------------------------
+    def _bins(self, bins: torch.Tensor) -> int:
+        """Device pointer of the bin matrix: uint8, or uint16 for a context created with bin_bytes=2."""
+        return _dev(bins, torch.uint16 if self.shape.bin_bytes == 2 else torch.uint8, "bins")
+
     def _chk(self, rc: int):
         if rc != 0:
             raise QgbdtError(rc, self.lib.qgbdt_last_error(self._h).decode())
@@ -199,7 +203,7 @@ class Context:
         W = self.shape.n_features * self.shape.n_bins
         hist = hist_out if hist_out is not None else torch.empty(W, dtype=torch.int64, device=self.device)
         self._chk(self.lib.qgbdt_build_histograms(
-            self._h, _dev(bins, torch.uint8, "bins"), _dev(gh, torch.int16, "gh"),
+            self._h, self._bins(bins), _dev(gh, torch.int16, "gh"),
             _dev(row_idx, torch.int32, "row_idx") if row_idx is not None else None, begin, count, bits_g, bits_h,
             acc_width, _dev(hist, torch.int64, "hist_out")))
         return hist
@@ -225,7 +229,7 @@ class Context:
     def partition_rows(self, bins, row_idx, begin, count, feature, bin):
         self._sync_stream()
         n_left = torch.empty(1, dtype=torch.int64, device=self.device)
-        self._chk(self.lib.qgbdt_partition_rows(self._h, _dev(bins, torch.uint8, "bins"),
+        self._chk(self.lib.qgbdt_partition_rows(self._h, self._bins(bins),
                                                 _dev(row_idx, torch.int32, "row_idx"), begin, count, feature, bin,
                                                 n_left.data_ptr()))
         return n_left
@@ -256,7 +260,7 @@ class Context:
         tree = tree if tree is not None else self.new_tree()
         p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
         tp = tree.ptrs()
-        self._chk(self.lib.qgbdt_grow_tree(self._h, _dev(bins, torch.uint8, "bins"), _dev(g, torch.float32, "g"),
+        self._chk(self.lib.qgbdt_grow_tree(self._h, self._bins(bins), _dev(g, torch.float32, "g"),
                                            _dev(h, torch.float32, "h"), C.byref(p), iteration, C.byref(tp),
                                            _dev(tree.row_idx, torch.int32, "row_idx")))
         return tree
@@ -303,11 +307,11 @@ class Context:
         tp = tree.ptrs()
         if group_size > 0:
             self._chk(self.lib.qgbdt_boost_iteration_lambdarank(
-                self._h, _dev(bins, torch.uint8, "bins"), _dev(label, torch.float32, "relevance"), int(group_size),
+                self._h, self._bins(bins), _dev(label, torch.float32, "relevance"), int(group_size),
                 _dev(score, torch.float32, "score"), C.byref(p), iteration, float(learning_rate), C.byref(tp),
                 _dev(tree.row_idx, torch.int32, "row_idx")))
         else:
-            self._chk(self.lib.qgbdt_boost_iteration(self._h, _dev(bins, torch.uint8, "bins"),
+            self._chk(self.lib.qgbdt_boost_iteration(self._h, self._bins(bins),
                                                      _dev(label, torch.float32, "label"),
                                                      _dev(score, torch.float32, "score"), C.byref(p), iteration,
                                                      float(learning_rate), C.byref(tp),

@@ -81,11 +81,11 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (!out || !shape) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
     *out = nullptr;
     if (shape->n_rows < 1 || shape->n_rows > 2147483647LL || shape->n_features < 1 || shape->n_bins < 2 ||
-        shape->n_bins > 256 || shape->max_leaves < 1)
+        shape->n_bins > (shape->bin_bytes == 2 ? 1024 : 256) || shape->max_leaves < 1)
         return set_error(nullptr, QGBDT_E_INVALID_ARG, "shape out of range (rows %lld, features %d, bins %d, leaves %d)",
                          (long long)shape->n_rows, shape->n_features, shape->n_bins, shape->max_leaves);
-    if (shape->bin_bytes != 1)
-        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "bin_bytes=%d: only uint8 bins are built", shape->bin_bytes);
+    if (shape->bin_bytes != 1 && shape->bin_bytes != 2)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "bin_bytes=%d: bins are uint8 (1) or uint16 (2)", shape->bin_bytes);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
         return set_error(nullptr, QGBDT_E_HIP, "no HIP device: this library has no CPU path");
@@ -114,7 +114,8 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     }
     int rc = QGBDT_OK;
     // narrow rows: moving a row costs less than gathering it twice per level
-    c->ordered = (shape->n_features % 4 == 0 && shape->n_features >= 16 && shape->n_features <= 64) ? 1 : 0;
+    c->ordered = (shape->bin_bytes == 1 && shape->n_features % 4 == 0 && shape->n_features >= 16 &&
+                  shape->n_features <= 64) ? 1 : 0;
     if (c->ordered) {
         for (int b = 0; b < 3 && rc == QGBDT_OK; ++b) {
             rc = ws_alloc(c, &c->obins[b], (size_t)N * shape->n_features);

@@ -598,8 +598,11 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
     }
 }
 
-// Any feature count (no alignment assumption): one byte load per (row, feature).
-template <int W>
+// Any feature count and bin type (no alignment assumption): one load per (row, feature).  Serves 16-bit
+// bins and rows or tiles narrower than a dword.  lane -> (row r of the iteration, feature f of the
+// tile); a wavefront covers 64/C rows per iteration, C = the tile width rounded up to a power of two
+// (tiles wider than 64 features are walked in steps of 64).
+template <int W, typename BIN>
 __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource src, IdxSet idxs, int use_idx,
                                                             const HistEntry* __restrict__ entries,
                                                             const int32_t* __restrict__ table_counts,
@@ -618,6 +621,11 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
     const int ft = min(plan.ft, F - f0);
     const int lds_words = ft * nb;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    int C = 1;
+    while (C < ft && C < 64) C <<= 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int rpi = 64 / C;                  // rows per wavefront iteration
+    const int r = lane / C, fl = lane % C;   // the lane's row of the iteration and first feature
     for (int item = glane; item < n_items; item += n_lanes) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
@@ -626,18 +634,16 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
         int64_t* hist = hist_base + (int64_t)en.slot * F * nb;
         unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
         const int32_t* idx = use_idx ? (idxs.p[en.buf] + en.begin) : nullptr;
-        const uint8_t* bins = src.bins[use_idx ? BUF_ORIGINAL : en.buf];
+        const BIN* bins = reinterpret_cast<const BIN*>(src.bins[use_idx ? BUF_ORIGINAL : en.buf]);
         const int16_t* gh = src.gh[use_idx ? BUF_ORIGINAL : en.buf];
         for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             __syncthreads();
-            const int64_t n_el = (cend - cbegin) * ft;
-            for (int64_t e = threadIdx.x; e < n_el; e += blockDim.x) {
-                const int64_t p = cbegin + e / ft;
-                const int f = (int)(e % ft);
+            for (int64_t p = cbegin + wave * rpi + r; p < cend; p += n_waves * rpi) {
                 const int64_t i = idx ? (int64_t)idx[p] : en.begin + p;
-                const uint32_t b = bins[i * F + f0 + f];
-                Acc<W>::add(&lds[b * ft + f], Acc<W>::expand(gh[i]));
+                const word v = Acc<W>::expand(gh[i]);
+                const BIN* row = bins + i * F + f0;
+                for (int f = fl; f < ft; f += C) Acc<W>::add(&lds[(uint32_t)row[f] * ft + f], v);
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, lds_words * (int)sizeof(word), slot);
@@ -719,9 +725,11 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     const int wbytes = (w == 16) ? 4 : 8;
     const int lds_budget = 64 * 1024;
     const bool aligned = (F % 4 == 0);
-    bool fast = aligned || F >= 4;  // dword kernels; rows of any width >= 4 bytes (unaligned loads)
+    // dword kernels: 8-bit bins, rows of any width >= 4 bytes (unaligned loads when not a multiple of 4)
+    bool fast = s.bin_bytes == 1 && (aligned || F >= 4);
     int wide_ft = 0;
-    if (F % 16 == 0 && F > 64) {
+    if (!fast) {
+    } else if (F % 16 == 0 && F > 64) {
         // wide rows: 16-byte pieces, padded local bins (20 words per 16 features)
         for (int ft = 256; ft >= 32 && !wide_ft; ft >>= 1)
             if ((int64_t)(ft + ft / 4) * nb * wbytes <= lds_budget) wide_ft = ft;
@@ -794,7 +802,7 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.ragged = (fast && !aligned) ? 1 : 0;
     p.bytewise = fast ? 0 : 1;
     p.flat_lanes = 0; p.flat_rows = 0;
-    if (aligned && p.n_tiles == 1 && F >= 16 && F <= 64) {
+    if (fast && aligned && p.n_tiles == 1 && F >= 16 && F <= 64) {
         for (int l = 64; l >= 32; --l)
             if ((16 * l) % F == 0) { p.flat_lanes = l; p.flat_rows = 16 * l / F; break; }
     }
@@ -905,12 +913,16 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         }
 #undef QG_LAUNCH_HIST_U
 #undef QG_LAUNCH_HIST
-    } else if (plan.acc_width == 16) {
-        hipLaunchKernelGGL(hist_generic_kernel<16>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
-                           use_idx ? 1 : 0, entries, table_counts, hist_base, partials, F, nb, plan, step);
     } else {
-        hipLaunchKernelGGL(hist_generic_kernel<32>, grid, block, plan.lds_bytes, ctx->stream, rows, idx,
-                           use_idx ? 1 : 0, entries, table_counts, hist_base, partials, F, nb, plan, step);
+#define QG_LAUNCH_GENERIC(W_, BIN_)                                                                              \
+    hipLaunchKernelGGL((hist_generic_kernel<W_, BIN_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
+                       use_idx ? 1 : 0, entries, table_counts, hist_base, partials, F, nb, plan, step)
+        if (ctx->shape.bin_bytes == 2) {
+            if (plan.acc_width == 16) QG_LAUNCH_GENERIC(16, uint16_t); else QG_LAUNCH_GENERIC(32, uint16_t);
+        } else {
+            if (plan.acc_width == 16) QG_LAUNCH_GENERIC(16, uint8_t); else QG_LAUNCH_GENERIC(32, uint8_t);
+        }
+#undef QG_LAUNCH_GENERIC
     }
     QG_HIP(ctx, hipGetLastError());
     {

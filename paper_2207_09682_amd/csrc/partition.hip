@@ -26,7 +26,12 @@ __global__ void set_part_work_kernel(PartWork* w, int64_t begin, int64_t count, 
     }
 }
 
-__global__ __launch_bounds__(256) void part_count_kernel(const uint8_t* __restrict__ bins, int F,
+// Bin of (row, feature) in a row-major matrix of 8-bit (bb = 1) or 16-bit (bb = 2) bins.
+__device__ __forceinline__ int bin_at(const uint8_t* __restrict__ bins, int64_t at, int bb) {
+    return bb == 2 ? (int)reinterpret_cast<const uint16_t*>(bins)[at] : (int)bins[at];
+}
+
+__global__ __launch_bounds__(256) void part_count_kernel(const uint8_t* __restrict__ bins, int bb, int F,
                                                          const int32_t* __restrict__ buf0,
                                                          const int32_t* __restrict__ buf1,
                                                          const PartWork* __restrict__ work,
@@ -50,7 +55,7 @@ __global__ __launch_bounds__(256) void part_count_kernel(const uint8_t* __restri
     int cnt = 0;
     for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
         const int64_t row = src[wk.begin + p];
-        const int fl = bins[row * F + wk.feature] <= wk.bin;
+        const int fl = bin_at(bins, row * F + wk.feature, bb) <= wk.bin;
         flags[wk.begin + p] = (uint8_t)fl;
         cnt += fl;
     }
@@ -130,7 +135,8 @@ int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, in
     if (g > PART_GROUPS) g = PART_GROUPS;
     if (g < 1) g = 1;
     const int64_t W = (int64_t)F * ctx->shape.n_bins;
-    hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, bins, F, buf0, buf1, work,
+    hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, bins, ctx->shape.bin_bytes, F, buf0,
+                       buf1, work,
                        ctx->flags, ctx->part_counts, ctx->hist_pool, W);
     hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, buf0, buf1, buf0, buf1,
                        work, ctx->flags, ctx->part_counts, n_left_out);
@@ -176,7 +182,7 @@ __device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, 
 // that this round's builds accumulate into are cleared.  In ordered mode the rows of a
 // node are physically contiguous in its buffer and the bin is read at the row's position;
 // otherwise it is gathered from the original matrix through the row id.
-__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int F, IdxSet idxs,
+__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int bb, int F, IdxSet idxs,
                                                                const StepState* __restrict__ step,
                                                                const BatchEntry* __restrict__ batch,
                                                                const Node* __restrict__ nodes,
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, i
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
             const int64_t row = ordered ? p : (int64_t)src[p];
-            const int fl = brow[row * F + feature] <= bin;
+            const int fl = bin_at(brow, row * F + feature, bb) <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;
         }
@@ -327,8 +333,8 @@ static IdxSet idx_set(const qgbdt_ctx* ctx) {
 int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows) {
     const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
     hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                       ctx->ordered, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
-                       ctx->seg_counts, ctx->hist_pool, W);
+                       ctx->ordered, ctx->shape.bin_bytes, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch,
+                       ctx->nodes, ctx->flags, ctx->seg_counts, ctx->hist_pool, W);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

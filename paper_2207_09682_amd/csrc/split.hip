@@ -37,7 +37,7 @@ __global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n,
 // inclusive scan of the packed words (fields cannot overflow: every prefix is
 // bounded by the leaf totals), then each thread evaluates its threshold and the
 // workgroup keeps the feature's best one.
-__global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
+__global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                    const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                    const float* __restrict__ delta, int64_t min_data,
                                                    double min_sum_hess, FeatCand* cand_base) {
@@ -47,10 +47,10 @@ __global__ __launch_bounds__(256) void scan_kernel(int64_t* hist_base, const Sca
     const int64_t W = (int64_t)F * nb;
     const int64_t at = (int64_t)b * F + f;  // histograms are [bin][feature]
     const double dg = (double)delta[0], dh = (double)delta[1];
-    __shared__ int64_t wtot[4];
-    __shared__ double sg[4];
-    __shared__ int sb[4];
-    __shared__ int64_t sl[4];
+    __shared__ int64_t wtot[16];
+    __shared__ double sg[16];
+    __shared__ int sb[16];
+    __shared__ int64_t sl[16];
     for (int item = blockIdx.y; item < n_items; item += gridDim.y) {
         const ScanItem it = items[item];
         if (!it.valid) continue;

@@ -511,3 +511,100 @@ def test_tree_stats_after_a_tree():
     rounds, expanded, committed, nodes = ctx.tree_stats()
     n = int(t.n_leaves.item())
     assert committed == n - 1 and expanded >= committed and nodes == 2 * expanded + 1 and 1 <= rounds <= expanded + 1
+
+
+# ----------------------------------------------------------------------------
+# 16-bit bins (more than 256 bins per feature)
+# ----------------------------------------------------------------------------
+
+def _ctx16(N, F, nb, L=63):
+    from paper_2207_09682_amd import Context
+    return Context(N, F, nb, max_leaves=L, bin_bytes=2)
+
+
+@pytest.mark.parametrize("N,F,nb,bg,bh", [(20000, 10, 600, 3, 3), (9000, 33, 1024, 4, 4), (5000, 100, 300, 3, 8),
+                                          (3000, 1, 1000, 2, 2)])
+@pytest.mark.parametrize("acc", [0, 16, 32])
+def test_histogram_uint16_bins_bit_exact(N, F, nb, bg, bh, acc):
+    rng = np.random.default_rng(N + F + nb)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint16)
+    bins[:, 0] = np.where(rng.random(N) < 0.5, nb - 1, bins[:, 0])
+    gq, hq, gh = _rand_gh(rng, N, bg, bh, "cuda")
+    ctx = _ctx16(N, F, nb)
+    dbins = torch.from_numpy(bins).cuda()
+    idx = np.sort(rng.choice(N, N // 3, replace=False)).astype(np.int32)
+    didx = torch.from_numpy(idx).cuda()
+    for kw in (dict(), dict(begin=11, count=N - 30), dict(row_idx=idx), dict(row_idx=idx, begin=2, count=1),
+               dict(begin=4, count=0)):
+        exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq, **kw))
+        gkw = dict(kw)
+        if "row_idx" in gkw:
+            gkw["row_idx"] = didx
+            gkw.setdefault("count", idx.size)
+        got = ctx.build_histograms(dbins, gh, bits_g=bg, bits_h=bh, acc_width=acc, **gkw).cpu().numpy().reshape(nb, F)
+        assert np.array_equal(got, exp), (kw.keys(), acc)
+
+
+def test_find_best_splits_and_partition_uint16_bins():
+    from paper_2207_09682_amd import unpack_splits
+    rng = np.random.default_rng(77)
+    N, F, nb = 30000, 6, 1000
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint16)
+    bins[:, 3] = bins[:, 0]                                                # duplicated feature: ties
+    g = ((bins[:, 0] > 700).astype(np.float32) - 0.5 + rng.normal(size=N)).astype(np.float32)
+    h = rng.uniform(0.01, 0.25, N).astype(np.float32)
+    gq, hq, d = oracle.quantize_gradients(g, h, 3, 3, 9, 1)
+    leaves = [np.arange(N, dtype=np.int32), np.arange(0, N, 7, dtype=np.int32), np.arange(30, dtype=np.int32)]
+    hists = [oracle.build_histograms(bins, nb, gq, hq, row_idx=r) for r in leaves]
+    stats = np.array([[len(r), gq[r].astype(np.int64).sum(), hq[r].astype(np.int64).sum()] for r in leaves], np.int64)
+    ctx = _ctx16(N, F, nb)
+    dh = torch.from_numpy(np.stack([_pack_hist(x).reshape(-1) for x in hists])).cuda()
+    got = unpack_splits(ctx.find_best_splits(dh, torch.from_numpy(stats).cuda(), torch.from_numpy(d).cuda(), 5, 0.0))
+    for k, r in enumerate(leaves):
+        e = oracle.find_best_split(hists[k], len(r), int(stats[k, 1]), int(stats[k, 2]), d[0], d[1], 5, 0.0)
+        assert (got[k]["feature"], got[k]["bin"]) == (e.feature, e.bin)
+        assert got[k]["gain"] == pytest.approx(e.gain, rel=RTOL, abs=0.0)
+    idx = np.sort(rng.choice(N, N // 2, replace=False)).astype(np.int32)
+    dbins = torch.from_numpy(bins).cuda()
+    for begin, count, f, b in ((0, idx.size, 5, 600), (9, idx.size - 20, 0, 255), (0, idx.size, 1, 256), (3, 0, 0, 5)):
+        exp, nl = oracle.partition_rows(bins, idx, begin, count, f, b)
+        didx = torch.from_numpy(idx.copy()).cuda()
+        assert int(ctx.partition_rows(dbins, didx, begin, count, f, b).item()) == nl
+        assert np.array_equal(didx.cpu().numpy(), exp)
+
+
+def test_grow_tree_uint16_bins():
+    rng = np.random.default_rng(5)
+    N, F, nb, L = 60000, 12, 800, 63
+    x = rng.normal(size=(N, F)).astype(np.float32)
+    edges = np.quantile(x[:, :], np.linspace(0, 1, nb + 1)[1:-1], axis=0)
+    bins = np.stack([np.searchsorted(edges[:, f], x[:, f]) for f in range(F)], axis=1).astype(np.uint16)
+    w = rng.normal(size=F)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-(x @ w)))).astype(np.float32)
+    score = np.zeros(N, np.float32)
+    ctx = _ctx16(N, F, nb, L=L)
+    dbins = torch.from_numpy(bins).cuda()
+    for it in range(2):
+        p = 1.0 / (1.0 + np.exp(-score.astype(np.float64)))
+        g = (p - y).astype(np.float32); h = (p * (1 - p)).astype(np.float32)
+        t = ctx.grow_tree(dbins, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), 3, 3, 21, it, L,
+                          min_data_in_leaf=20)
+        e = oracle.grow_tree(bins, nb, g, h, 3, 3, 21, it, L, min_data=20)
+        _compare_tree(t, e, N)
+        assert int(np.max(e.split_bin)) > 255                               # thresholds beyond 8 bits are in play
+        n = e.n_leaves
+        for l in range(n):
+            rows = e.row_idx[e.leaf_begin[l]: e.leaf_begin[l] + e.leaf_count[l]]
+            score[rows] += np.float32(0.1 * e.leaf_value[l])
+
+
+def test_uint16_context_rejects_wrong_bin_type_and_too_many_bins():
+    from paper_2207_09682_amd import Context, QgbdtError
+    with pytest.raises(QgbdtError):
+        Context(100, 4, 1025, max_leaves=7, bin_bytes=2)
+    with pytest.raises(QgbdtError):
+        Context(100, 4, 257, max_leaves=7, bin_bytes=1)
+    ctx = _ctx16(100, 4, 300, L=7)
+    with pytest.raises(TypeError):
+        ctx.build_histograms(torch.zeros((100, 4), dtype=torch.uint8, device="cuda"),
+                             torch.zeros(100, dtype=torch.int16, device="cuda"), bits_g=3, bits_h=3)
