@@ -236,7 +236,7 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     rc = launch_fill_zero(ctx, hist_out, W);
     if (rc != QGBDT_OK) return rc;
     if (count == 0) return QGBDT_OK;
-    const HistPlan plan = make_hist_plan(ctx->shape, bits_g, bits_h, acc_width);
+    const HistPlan plan = make_hist_plan_for(ctx->shape, bits_g, bits_h, acc_width, count);
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
     RowSource rows;

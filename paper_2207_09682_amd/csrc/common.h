@@ -212,6 +212,7 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
                     int64_t* totals_out, float2* pairs_out);
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
+HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
 int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,

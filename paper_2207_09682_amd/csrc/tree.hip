@@ -528,6 +528,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                              (long long)tot[1], (long long)tot[2]);
     }
     const HistPlan plan = make_hist_plan(ctx->shape, p->bits_g, p->bits_h, p->acc_width);
+    const HistPlan root_plan = make_hist_plan_for(ctx->shape, p->bits_g, p->bits_h, p->acc_width, N);  // the root's build alone
     // Row sources: buffer 2 = the caller's matrix and the quantized gradients in original order;
     // in ordered mode buffers 0/1 are the leaf-ordered copies that the partition writes.
     RowSource rows;
@@ -545,10 +546,10 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
-                       ctx->hist_pool, W, plan);
-    rc = launch_hist(ctx, plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
+                       ctx->hist_pool, W, root_plan);
+    rc = launch_hist(ctx, root_plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
-                     (N + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
+                     (N + root_plan.min_rows_per_group - 1) / root_plan.min_rows_per_group, ctx->step);
     if (rc != QGBDT_OK) return rc;
     rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 1, ctx->delta,
                            p->min_data_in_leaf, p->min_sum_hessian);
