@@ -40,9 +40,16 @@ __global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n,
 __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                    const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                    const float* __restrict__ delta, int64_t min_data,
-                                                   double min_sum_hess, FeatCand* cand_base) {
+                                                   double min_sum_hess, FeatCand* cand_base, int glog) {
     const int n_items = *n_items_ptr;
-    const int f = blockIdx.x, b = threadIdx.x;
+    // Workgroup -> feature: histograms are [bin][feature], so the 16 features of a 128-byte line are
+    // read by 16 workgroups; consecutive workgroup ids go round-robin to the 8 XCDs, so the ids are
+    // dealt such that those 16 run next to each other behind one L2.
+    // (Fewer per group when there are too few features to keep all XCDs busy that way.)
+    const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+    const int f = ((s >> glog) * 8 + xcd) * (1 << glog) + (s & ((1 << glog) - 1));
+    if (f >= F) return;
+    const int b = threadIdx.x;
     const int lane = b & 63, wave = b >> 6;
     const int64_t W = (int64_t)F * nb;
     const int64_t at = (int64_t)b * F + f;  // histograms are [bin][feature]
@@ -112,12 +119,126 @@ __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const Sc
     }
 }
 
+// The same search for histograms of at most 64 bins and many features.  A workgroup of 16
+// wavefronts takes 16 consecutive features of an item: the [bin][16 features] tile (one 128-byte
+// line per bin) is read -- and, for a subtracted sibling, written back -- with coalesced accesses
+// and staged in LDS; wavefront w then scans feature w of the tile, lane = bin.
+__global__ __launch_bounds__(1024) void scan_tile_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
+                                                         const int32_t* __restrict__ n_items_ptr, int F, int nb,
+                                                         const float* __restrict__ delta, int64_t min_data,
+                                                         double min_sum_hess, FeatCand* cand_base) {
+    const int n_items = *n_items_ptr;
+    const int f0 = blockIdx.x * 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t W = (int64_t)F * nb;
+    const double dg = (double)delta[0], dh = (double)delta[1];
+    __shared__ int64_t tile[64 * 17];  // [bin][feature], pitch 17 words: a wavefront's column walk spreads over the banks
+    const int tf = threadIdx.x & 15, tb = threadIdx.x >> 4;  // tile loader: feature and bin of this thread
+    for (int item = blockIdx.y; item < n_items; item += gridDim.y) {
+        const ScanItem it = items[item];
+        if (!it.valid) continue;
+        int64_t word = 0;
+        if (tb < nb && f0 + tf < F) {
+            const int64_t at = (int64_t)tb * F + f0 + tf;
+            if (it.sub_parent >= 0) {
+                word = hist_base[it.sub_parent * W + at] - hist_base[it.sub_child * W + at];
+                hist_base[it.slot * W + at] = word;
+            } else {
+                word = hist_base[it.slot * W + at];
+            }
+        }
+        __syncthreads();  // the previous item's tile has been read
+        tile[tb * 17 + tf] = word;
+        __syncthreads();
+        const int f = f0 + wave;
+        if (f >= F) continue;  // no barrier below depends on this wavefront
+        int64_t pre = tile[lane * 17 + wave];
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t v = __shfl_up(pre, o);
+            if (lane >= o) pre += v;
+        }
+        const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
+        double gain = 0.0;
+        int bin = -1;
+        if (lane + 1 < nb && Hs > 0) {
+            const int64_t GL = packed_g(pre), HL = packed_h(pre);
+            const int64_t GR = Gs - GL, HR = Hs - HL;
+            if (HL > 0 && HR > 0) {
+                const int64_t cl = count_estimate(HL, Hs, n), cr = n - cl;
+                if (cl >= min_data && cr >= min_data && !((double)HL * dh < min_sum_hess) &&
+                    !((double)HR * dh < min_sum_hess)) {
+                    const double parent = half_loss(Gs, Hs, dg, dh);
+                    const double gn = half_loss(GL, HL, dg, dh) + half_loss(GR, HR, dg, dh) - parent;
+                    if (gn > 0.0) { gain = gn; bin = lane; }
+                }
+            }
+        }
+        int64_t left = pre;
+        for (int o = 32; o > 0; o >>= 1) {  // arg-max: largest gain, ties to the lowest bin
+            const double og = __shfl_xor(gain, o);
+            const int ob = __shfl_xor(bin, o);
+            const int64_t ol = __shfl_xor(left, o);
+            if (ob >= 0 && (bin < 0 || og > gain || (og == gain && ob < bin))) { gain = og; bin = ob; left = ol; }
+        }
+        if (lane == 0) {
+            FeatCand c;
+            c.gain = gain; c.left = left; c.bin = bin; c.pad = 0;
+            cand_base[(int64_t)item * F + f] = c;
+        }
+    }
+}
+
 // Per-feature candidates -> best split of every scanned histogram, one wavefront per histogram.
 __global__ __launch_bounds__(256) void reduce_items_kernel(const FeatCand* __restrict__ cand_base,
                                                            const ScanItem* __restrict__ items,
                                                            const int32_t* __restrict__ n_items_ptr, int F) {
     const int n_items = *n_items_ptr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (F > 256) {
+        // many features: the four wavefronts share an item (a quarter of the features each, ascending)
+        __shared__ FeatCand part[4];
+        __shared__ int pf[4];
+        for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+            const ScanItem it = items[item];
+            if (!it.valid) continue;  // uniform over the workgroup
+            const FeatCand* cand = cand_base + (int64_t)item * F;
+            const int q = (F + 3) / 4, fb = wave * q, fe = min(F, fb + q);
+            double bg = 0.0;
+            int bf = -1;
+            for (int f = fb + lane; f < fe; f += 64) {
+                const FeatCand c = cand[f];
+                if (c.bin >= 0 && (c.gain > bg)) { bg = c.gain; bf = f; }
+            }
+            for (int o = 32; o > 0; o >>= 1) {
+                const double og = __shfl_xor(bg, o);
+                const int of = __shfl_xor(bf, o);
+                if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) { bg = og; bf = of; }
+            }
+            __syncthreads();
+            if (lane == 0) {
+                pf[wave] = bf;
+                if (bf >= 0) part[wave] = cand[bf];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                int best = -1;
+                for (int k = 0; k < 4; ++k)  // ascending feature ranges: strict > keeps the lowest feature
+                    if (pf[k] >= 0 && (best < 0 || part[k].gain > part[best].gain)) best = k;
+                qgbdt_split sp;
+                sp.gain = 0.0; sp.feature = -1; sp.bin = -1;
+                sp.left_g = sp.left_h = sp.right_g = sp.right_h = sp.left_count = 0;
+                if (best >= 0) {
+                    const FeatCand c = part[best];
+                    sp.gain = c.gain; sp.feature = pf[best]; sp.bin = c.bin;
+                    sp.left_g = packed_g(c.left); sp.left_h = packed_h(c.left);
+                    sp.right_g = it.stat.sum_g - sp.left_g; sp.right_h = it.stat.sum_h - sp.left_h;
+                    sp.left_count = count_estimate(sp.left_h, it.stat.sum_h, it.stat.n_rows);
+                }
+                *it.out = sp;
+            }
+        }
+        return;
+    }
     for (int item = blockIdx.x * 4 + wave; item < n_items; item += gridDim.x * 4) {
         const ScanItem it = items[item];
         if (!it.valid) continue;
@@ -130,13 +251,29 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int threads = 64;
     while (threads < nb) threads <<= 1;
-    int gy = 4096 / F;
+    // a workgroup walks the items gy apart one after the other, each a chain of dependent loads:
+    // enough workgroups that few items queue behind each other (about 32 K wavefronts at most)
+    int gy = 32768 / (F * (threads / 64));
     if (gy < 2) gy = 2;
     if (gy > max_items) gy = max_items;
     if (gy < 1) gy = 1;
-    hipLaunchKernelGGL(scan_kernel, dim3(F, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb, delta,
-                       (int64_t)min_data, min_sum_hess, ctx->cand);
-    int gr = (max_items + 3) / 4;
+    int glog = 0;  // features per XCD group: 16 (one 128-byte line) when F >= 128, fewer for narrow matrices
+    while (glog < 4 && (16 << glog) <= F) ++glog;
+    if (nb <= 64 && F >= 64) {
+        const int gx = (F + 15) / 16;
+        gy = 2048 / gx;
+        if (gy < 2) gy = 2;
+        if (gy > max_items) gy = max_items;
+        if (gy < 1) gy = 1;
+        hipLaunchKernelGGL(scan_tile_kernel, dim3(gx, gy), dim3(1024), 0, ctx->stream, hist_base, items, n_items, F, nb,
+                           delta, (int64_t)min_data, min_sum_hess, ctx->cand);
+    } else {
+        const int per = 8 << glog;
+        const int gx = (F + per - 1) / per * per;
+        hipLaunchKernelGGL(scan_kernel, dim3(gx, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb,
+                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, glog);
+    }
+    int gr = F > 256 ? max_items : (max_items + 3) / 4;
     if (gr > 64) gr = 64;
     hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, ctx->cand, items, n_items, F);
     QG_HIP(ctx, hipGetLastError());

@@ -157,7 +157,7 @@ def test_subtract_bit_exact():
 # split search
 # ----------------------------------------------------------------------------
 
-@pytest.mark.parametrize("F,nb", [(28, 255), (28, 63), (200, 255), (2000, 63), (5, 16), (3, 256)])
+@pytest.mark.parametrize("F,nb", [(28, 255), (28, 63), (200, 255), (2000, 63), (5, 16), (3, 256), (70, 33), (300, 64)])
 def test_find_best_splits_matches_oracle(F, nb):
     from paper_2207_09682_amd import unpack_splits
     rng = np.random.default_rng(F * nb)
