@@ -377,6 +377,28 @@ def test_grow_tree_degenerate_cases():
         _compare_tree(t, e, N)
 
 
+@pytest.mark.parametrize("N,F,nb,L", [(1, 1, 2, 4), (2, 1, 2, 4), (64, 3, 4, 8), (1000, 5, 16, 15), (3000, 30, 63, 31),
+                                      (5000, 65, 32, 31), (4000, 17, 255, 63), (2500, 130, 8, 15)])
+def test_grow_tree_small_and_ragged_shapes(N, F, nb, L):
+    # every kernel variant of the tree path at small sizes: rows narrower than a dword, ragged rows,
+    # tiles cut so that none is narrower than a dword, a single row, leaves of one row
+    rng = np.random.default_rng(N * 131 + F)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint8)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-(bins[:, 0].astype(np.float64) - nb / 2) * 4.0 / nb))).astype(np.float32)
+    score = np.zeros(N, np.float32)
+    ctx = _ctx(N, F, nb, L=L)
+    dbins = torch.from_numpy(bins).cuda()
+    for it in range(2):
+        p = 1.0 / (1.0 + np.exp(-score.astype(np.float64)))
+        g = (p - y).astype(np.float32); h = (p * (1 - p)).astype(np.float32)
+        t = ctx.grow_tree(dbins, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), 4, 4, 99, it, L, min_data_in_leaf=1)
+        e = oracle.grow_tree(bins, nb, g, h, 4, 4, 99, it, L, min_data=1)
+        _compare_tree(t, e, N)
+        for l in range(e.n_leaves):
+            rows = e.row_idx[e.leaf_begin[l]: e.leaf_begin[l] + e.leaf_count[l]]
+            score[rows] += np.float32(0.3 * e.leaf_value[l])
+
+
 def test_errors_are_reported_not_crashes():
     from paper_2207_09682_amd import QgbdtError
     ctx = _ctx(1000, 8, 32, L=8)
