@@ -61,27 +61,46 @@ __global__ __launch_bounds__(256) void update_scores_kernel(float* __restrict__ 
 // atomics and have a fixed order.  For a pair (a, b) with rel_a > rel_b:
 //   rho = 1 / (1 + exp(s_a - s_b)),  w = |gain_a - gain_b| |disc_a - disc_b| / maxDCG,
 //   g_a -= rho w, g_b += rho w, h_a += rho (1 - rho) w, h_b += rho (1 - rho) w;  fp64, rounded once.
+// The path is bound by fp64 arithmetic (group^2 pair terms per query), so the per-pair work is
+// kept small: exp(s_a - s_b) = exp(s_a - c) exp(c - s_b) with c the middle of the query's score
+// range (two exp per document instead of one per pair; queries whose range would overflow that
+// take the direct form), the reciprocal by the hardware estimate and two Newton steps, the
+// division by maxDCG once per document, and pairs of equal relevance drop out through w = 0.
+__device__ __forceinline__ double recip_newton(double d) {
+    double y = __builtin_amdgcn_rcp(d);
+    y = fma(fma(-d, y, 1.0), y, y);
+    y = fma(fma(-d, y, 1.0), y, y);
+    return y;
+}
+
 __global__ __launch_bounds__(128) void lambdarank_grad_kernel(const float* __restrict__ score,
                                                               const float* __restrict__ label, int64_t n, int group,
                                                               float* __restrict__ g, float* __restrict__ h) {
-    extern __shared__ double lr_lds[];
-    double* s = lr_lds;
-    double* r = s + group;
-    double* gain = r + group;
-    double* disc = gain + group;
-    __shared__ double wsum[2];
+    extern __shared__ __align__(16) double lr_lds[];
+    double* s = lr_lds;                                        // [group] scores
+    double* r = s + group;                                     // [group] relevance grades
+    double2* ee = reinterpret_cast<double2*>(r + group);       // [group] exp(s - c), exp(c - s)
+    double2* gd = ee + group;                                  // [group] gain, discount
+    __shared__ double wsum[2], wmax[2], wmin[2];
     const int tid = threadIdx.x;
     const int64_t n_queries = (n + group - 1) / group;
     for (int64_t q = blockIdx.x; q < n_queries; q += gridDim.x) {
         const int64_t q0 = q * group;
         const int m = (int)min((int64_t)group, n - q0);
         __syncthreads();  // the previous query's values are no longer read
+        double smax = -1.0e308, smin = 1.0e308;
         for (int k = tid; k < m; k += blockDim.x) {
-            s[k] = (double)score[q0 + k];
+            const double sk = (double)score[q0 + k];
+            s[k] = sk;
             r[k] = (double)label[q0 + k];
-            gain[k] = exp2(r[k]) - 1.0;
+            smax = fmax(smax, sk); smin = fmin(smin, sk);
         }
+        for (int o = 32; o > 0; o >>= 1) { smax = fmax(smax, __shfl_xor(smax, o)); smin = fmin(smin, __shfl_xor(smin, o)); }
+        if ((tid & 63) == 0) { wmax[tid >> 6] = smax; wmin[tid >> 6] = smin; }
         __syncthreads();
+        smax = fmax(wmax[0], wmax[1]); smin = fmin(wmin[0], wmin[1]);
+        const double c = 0.5 * (smax + smin);
+        const bool direct = !((smax - smin) < 690.0);  // the product of two factors reaches exp(range): must stay finite (also catches NaN scores)
         double part = 0.0;
         for (int k = tid; k < m; k += blockDim.x) {
             int rank = 0, irank = 0;
@@ -90,8 +109,10 @@ __global__ __launch_bounds__(128) void lambdarank_grad_kernel(const float* __res
                 rank += (s[j] > sk || (s[j] == sk && j < k)) ? 1 : 0;
                 irank += (r[j] > rk || (r[j] == rk && j < k)) ? 1 : 0;
             }
-            disc[k] = 1.0 / log2((double)rank + 2.0);
-            part += gain[k] / log2((double)irank + 2.0);
+            const double gk = exp2(rk) - 1.0;
+            gd[k] = make_double2(gk, 1.0 / log2((double)rank + 2.0));
+            if (!direct) ee[k] = make_double2(exp(sk - c), exp(c - sk));
+            part += gk / log2((double)irank + 2.0);
         }
         for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
         if ((tid & 63) == 0) wsum[tid >> 6] = part;
@@ -100,21 +121,32 @@ __global__ __launch_bounds__(128) void lambdarank_grad_kernel(const float* __res
         for (int k = tid; k < m; k += blockDim.x) {
             double G = 0.0, H = 0.0;
             if (max_dcg > 0.0) {
-                const double sk = s[k], rk = r[k], gk = gain[k], dk = disc[k];
-                for (int j = 0; j < m; ++j) {
-                    const double rj = r[j];
-                    if (rj == rk) continue;
-                    const double w = fabs(gk - gain[j]) * fabs(dk - disc[j]) / max_dcg;
-                    if (rk > rj) {  // k is the more relevant one of the pair
-                        const double rho = 1.0 / (1.0 + exp(sk - s[j]));
-                        G -= rho * w;
-                        H += rho * (1.0 - rho) * w;
-                    } else {
-                        const double rho = 1.0 / (1.0 + exp(s[j] - sk));
-                        G += rho * w;
+                const double2 gdk = gd[k];
+                if (!direct) {
+                    const double2 ek = ee[k];
+                    for (int j = 0; j < m; ++j) {
+                        const double2 gdj = gd[j], ej = ee[j];
+                        const bool up = gdk.x > gdj.x;  // k is the more relevant one of the pair
+                        const double w = fabs(gdk.x - gdj.x) * fabs(gdk.y - gdj.y);  // 0 for equal relevance
+                        const double x = up ? ek.x * ej.y : ej.x * ek.y;          // exp(s_hi - s_lo)
+                        const double rho = recip_newton(1.0 + x);
+                        const double rw = rho * w;
+                        G += up ? -rw : rw;
+                        H = fma(1.0 - rho, rw, H);
+                    }
+                } else {
+                    const double sk = s[k];
+                    for (int j = 0; j < m; ++j) {
+                        const double2 gdj = gd[j];
+                        if (gdj.x == gdk.x) continue;
+                        const bool up = gdk.x > gdj.x;
+                        const double w = fabs(gdk.x - gdj.x) * fabs(gdk.y - gdj.y);
+                        const double rho = 1.0 / (1.0 + exp(up ? sk - s[j] : s[j] - sk));
+                        G += up ? -rho * w : rho * w;
                         H += rho * (1.0 - rho) * w;
                     }
                 }
+                G /= max_dcg; H /= max_dcg;
             }
             g[q0 + k] = (float)G;
             h[q0 + k] = (float)H;
@@ -127,7 +159,7 @@ int launch_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float*
     if (n <= 0) return QGBDT_OK;
     const int64_t n_queries = (n + group - 1) / group;
     const int blocks = (int)(n_queries < 65536 ? n_queries : 65536);
-    hipLaunchKernelGGL(lambdarank_grad_kernel, dim3(blocks), dim3(128), sizeof(double) * 4 * (size_t)group, ctx->stream,
+    hipLaunchKernelGGL(lambdarank_grad_kernel, dim3(blocks), dim3(128), sizeof(double) * 6 * (size_t)group, ctx->stream,
                        score, label, n, group, g, h);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;

@@ -493,6 +493,24 @@ def test_lambdarank_gradients_match_oracle(n, gs):
     assert np.allclose(h.cpu().numpy(), eh, rtol=1e-6, atol=1e-7 * scale)
 
 
+def test_lambdarank_gradients_extreme_score_ranges():
+    # a query whose score range is far beyond what exp() of half the range can hold takes the direct form;
+    # one near the switch takes the factored form with large factors
+    rng = np.random.default_rng(8)
+    n, gs = 400, 100
+    s = rng.normal(size=n).astype(np.float32); rel = rng.integers(0, 5, n).astype(np.float32)
+    s[:100] *= 2000.0                                   # range of several thousand
+    s[100:200] *= 100.0                                 # range of ~550: still the factored form, products up to e^550
+    s[200:300] = 3.0                                    # all scores equal
+    ctx = _ctx(n, 4, 16)
+    g, h = ctx.lambdarank_gradients(torch.from_numpy(s).cuda(), torch.from_numpy(rel).cuda(), gs)
+    eg, eh = oracle.lambdarank_gradients(s, rel, gs)
+    assert np.all(np.isfinite(g.cpu().numpy())) and np.all(np.isfinite(h.cpu().numpy()))
+    scale = max(float(np.abs(eg).max()), 1e-30)
+    assert np.allclose(g.cpu().numpy(), eg, rtol=1e-6, atol=1e-7 * scale)
+    assert np.allclose(h.cpu().numpy(), eh, rtol=1e-6, atol=1e-7 * scale)
+
+
 def test_boost_iterations_lambdarank_lock_step():
     cfg = workloads.CONFIGS[4]
     N, F, L, lr = 60_000, 40, 63, 0.1
