@@ -202,3 +202,30 @@ def test_constant_hessians_not_quantized():
     # all-zero hessians: nothing to split on
     t0 = oracle.grow_tree(bins, nb, g, np.zeros(N, np.float32), 4, 0, 9, 1, L)
     assert t0.n_leaves == 1
+
+
+def test_uint16_bins_on_grid_tree_with_thresholds_beyond_8_bits():
+    # 16-bit bins: the on-grid special case again, with 700 bins per feature, so that bin ids and thresholds
+    # above 255 are in play (a reader that took one byte per bin would fail), and the partition against its
+    # plain definition
+    rng = np.random.default_rng(21)
+    N, F, nb = 600, 2, 700
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint16)
+    kq = np.clip(np.round(6.0 * (bins[:, 0].astype(np.float64) / nb - 0.5) + rng.normal(scale=1.5, size=N)), -7, 7)
+    kq[0] = 7
+    g = (kq * 0.125).astype(np.float32)
+    h = np.full(N, 0.875, np.float32)
+    t = oracle.grow_tree(bins, nb, g, h, 4, 4, 3, 0, 6, min_data=5)
+    splits, leaves, values = _exact_gbdt_tree(bins, nb, g, h, 6, 5)
+    assert t.n_leaves == len(leaves)
+    assert [(int(a), int(b), int(c)) for a, b, c in zip(t.split_leaf, t.split_feature, t.split_bin)] == \
+           [(s, f, th) for s, f, th, _, _ in splits]
+    assert max(int(b) for b in t.split_bin) > 255
+    for l, rows in enumerate(leaves):
+        assert np.array_equal(t.row_idx[t.leaf_begin[l]: t.leaf_begin[l] + t.leaf_count[l]], rows)
+    idx = np.sort(rng.choice(N, 400, replace=False)).astype(np.int32)
+    out, nl = oracle.partition_rows(bins, idx, 10, 300, 1, 300)
+    part = idx[10:310]
+    exp = np.concatenate([part[bins[part, 1] <= 300], part[bins[part, 1] > 300]])
+    assert nl == int((bins[part, 1] <= 300).sum())
+    assert np.array_equal(out[10:310], exp) and np.array_equal(out[:10], idx[:10]) and np.array_equal(out[310:], idx[310:])
