@@ -69,7 +69,9 @@ typedef struct {
     int32_t rounding;         /* QGBDT_ROUND_* */
     int32_t num_leaves;       /* leaf budget of leaf-wise growth */
     int32_t min_data_in_leaf; /* minimum (hessian-share estimated) rows per child */
-    int32_t acc_width;        /* local accumulator fields: 0 auto, 16 or 32 bits (Sec. 6.1, 7.4.3) */
+    int32_t acc_width;        /* local accumulators: 0 auto; 16: 32-bit words (16|16 fields, or for unequal bit widths
+                                 the split that takes the most rows, e.g. 13|19 for 3-bit g / 8-bit h);
+                                 32: 64-bit words with 32|32 fields (Sec. 6.1, 7.4.3) */
     uint64_t seed;            /* key of the counter-based RNG */
     double min_sum_hessian;   /* minimum H~ * delta_h per child */
 } qgbdt_params;
@@ -145,8 +147,8 @@ QGBDT_API int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const flo
  * packed low-width bins and merged into the total histogram (Sec. 6.1, 6.2).
  * Rows are row_idx[begin .. begin+count) (dev int32) or, when row_idx is NULL,
  * begin .. begin+count.  bits_g/bits_h bound |g~|, h~ and set how many rows a local
- * 16|16 accumulator may take before it is merged (Sec. 7.4.3); acc_width 0 picks the
- * width, 16 / 32 force it.  hist_out: dev int64[n_bins][n_features], overwritten.
+ * 32-bit accumulator word may take before it is merged (Sec. 7.4.3); acc_width 0 picks the
+ * width, 16 (32-bit words) / 32 (64-bit words) force it.  hist_out: dev int64[n_bins][n_features], overwritten.
  * QGBDT_E_OVERFLOW_RISK if count rows could overflow a 32-bit field. */
 QGBDT_API int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh,
                            const int32_t* row_idx, int64_t begin, int64_t count, int32_t bits_g,

@@ -89,7 +89,8 @@ struct HistPlan {
     int32_t chunk_rows;  // rows accumulated between two merges of the local bins
     int32_t max_groups;  // workgroups along the row axis
     int32_t min_rows_per_group;
-    int32_t acc_width;   // 16: packed 16|16 words in LDS, 32: packed 32|32 words
+    int32_t acc_width;   // 16: packed 32-bit words in LDS (g~ sums above hshift, h~ sums below), 32: packed 32|32 words
+    int32_t hshift;      // bits of the hessian field of a 32-bit local word: 16, or the split that takes more rows
     int32_t flat_lanes;  // > 0: contiguous slices may use the flat 16-byte-load kernel with this many lanes
     int32_t flat_rows;   // rows per wavefront iteration of that kernel
     int32_t flat_unroll;

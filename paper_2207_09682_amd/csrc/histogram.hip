@@ -56,29 +56,33 @@ int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words) {
 }
 
 // Expands the per-row int16 (g~ high byte, h~ low byte) into the packed word that
-// is added to a bin: g~ * 2^W + h~.
+// is added to a bin: g~ * 2^s + h~, where s is the width of the hessian field: 32 for 64-bit
+// words; for 32-bit words 16, or -- when the two bit widths differ -- the split of the 32 bits
+// that lets a word take the most rows (Sec. 7.4.3: the field widths follow from the bit widths
+// and the number of rows; e.g. 13|19 for 3-bit gradients and 8-bit hessians).
 template <int W>
 struct Acc;
 template <>
 struct Acc<16> {
     using word = uint32_t;
-    // (g~ << 16) + h~ = t*255 + ghv with t = ghv minus its low byte (one AND, one multiply-add)
-    static __device__ __forceinline__ word expand(int ghv) { return (word)(__mul24(ghv & ~0xff, 255) + ghv); }
+    // (g~ << s) + h~ = t * (2^(s-8) - 1) + ghv with t = ghv minus its low byte (one AND, one multiply-add);
+    // `mul` = 2^(s-8) - 1
+    static __device__ __forceinline__ word expand(int ghv, int mul) { return (word)(__mul24(ghv & ~0xff, mul) + ghv); }
     static __device__ __forceinline__ void add(word* p, word v) { atomicAdd(p, v); }
-    static __device__ __forceinline__ int64_t widen(word v) {
-        const int64_t G = (int32_t)v >> 16;
-        const int64_t H = v & 0xffffu;
+    static __device__ __forceinline__ int64_t widen(word v, int s) {
+        const int64_t G = (int32_t)v >> s;
+        const int64_t H = v & ((1u << s) - 1u);
         return G * 4294967296LL + H;
     }
 };
 template <>
 struct Acc<32> {
     using word = unsigned long long;
-    static __device__ __forceinline__ word expand(int ghv) {
+    static __device__ __forceinline__ word expand(int ghv, int) {
         return (word)((int64_t)(ghv >> 8) * 4294967296LL + (int64_t)(ghv & 0xff));
     }
     static __device__ __forceinline__ void add(word* p, word v) { atomicAdd(p, v); }
-    static __device__ __forceinline__ int64_t widen(word v) { return (int64_t)v; }
+    static __device__ __forceinline__ int64_t widen(word v, int) { return (int64_t)v; }
 };
 
 // Work item -> (table entry, row group).
@@ -124,7 +128,7 @@ __device__ __forceinline__ int unpad16(int col) {
 
 template <int W>
 __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_words, int ftp, int ft, int f0, int F,
-                                            int64_t* hist, bool pad16 = false) {
+                                            int64_t* hist, int hshift, bool pad16 = false) {
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
         const int b = w / ftp;
         int f = w - b * ftp;
@@ -133,7 +137,7 @@ __device__ __forceinline__ void merge_local(typename Acc<W>::word* lds, int lds_
         if (v != 0 && f < ft) {
             lds[w] = 0;
             atomicAdd(reinterpret_cast<unsigned long long*>(hist + (int64_t)b * F + f0 + f),
-                      (unsigned long long)Acc<W>::widen(v));
+                      (unsigned long long)Acc<W>::widen(v, hshift));
         }
     }
 }
@@ -194,6 +198,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
     word* lds = reinterpret_cast<word*>(lds_raw);
 
     const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int hmul = (1 << (plan.hshift - 8)) - 1;
     int tile, glane;
     tile_and_lane(plan.n_tiles, tile, glane);
     const int n_lanes = (int)gridDim.x / plan.n_tiles;  // row-group lanes (a multiple of 8)
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
                             const bool ok = ro + u * rpi + r < crow;
-                            const word v = Acc<W>::expand(ok ? gv[u] : 0);
+                            const word v = Acc<W>::expand(ok ? gv[u] : 0, hmul);
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
-            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.pad16 != 0);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.hshift, plan.pad16 != 0);
         }
     }
 }
@@ -332,6 +337,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
     word* lds = reinterpret_cast<word*>(lds_raw);
 
     const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int hmul = (1 << (plan.hshift - 8)) - 1;
     int tile, glane;
     tile_and_lane(plan.n_tiles, tile, glane);
     const int n_lanes = (int)gridDim.x / plan.n_tiles;
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const bool ok = ro + u * rpi + r < crow;
-                        const word v = Acc<W>::expand(ok ? gv[u] : 0);
+                        const word v = Acc<W>::expand(ok ? gv[u] : 0, hmul);
                         uint32_t dw[4];
                         if constexpr (V == 16) {
                             dw[0] = d[u].x; dw[1] = d[u].y; dw[2] = d[u].z; dw[3] = d[u].w;
@@ -449,7 +455,7 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
-            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.pad16 != 0);
+            else merge_local<W>(lds, lds_words, ftp, ft, f0, F, hist, plan.hshift, plan.pad16 != 0);
         }
     }
 }
@@ -471,6 +477,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
     word* lds = reinterpret_cast<word*>(lds_raw);
 
     const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int hmul = (1 << (plan.hshift - 8)) - 1;
     if ((int)blockIdx.x >= n_items) return;
     if (step && blockIdx.x == 0 && threadIdx.x == 0) count_profile(entries, n_entries, false, step);
 
@@ -555,8 +562,8 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
                     if (lane_on) {  // the lanes beyond the last whole row of an iteration sit out
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const word va = Acc<W>::expand(ga[u]);
-                        const word vb = Acc<W>::expand(gbv[u]);
+                        const word va = Acc<W>::expand(ga[u], hmul);
+                        const word vb = Acc<W>::expand(gbv[u], hmul);
                         const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -583,7 +590,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
                 // row index inside the entry: head rows come first, tail rows follow the chunk's blocks
                 const int64_t arow = rs < n_head ? (int64_t)rs : cbegin + tail0 + (rs - n_head);
                 const uint32_t dwd = *reinterpret_cast<const uint32_t*>(bins + (en.begin + arow) * (int64_t)F + 4 * q);
-                const word v = Acc<W>::expand(gh[en.begin + arow]);
+                const word v = Acc<W>::expand(gh[en.begin + arow], hmul);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const uint32_t b = (dwd >> (8 * k)) & 0xffu;
@@ -592,7 +599,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
-            else merge_local<W>(lds, lds_words, ftp, F, 0, F, hist);
+            else merge_local<W>(lds, lds_words, ftp, F, 0, F, hist, plan.hshift);
             first = false;
         }
     }
@@ -612,6 +619,7 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
     const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int hmul = (1 << (plan.hshift - 8)) - 1;
     int tile, glane;
     tile_and_lane(plan.n_tiles, tile, glane);
     const int n_lanes = (int)gridDim.x / plan.n_tiles;
@@ -641,13 +649,13 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
             __syncthreads();
             for (int64_t p = cbegin + wave * rpi + r; p < cend; p += n_waves * rpi) {
                 const int64_t i = idx ? (int64_t)idx[p] : en.begin + p;
-                const word v = Acc<W>::expand(gh[i]);
+                const word v = Acc<W>::expand(gh[i], hmul);
                 const BIN* row = bins + i * F + f0;
                 for (int f = fl; f < ft; f += C) Acc<W>::add(&lds[(uint32_t)row[f] * ft + f], v);
             }
             __syncthreads();
             if (cend >= gend) store_partial<W>(lds, lds_words * (int)sizeof(word), slot);
-            else merge_local<W>(lds, lds_words, ft, ft, f0, F, hist);
+            else merge_local<W>(lds, lds_words, ft, ft, f0, F, hist, plan.hshift);
         }
     }
 }
@@ -664,6 +672,8 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
                                                           int generic) {
     using word = typename Acc<W>::word;
     const int n_entries = table_counts[0], n_items = table_counts[1];
+    const int hs = plan.hshift;
+    const uint32_t hmask = (1u << hs) - 1u;
     const int per = (n_items + (int)gridDim.z - 1) / (int)gridDim.z;
     const int i0 = blockIdx.z * per, i1 = min(n_items, i0 + per);
     if (i0 >= i1) return;
@@ -689,13 +699,13 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
             for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const word*>(base + (size_t)(i + k) * stride);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (W == 16) { sg += (int32_t)v[k] >> 16; sh += (uint32_t)v[k] & 0xffffu; }
+                if (W == 16) { sg += (int32_t)v[k] >> hs; sh += (uint32_t)v[k] & hmask; }
                 else sg += (int64_t)v[k];
             }
         }
         for (; i < iend; ++i) {
             const word v = *reinterpret_cast<const word*>(base + (size_t)i * stride);
-            if (W == 16) { sg += (int32_t)v >> 16; sh += (uint32_t)v & 0xffffu; }
+            if (W == 16) { sg += (int32_t)v >> hs; sh += (uint32_t)v & hmask; }
             else sg += (int64_t)v;
         }
         const int64_t sum = (W == 16) ? sg * 4294967296LL + sh : sg;
@@ -715,11 +725,28 @@ static int64_t rows_fitting(int bits_g, int bits_h, int w) {
 
 int64_t max_rows_for_width(int bits_g, int bits_h, int w) { return rows_fitting(bits_g, bits_h, w); }
 
+// Rows a 32-bit local word takes when its low `s` bits hold the hessian sum (unsigned) and the
+// 32 - s bits above it the gradient sum (signed); the s in 8..24 with the most rows, 16 on a tie.
+static int64_t rows_fitting_word32(int bits_g, int bits_h, int* hshift) {
+    const int64_t kg = (1 << (bits_g - 1)) - 1, kh = bits_h == 0 ? 1 : (1 << bits_h) - 2;
+    int64_t best = -1;
+    int bs = 16;
+    for (int s = 8; s <= 24; ++s) {
+        const int64_t a = (((int64_t)1 << (31 - s)) - 1) / kg;
+        const int64_t b = (((int64_t)1 << s) - 1) / kh;
+        const int64_t r = a < b ? a : b;
+        if (r > best || (r == best && s == 16)) { best = r; bs = s; }
+    }
+    *hshift = bs;
+    return best;
+}
+
 // Chooses tile width, accumulator width and launch shape for a problem shape.
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width) {
     HistPlan p{};
     const int F = s.n_features, nb = s.n_bins;
-    const int64_t n16 = rows_fitting(bits_g, bits_h, 16);
+    int hshift = 16;
+    const int64_t n16 = rows_fitting_word32(bits_g, bits_h, &hshift);  // rows per chunk of 32-bit local words
     int w = acc_width;
     // a 16|16 chunk must amortise its hand-over: measured on 10.5 M x 28, whole trees, 16|16 against 32|32:
     // 4.07 / 4.17 ms at 4 bits (4681 rows per chunk), 4.29 / 4.10 ms at 5 bits (2184 rows)
@@ -801,6 +828,7 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (groups < 1) groups = 1;
     p.max_groups = groups;
     p.acc_width = w;
+    p.hshift = hshift;
     p.ragged = (fast && !aligned) ? 1 : 0;
     p.bytewise = fast ? 0 : 1;
     p.flat_lanes = 0; p.flat_rows = 0;

@@ -124,15 +124,20 @@ def test_histogram_worst_case_first_tree_values():
     N, F, nb = 200000, 28, 255
     rng = np.random.default_rng(1)
     bins = rng.integers(0, 4, (N, F)).astype(np.uint8)                    # few bins: large sums per bin
-    for bg, bh in ((3, 3), (5, 5), (3, 8)):
-        kg, kh = 2 ** (bg - 1) - 1, 2 ** bh - 2
-        gq = np.where(rng.random(N) < 0.9, kg, -kg).astype(np.int8); hq = np.full(N, kh, np.uint8)
-        gh = torch.from_numpy(_pack_gh(gq, hq)).cuda()
+    # equal bit widths (16|16 fields) and unequal ones, where a 32-bit word is split unevenly (13|19 for (3, 8),
+    # 17|15 for un-quantized constant hessians, 19|13 for (8, 2)): the chunk length is exactly what the fields hold
+    for bg, bh in ((3, 3), (5, 5), (3, 8), (3, 0), (4, 0), (2, 5), (8, 2), (6, 3)):
+        kg, kh = 2 ** (bg - 1) - 1, (2 ** bh - 2 if bh else 1)
+        hq = np.full(N, kh, np.uint8)
         ctx = _ctx(N, F, nb)
-        exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq))
-        for acc in (16, 32):
-            got = ctx.build_histograms(torch.from_numpy(bins).cuda(), gh, bits_g=bg, bits_h=bh, acc_width=acc)
-            assert np.array_equal(got.cpu().numpy().reshape(nb, F), exp)
+        bins[:, 0] = 0                                                    # one feature: every row in one bin
+        for gq in (np.where(rng.random(N) < 0.9, kg, -kg).astype(np.int8), np.full(N, kg, np.int8),
+                   np.full(N, -kg, np.int8)):                             # the last two fill a field to its last row
+            gh = torch.from_numpy(_pack_gh(gq, hq)).cuda()
+            exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq))
+            for acc in (16, 32):
+                got = ctx.build_histograms(torch.from_numpy(bins).cuda(), gh, bits_g=bg, bits_h=bh, acc_width=acc)
+                assert np.array_equal(got.cpu().numpy().reshape(nb, F), exp), (bg, bh, acc)
 
 
 def test_subtract_bit_exact():
