@@ -336,6 +336,27 @@ def test_full_size_cfg5():
     torch.cuda.empty_cache()
 
 
+def test_rows_times_features_beyond_2_to_32():
+    # 160 M x 28: byte offsets into the bin matrix exceed 32 bits, the partition has 156 K segments, and with
+    # forced 32-bit local words every row group spans several chunks (merged through atomics).  One
+    # first-iteration tree (g = +-1/2, h = 1/4: the extreme quantized values) per accumulator setting.
+    N, F, nb, L = 160_000_000, 28, 255, 15
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    bins = torch.randint(0, nb, (N, F), dtype=torch.uint8, device="cuda", generator=gen)
+    z = (bins[:, 3].float() - 127.0) / 40.0 + (bins[:, F - 1] > 200).float() - (bins[:, 11] < 30).float()
+    y = (torch.rand(N, generator=gen, device="cuda") < torch.sigmoid(z)).float()
+    del z
+    g = 0.5 - y; h = torch.full((N,), 0.25, device="cuda")
+    bins_np = bins.cpu().numpy(); g_np = g.cpu().numpy(); h_np = h.cpu().numpy()
+    e = oracle.grow_tree(bins_np, nb, g_np, h_np, 3, 3, 11, 0, L, min_data=20)
+    ctx = _ctx(N, F, nb, L=L)
+    for acc in (0, 16):
+        t = ctx.grow_tree(bins, g, h, 3, 3, 11, 0, L, min_data_in_leaf=20, acc_width=acc)
+        _compare_tree(t, e, N)
+    del ctx, bins
+    torch.cuda.empty_cache()
+
+
 def test_constant_hessian_regression_full_size():
     # squared error on a 463,715 x 90 matrix: bits_h = 0 (hessians not quantized), F % 4 == 2 takes the
     # byte-wise histogram kernel; three trees in lock step
