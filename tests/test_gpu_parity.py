@@ -336,19 +336,21 @@ def test_full_size_cfg5():
     torch.cuda.empty_cache()
 
 
-def test_rows_times_features_beyond_2_to_32():
-    # 160 M x 28: byte offsets into the bin matrix exceed 32 bits, the partition has 156 K segments, and with
-    # forced 32-bit local words every row group spans several chunks (merged through atomics).  One
-    # first-iteration tree (g = +-1/2, h = 1/4: the extreme quantized values) per accumulator setting.
-    N, F, nb, L = 160_000_000, 28, 255, 15
+@pytest.mark.parametrize("N,F,nb,L", [(160_000_000, 28, 255, 15), (2_400_000, 2000, 63, 7)])
+def test_rows_times_features_beyond_2_to_32(N, F, nb, L):
+    # Byte offsets into the bin matrix exceed 32 bits.  160 M x 28 (rows kept in leaf order): the partition has
+    # 156 K segments, and with forced 32-bit local words every row group spans several chunks (merged through
+    # atomics).  2.4 M x 2000 (rows gathered through row ids, 16 feature tiles).  One first-iteration tree
+    # (g = +-1/2, h = 1/4: the extreme quantized values) per accumulator setting.
     gen = torch.Generator(device="cuda").manual_seed(5)
     bins = torch.randint(0, nb, (N, F), dtype=torch.uint8, device="cuda", generator=gen)
-    z = (bins[:, 3].float() - 127.0) / 40.0 + (bins[:, F - 1] > 200).float() - (bins[:, 11] < 30).float()
+    z = (bins[:, 3].float() - nb / 2) / (nb / 6) + (bins[:, F - 1] > (3 * nb) // 4).float() - (bins[:, 11] < nb // 8).float()
     y = (torch.rand(N, generator=gen, device="cuda") < torch.sigmoid(z)).float()
     del z
     g = 0.5 - y; h = torch.full((N,), 0.25, device="cuda")
     bins_np = bins.cpu().numpy(); g_np = g.cpu().numpy(); h_np = h.cpu().numpy()
     e = oracle.grow_tree(bins_np, nb, g_np, h_np, 3, 3, 11, 0, L, min_data=20)
+    del bins_np
     ctx = _ctx(N, F, nb, L=L)
     for acc in (0, 16):
         t = ctx.grow_tree(bins, g, h, 3, 3, 11, 0, L, min_data_in_leaf=20, acc_width=acc)
