@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--acc-width", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--root-reps", type=int, default=20)
+    ap.add_argument("--no-bind", action="store_true",
+                    help="do not bind the bin matrix to the context (no feature-major copy for the partitions)")
     ap.add_argument("--root-only", action="store_true",
                     help="only the full-size root-pass histogram build (3 warm-up + --root-reps launches); prints "
                          "the root_pass object alone (used for the per-kernel rocprofv3 summaries)")
@@ -93,6 +95,15 @@ def main():
     ctx = Context(N, F, nb, max_leaves=L)
     K, W = args.steps, args.warmup
     sys.stderr.write(f"[bench] workload {cfg.name}: {N} x {F}, {nb} bins, generated in {time.time() - t0:.1f}s\n")
+
+    # the matrix of all trees of the run: bound once, like binning part of the set-up (no effect for narrow rows)
+    bind_ms = None
+    if not args.no_bind:
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        ctx.bind_bins(bins)
+        torch.cuda.synchronize()
+        bind_ms = (time.perf_counter() - tb) * 1e3
 
     if args.pmc_probe:
         g, h = workloads.gradients(wl, torch.zeros(N, device=dev))
@@ -233,7 +244,8 @@ def main():
         "config": {"workload": f"{cfg.name}: {N} rows x {F} features, {nb} bins (uint8), {cfg.loss} loss, "
                                f"{bits_g}-bit g / {bits_h}-bit h, {L} leaves/tree, leaf-wise",
                    "acc_width": args.acc_width or "auto", "leaves_last_tree": n_leaves_last,
-                   "hist_units_per_tree": total_units / K},
+                   "hist_units_per_tree": total_units / K,
+                   "bins_bound": bind_ms is not None, "bind_ms_once": bind_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "histogram build = hist_*_kernel + hist_reduce_kernel (all launches of the timed trees)",

@@ -25,7 +25,7 @@ EXPORTS = [
     "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_boost_iteration_lambdarank",
-    "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats",
+    "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats", "qgbdt_bind_bins",
 ]
 
 
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
         lib.qgbdt_set_profiling.argtypes = [C.c_void_p, C.c_int32]
         lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         lib.qgbdt_tree_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        lib.qgbdt_bind_bins.argtypes = [C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -153,6 +154,11 @@ class Context:
             rc = self.lib.qgbdt_create(C.byref(self._h), C.byref(self.shape), C.c_void_p(stream))
         if rc != 0:
             raise QgbdtError(rc, self.lib.qgbdt_last_error(None).decode())
+
+    def bind_bins(self, bins: torch.Tensor | None) -> None:
+        """qgbdt_bind_bins: keep a feature-major copy of `bins` for the partitions of the trees that follow
+        (None frees it).  The tensor must stay alive and unchanged while it is bound."""
+        self._chk(self.lib.qgbdt_bind_bins(self._h, C.c_void_p(self._bins(bins)) if bins is not None else None))
 
     # -- helpers ---------------------------------------------------------------
     def _bins(self, bins: torch.Tensor) -> int:

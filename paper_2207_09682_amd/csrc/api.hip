@@ -51,7 +51,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->idx[2], c->bins_t, c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->sorted_idx, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -245,6 +245,30 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     return launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
                        ctx->hist_entries, ctx->hist_counts, hist_out,
                        (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
+}
+
+int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    ctx->bound_bins = nullptr;
+    if (!bins) {
+        if (ctx->bins_t) {
+            QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            const size_t bytes = (size_t)ctx->shape.n_rows * ctx->shape.n_features * ctx->shape.bin_bytes;
+            (void)hipFree(ctx->bins_t);
+            ctx->bins_t = nullptr;
+            ctx->ws_bytes -= bytes;
+        }
+        return QGBDT_OK;
+    }
+    if (ctx->ordered) return QGBDT_OK;  // narrow rows are kept in leaf order: the copy would not be read
+    if (!ctx->bins_t) {
+        int rc = ws_alloc(ctx, &ctx->bins_t, (size_t)ctx->shape.n_rows * ctx->shape.n_features * ctx->shape.bin_bytes);
+        if (rc != QGBDT_OK) { ctx->bins_t = nullptr; return rc; }
+    }
+    int rc = launch_transpose_bins(ctx, bins, ctx->bins_t);
+    if (rc != QGBDT_OK) return rc;
+    ctx->bound_bins = bins;
+    return QGBDT_OK;
 }
 
 int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* sibling_out) {

@@ -157,6 +157,8 @@ struct qgbdt_ctx {
     uint8_t* obins[3];     // [N][F] each (ordered mode)
     int16_t* ogh[3];       // [N] each (ordered mode)
     int32_t* idx[3];       // [N] each
+    uint8_t* bins_t;       // [F][N] feature-major copy of the bound bin matrix (qgbdt_bind_bins), else null
+    const void* bound_bins; // the matrix that copy was made from
     int16_t* gh;           // [N]
     float2* ghf;           // [N] (g, h) interleaved, written by the quantizer for the refit's gather
     float* gbuf;           // [N] loss derivatives of a boosting iteration run by the library (allocated on first use)
@@ -229,7 +231,8 @@ int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, in
                           int64_t* n_left_out, int64_t max_count);
 int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,
                        int feature, int bin, int64_t* n_left_out);
-int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows);
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t);
+int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,

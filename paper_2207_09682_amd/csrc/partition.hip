@@ -182,7 +182,8 @@ __device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, 
 // that this round's builds accumulate into are cleared.  In ordered mode the rows of a
 // node are physically contiguous in its buffer and the bin is read at the row's position;
 // otherwise it is gathered from the original matrix through the row id.
-__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, int ordered, int bb, int F, IdxSet idxs,
+__global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, const uint8_t* __restrict__ bins_t, int64_t n_rows, int ordered,
+                                                               int bb, int F, IdxSet idxs,
                                                                const StepState* __restrict__ step,
                                                                const BatchEntry* __restrict__ batch,
                                                                const Node* __restrict__ nodes,
@@ -204,13 +205,16 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, i
         const Node nd = nodes[be.node];
         const int32_t* src = idxs.p[nd.buf] + nd.begin;
         const uint8_t* brow = rows.bins[ordered ? nd.buf : BUF_ORIGINAL] + (ordered ? nd.begin * (int64_t)F : 0);
+        // with a feature-major copy of the matrix the split feature's column is read instead: the ascending row
+        // ids of a node then fall into few sectors, where the row-major matrix costs one sector per row
+        const uint8_t* col = (bins_t && !ordered) ? bins_t + (int64_t)nd.best.feature * n_rows * bb : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int feature = nd.best.feature, bin = nd.best.bin;
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
             const int64_t row = ordered ? p : (int64_t)src[p];
-            const int fl = bin_at(brow, row * F + feature, bb) <= bin;
+            const int fl = (col ? bin_at(col, row, bb) : bin_at(brow, row * F + feature, bb)) <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;
         }
@@ -330,10 +334,10 @@ static IdxSet idx_set(const qgbdt_ctx* ctx) {
     return s;
 }
 
-int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows) {
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t) {
     const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
-    hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                       ctx->ordered, ctx->shape.bin_bytes, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch,
+    hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows, bins_t,
+                       ctx->shape.n_rows, ctx->ordered, ctx->shape.bin_bytes, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch,
                        ctx->nodes, ctx->flags, ctx->seg_counts, ctx->hist_pool, W);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
@@ -350,6 +354,41 @@ int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows) {
         hipLaunchKernelGGL(batch_part_scatter_kernel<false>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
                            out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
                            ctx->seg_prefix);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+// Feature-major copy of a row-major bin matrix: out[f][row] = in[row][f], 32 x 32 tiles through LDS
+// so that both sides are accessed along their contiguous direction.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_bins_kernel(const T* __restrict__ in, T* __restrict__ out, int64_t N, int F) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int64_t tiles_r = (N + 31) / 32;
+    const int tiles_f = (F + 31) / 32;
+    for (int64_t t = blockIdx.x; t < tiles_r * tiles_f; t += gridDim.x) {
+        const int64_t r0 = (t / tiles_f) * 32;
+        const int f0 = (int)(t % tiles_f) * 32;
+        __syncthreads();
+        for (int k = ty; k < 32; k += 8)
+            if (r0 + k < N && f0 + tx < F) tile[k][tx] = in[(r0 + k) * F + f0 + tx];
+        __syncthreads();
+        for (int k = ty; k < 32; k += 8)
+            if (f0 + k < F && r0 + tx < N) out[(int64_t)(f0 + k) * N + r0 + tx] = tile[tx][k];
+    }
+}
+
+int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out) {
+    const int64_t N = ctx->shape.n_rows;
+    const int F = ctx->shape.n_features;
+    int64_t tiles = ((N + 31) / 32) * ((F + 31) / 32);
+    const int grid = (int)(tiles < 65536 ? tiles : 65536);
+    if (ctx->shape.bin_bytes == 2)
+        hipLaunchKernelGGL(transpose_bins_kernel<uint16_t>, dim3(grid), dim3(256), 0, ctx->stream,
+                           static_cast<const uint16_t*>(bins), static_cast<uint16_t*>(out), N, F);
+    else
+        hipLaunchKernelGGL(transpose_bins_kernel<uint8_t>, dim3(grid), dim3(256), 0, ctx->stream,
+                           static_cast<const uint8_t*>(bins), static_cast<uint8_t*>(out), N, F);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

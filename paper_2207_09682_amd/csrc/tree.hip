@@ -541,6 +541,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     }
     rows.bins[BUF_ORIGINAL] = bins; rows.gh[BUF_ORIGINAL] = ctx->gh; idxs.p[BUF_ORIGINAL] = ctx->idx[0];
     const int root_buf = ordered ? BUF_ORIGINAL : 0;
+    // the feature-major copy serves only the matrix it was made from
+    const uint8_t* bins_t = (ctx->bins_t && ctx->bound_bins == (const void*)bins) ? ctx->bins_t : nullptr;
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;
@@ -572,7 +574,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                                ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                                ctx->max_expand, p_max, out);
-            rc = launch_batch_partition_count(ctx, rows);
+            rc = launch_batch_partition_count(ctx, rows, bins_t);
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                                ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
@@ -597,7 +599,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         if (ctx->host_state->done) break;
         if (launched > round_cap) return set_error(ctx, QGBDT_E_HIP, "tree growth did not finish in %d rounds", launched);
         // the trailing plan has already chosen a batch: finish that round, then continue
-        rc = launch_batch_partition_count(ctx, rows);
+        rc = launch_batch_partition_count(ctx, rows, bins_t);
         if (rc != QGBDT_OK) return rc;
         hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                            ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,

@@ -676,3 +676,34 @@ def test_uint16_context_rejects_wrong_bin_type_and_too_many_bins():
     with pytest.raises(TypeError):
         ctx.build_histograms(torch.zeros((100, 4), dtype=torch.uint8, device="cuda"),
                              torch.zeros(100, dtype=torch.int16, device="cuda"), bits_g=3, bits_h=3)
+
+
+# ----------------------------------------------------------------------------
+# bound bin matrix: feature-major copy for the partition of wide or ragged matrices
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,F,nb,L,bb", [(30000, 200, 255, 31, 1), (20000, 2000, 63, 15, 1), (9000, 33, 40, 15, 1),
+                                         (12000, 12, 800, 15, 2), (50000, 28, 255, 31, 1)])
+def test_grow_tree_with_bound_bins(N, F, nb, L, bb):
+    from paper_2207_09682_amd import Context
+    rng = np.random.default_rng(N + F)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint16 if bb == 2 else np.uint8)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-(bins[:, 1].astype(np.float64) - nb / 2) * 6.0 / nb))).astype(np.float32)
+    g = (0.5 - y).astype(np.float32); h = np.full(N, 0.25, np.float32)
+    e = oracle.grow_tree(bins, nb, g, h, 3, 3, 4, 0, L, min_data=5)
+    ctx = Context(N, F, nb, max_leaves=L, bin_bytes=bb)
+    dbins = torch.from_numpy(bins).cuda()
+    dg, dh = torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda()
+    ws0 = ctx.workspace_bytes
+    ctx.bind_bins(dbins)
+    _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e, N)
+    other = dbins.clone()                                     # another matrix object: the copy is not used
+    _compare_tree(ctx.grow_tree(other, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e, N)
+    bins2 = bins.copy(); bins2[:, 1] = bins[::-1, 1]          # new contents, bound again
+    e2 = oracle.grow_tree(bins2, nb, g, h, 3, 3, 4, 0, L, min_data=5)
+    dbins.copy_(torch.from_numpy(bins2))
+    ctx.bind_bins(dbins)
+    _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
+    ctx.bind_bins(None)
+    assert ctx.workspace_bytes == ws0
+    _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
