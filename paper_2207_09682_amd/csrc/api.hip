@@ -260,7 +260,6 @@ int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
         }
         return QGBDT_OK;
     }
-    if (ctx->ordered) return QGBDT_OK;  // narrow rows are kept in leaf order: the copy would not be read
     if (!ctx->bins_t) {
         int rc = ws_alloc(ctx, &ctx->bins_t, (size_t)ctx->shape.n_rows * ctx->shape.n_features * ctx->shape.bin_bytes);
         if (rc != QGBDT_OK) { ctx->bins_t = nullptr; return rc; }

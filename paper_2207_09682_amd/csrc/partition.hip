@@ -207,13 +207,16 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, c
         const uint8_t* brow = rows.bins[ordered ? nd.buf : BUF_ORIGINAL] + (ordered ? nd.begin * (int64_t)F : 0);
         // with a feature-major copy of the matrix the split feature's column is read instead: the ascending row
         // ids of a node then fall into few sectors, where the row-major matrix costs one sector per row
-        const uint8_t* col = (bins_t && !ordered) ? bins_t + (int64_t)nd.best.feature * n_rows * bb : nullptr;
+        // (rows kept in leaf order: only for nodes with at least 1/16 of all rows -- below that the gather
+        // through the row ids costs more than streaming the node's rows)
+        const uint8_t* col = (bins_t && (!ordered || nd.count * 16 >= n_rows))
+                                 ? bins_t + (int64_t)nd.best.feature * n_rows * bb : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int feature = nd.best.feature, bin = nd.best.bin;
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
-            const int64_t row = ordered ? p : (int64_t)src[p];
+            const int64_t row = (ordered && !col) ? p : (int64_t)src[p];
             const int fl = (col ? bin_at(col, row, bb) : bin_at(brow, row * F + feature, bb)) <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;

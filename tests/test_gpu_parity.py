@@ -265,6 +265,8 @@ def _lockstep(cfg, N, F, n_trees, num_leaves, acc=0, bits=None, device="cpu"):
     dbins = wl.bins.cuda()
     score = torch.zeros(N, device=device)
     ctx = _ctx(N, F, cfg.n_bins, L=num_leaves)
+    if device == "cuda":
+        ctx.bind_bins(dbins)                               # the full-size cases run as bench.py does: matrix bound
     bg, bh = bits or (cfg.bits_g, cfg.bits_h)
     for it in range(n_trees):
         g, h = workloads.gradients(wl, score)
