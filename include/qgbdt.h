@@ -133,10 +133,10 @@ QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
  * as it is for all trees of a boosting run, and makes a feature-major copy of it on the stream
  * (n_rows * n_features * bin_bytes more workspace, allocated at the first call).  The counting pass of
  * the row partition then reads the split feature's column -- the ascending row ids of a node fall into
- * few memory sectors -- instead of the row-major matrix (one sector per row for wide rows; the whole row
- * for narrow rows, where the column is used for nodes of at least 1/16 of all rows).  Results do not
- * change.  Call again after the matrix' contents change; a grow_tree call with another pointer simply
- * does not use the copy; bins = NULL frees it (synchronises the stream first). */
+ * few memory sectors -- instead of one sector of the row-major matrix per row, and narrow matrices, whose
+ * rows are otherwise moved into leaf order level by level, are left in place.  Results do not change.
+ * Call again after the matrix' contents change; a grow_tree call with another pointer simply does not
+ * use the copy; bins = NULL frees it (synchronises the stream first). */
 QGBDT_API int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins);
 
 /* ---- steps of the path ---------------------------------------------------- */

@@ -231,9 +231,9 @@ int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, in
                           int64_t* n_left_out, int64_t max_count);
 int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,
                        int feature, int bin, int64_t* n_left_out);
-int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t);
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t, bool ordered);
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
-int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows);
+int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);

@@ -207,16 +207,13 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, c
         const uint8_t* brow = rows.bins[ordered ? nd.buf : BUF_ORIGINAL] + (ordered ? nd.begin * (int64_t)F : 0);
         // with a feature-major copy of the matrix the split feature's column is read instead: the ascending row
         // ids of a node then fall into few sectors, where the row-major matrix costs one sector per row
-        // (rows kept in leaf order: only for nodes with at least 1/16 of all rows -- below that the gather
-        // through the row ids costs more than streaming the node's rows)
-        const uint8_t* col = (bins_t && (!ordered || nd.count * 16 >= n_rows))
-                                 ? bins_t + (int64_t)nd.best.feature * n_rows * bb : nullptr;
+        const uint8_t* col = (bins_t && !ordered) ? bins_t + (int64_t)nd.best.feature * n_rows * bb : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int feature = nd.best.feature, bin = nd.best.bin;
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
-            const int64_t row = (ordered && !col) ? p : (int64_t)src[p];
+            const int64_t row = ordered ? p : (int64_t)src[p];
             const int fl = (col ? bin_at(col, row, bb) : bin_at(brow, row * F + feature, bb)) <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;
@@ -337,19 +334,19 @@ static IdxSet idx_set(const qgbdt_ctx* ctx) {
     return s;
 }
 
-int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t) {
+int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t, bool ordered) {
     const int64_t W = (int64_t)ctx->shape.n_features * ctx->shape.n_bins;
     hipLaunchKernelGGL(batch_part_count_kernel, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows, bins_t,
-                       ctx->shape.n_rows, ctx->ordered, ctx->shape.bin_bytes, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch,
+                       ctx->shape.n_rows, ordered ? 1 : 0, ctx->shape.bin_bytes, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch,
                        ctx->nodes, ctx->flags, ctx->seg_counts, ctx->hist_pool, W);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
-int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows) {
+int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered) {
     RowDest out;
     for (int b = 0; b < 3; ++b) { out.bins[b] = ctx->obins[b]; out.gh[b] = ctx->ogh[b]; }
-    if (ctx->ordered)
+    if (ordered)
         hipLaunchKernelGGL(batch_part_scatter_kernel<true>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
                            out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
                            ctx->seg_prefix);

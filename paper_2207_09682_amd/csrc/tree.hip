@@ -533,7 +533,13 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // in ordered mode buffers 0/1 are the leaf-ordered copies that the partition writes.
     RowSource rows;
     IdxSet idxs;
-    const bool ordered = ctx->ordered != 0;
+    // the feature-major copy serves only the matrix it was made from
+    const uint8_t* bins_t = (ctx->bins_t && ctx->bound_bins == (const void*)bins) ? ctx->bins_t : nullptr;
+    // Narrow rows are kept in leaf order (every level moves them) when the partition would otherwise gather a
+    // sector of the row-major matrix per row; with the feature-major copy the partition is cheap without
+    // moving rows, and gathering the rows of the smaller children costs less than moving all rows
+    // (10.5 M x 28: 3.58 against 3.97 ms per tree).
+    const bool ordered = ctx->ordered != 0 && !bins_t;
     for (int b = 0; b < 3; ++b) {
         rows.bins[b] = ordered ? ctx->obins[b] : bins;
         rows.gh[b] = ordered ? ctx->ogh[b] : ctx->gh;
@@ -541,8 +547,6 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     }
     rows.bins[BUF_ORIGINAL] = bins; rows.gh[BUF_ORIGINAL] = ctx->gh; idxs.p[BUF_ORIGINAL] = ctx->idx[0];
     const int root_buf = ordered ? BUF_ORIGINAL : 0;
-    // the feature-major copy serves only the matrix it was made from
-    const uint8_t* bins_t = (ctx->bins_t && ctx->bound_bins == (const void*)bins) ? ctx->bins_t : nullptr;
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;
@@ -574,12 +578,12 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                                ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
                                ctx->max_expand, p_max, out);
-            rc = launch_batch_partition_count(ctx, rows, bins_t);
+            rc = launch_batch_partition_count(ctx, rows, bins_t, ordered);
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                                ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                                plan);
-            rc = launch_batch_partition_scatter(ctx, rows);
+            rc = launch_batch_partition_scatter(ctx, rows, ordered);
             if (rc != QGBDT_OK) return rc;
             rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
                              ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
@@ -599,12 +603,12 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         if (ctx->host_state->done) break;
         if (launched > round_cap) return set_error(ctx, QGBDT_E_HIP, "tree growth did not finish in %d rounds", launched);
         // the trailing plan has already chosen a batch: finish that round, then continue
-        rc = launch_batch_partition_count(ctx, rows, bins_t);
+        rc = launch_batch_partition_count(ctx, rows, bins_t, ordered);
         if (rc != QGBDT_OK) return rc;
         hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
                            ctx->seg_counts, ctx->seg_prefix, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                            plan);
-        rc = launch_batch_partition_scatter(ctx, rows);
+        rc = launch_batch_partition_scatter(ctx, rows, ordered);
         if (rc != QGBDT_OK) return rc;
         rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
                          ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step);
