@@ -116,9 +116,10 @@ typedef struct {
 
 /* Creates a context for `shape` on the current device and allocates its workspace
  * (three row-index buffers, quantized gradients, a pool of histograms, small
- * descriptors; for 16..64 features that are a multiple of 4 also three leaf-ordered
- * copies of the bin rows).  `stream` is a hipStream_t (NULL = default stream).
- * Synchronous. */
+ * descriptors).  Three leaf-ordered copies of the bin rows (16..64 features that are a
+ * multiple of 4, matrix not bound), the feature-major copy of a bound matrix and the
+ * derivative buffers of qgbdt_boost_iteration are allocated by the first call that needs
+ * them.  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
 QGBDT_API int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream);
 /* Frees the workspace and the context.  Synchronises the stream first. */
 QGBDT_API int qgbdt_destroy(qgbdt_ctx* ctx);

@@ -65,6 +65,27 @@ static void free_all(qgbdt_ctx* c) {
     }
 }
 
+}  // namespace qgbdt
+
+// The three leaf-ordered copies of the bin rows and packed gradients (ordered mode), allocated on first use.
+int qgbdt::ensure_ordered_buffers(qgbdt_ctx* c) {
+    if (c->obins[0] && c->obins[1] && c->obins[2] && c->ogh[0] && c->ogh[1] && c->ogh[2]) return QGBDT_OK;
+    const size_t N = (size_t)c->shape.n_rows;
+    for (int b = 0; b < 3; ++b) {
+        if (!c->obins[b]) {
+            int rc = qgbdt::ws_alloc(c, &c->obins[b], N * c->shape.n_features);
+            if (rc != QGBDT_OK) { c->obins[b] = nullptr; return rc; }
+        }
+        if (!c->ogh[b]) {
+            int rc = qgbdt::ws_alloc(c, &c->ogh[b], N);
+            if (rc != QGBDT_OK) { c->ogh[b] = nullptr; return rc; }
+        }
+    }
+    return QGBDT_OK;
+}
+
+namespace qgbdt {
+
 static int check_bits(qgbdt_ctx* ctx, int bits_g, int bits_h) {
     if (bits_g < 2 || bits_g > 8 || !(bits_h == 0 || (bits_h >= 2 && bits_h <= 8)))
         return set_error(ctx, QGBDT_E_INVALID_ARG, "bits_g=%d, bits_h=%d outside 2..8 (bits_h = 0: constant hessians)", bits_g, bits_h);
@@ -113,15 +134,9 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
         }
     }
     int rc = QGBDT_OK;
-    // narrow rows: moving a row costs less than gathering it twice per level
+    // narrow rows may be kept in leaf order (the copies are allocated by the first tree that is grown that way)
     c->ordered = (shape->bin_bytes == 1 && shape->n_features % 4 == 0 && shape->n_features >= 16 &&
                   shape->n_features <= 64) ? 1 : 0;
-    if (c->ordered) {
-        for (int b = 0; b < 3 && rc == QGBDT_OK; ++b) {
-            rc = ws_alloc(c, &c->obins[b], (size_t)N * shape->n_features);
-            if (rc == QGBDT_OK) rc = ws_alloc(c, &c->ogh[b], (size_t)N);
-        }
-    }
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
     if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[2], (size_t)N);

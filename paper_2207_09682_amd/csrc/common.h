@@ -233,6 +233,7 @@ int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, in
                        int feature, int bin, int64_t* n_left_out);
 int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t, bool ordered);
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
+int ensure_ordered_buffers(qgbdt_ctx* ctx);
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,

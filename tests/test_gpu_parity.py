@@ -706,6 +706,7 @@ def test_grow_tree_with_bound_bins(N, F, nb, L, bb):
     dbins.copy_(torch.from_numpy(bins2))
     ctx.bind_bins(dbins)
     _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
+    before = ctx.workspace_bytes
     ctx.bind_bins(None)
-    assert ctx.workspace_bytes == ws0
+    assert ctx.workspace_bytes == before - N * F * bb and ctx.workspace_bytes >= ws0
     _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
