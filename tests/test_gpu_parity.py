@@ -710,3 +710,50 @@ def test_grow_tree_with_bound_bins(N, F, nb, L, bb):
     ctx.bind_bins(None)
     assert ctx.workspace_bytes == before - N * F * bb and ctx.workspace_bytes >= ws0
     _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
+
+
+# ----------------------------------------------------------------------------
+# seeded sweep over valid configurations
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_valid_configurations(seed):
+    # 100 seeded draws per seed of (rows, features, bins, bin type, leaf budget, bit widths, accumulator setting,
+    # bound matrix or not, rounding, minimum rows per leaf): two trees each, every output against the oracle
+    from paper_2207_09682_amd import Context
+    rng = np.random.default_rng(seed)
+    for case in range(100):
+        bb = 2 if rng.random() < 0.15 else 1
+        N = int(rng.choice([1, 2, 3, 17, 100, 1000, 5000, 20000, 60000, 150000]))
+        F = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 20, 28, 30, 32, 33, 48, 63, 64, 65, 72, 100, 128, 130, 200, 256, 300]))
+        if N * F > 12_000_000:
+            F = max(1, 12_000_000 // N)
+        nb = int(rng.choice([2, 3, 4, 16, 63, 64, 100, 255, 256])) if bb == 1 else int(rng.choice([257, 300, 700, 1024]))
+        L = int(rng.choice([2, 3, 7, 15, 31, 63]))
+        bits = [(2, 2), (3, 3), (4, 4), (5, 5), (3, 8), (8, 2), (3, 0), (6, 3)][int(rng.integers(0, 8))]
+        acc = int(rng.choice([0, 16, 32]))
+        bind = bool(rng.random() < 0.5)
+        rounding = int(rng.random() < 0.2)
+        md = int(rng.choice([0, 1, 5, 20]))
+        bins = rng.integers(0, nb, (N, F)).astype(np.uint16 if bb == 2 else np.uint8)
+        if rng.random() < 0.3:
+            bins[:, 0] = np.where(rng.random(N) < 0.8, 0, bins[:, 0])
+        sig = (bins[:, F // 2].astype(np.float64) / nb - 0.5) * 3 + (bins[:, 0] > nb // 3) * 0.7
+        y = (rng.random(N) < 1 / (1 + np.exp(-sig))).astype(np.float32)
+        pr = 1 / (1 + np.exp(-rng.normal(scale=0.5, size=N)))
+        g = (pr - y).astype(np.float32)
+        h = (pr * (1 - pr)).astype(np.float32) if bits[1] != 0 else np.full(N, 1.0, np.float32)
+        what = dict(case=case, N=N, F=F, nb=nb, bb=bb, L=L, bits=bits, acc=acc, bind=bind, rounding=rounding, md=md)
+        ctx = Context(N, F, nb, max_leaves=L, bin_bytes=bb)
+        dbins = torch.from_numpy(bins).cuda()
+        if bind:
+            ctx.bind_bins(dbins)
+        for it in range(2):
+            t = ctx.grow_tree(dbins, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), bits[0], bits[1], 77, it, L,
+                              min_data_in_leaf=md, acc_width=acc, rounding=rounding)
+            e = oracle.grow_tree(bins, nb, g, h, bits[0], bits[1], 77, it, L, min_data=md, rounding=rounding)
+            try:
+                _compare_tree(t, e, N)
+            except AssertionError as err:
+                raise AssertionError(f"{what}: {err}") from err
+        del ctx
