@@ -757,3 +757,44 @@ def test_random_valid_configurations(seed):
             except AssertionError as err:
                 raise AssertionError(f"{what}: {err}") from err
         del ctx
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_histogram_slices(seed):
+    # seeded draws of shape, bit widths, accumulator setting and row set (contiguous slice or gathered slice of a
+    # sorted row list) for the stand-alone build; bit-exact against the oracle
+    from paper_2207_09682_amd import Context
+    rng = np.random.default_rng(seed)
+    for case in range(120):
+        bb = 2 if rng.random() < 0.15 else 1
+        N = int(rng.choice([1, 5, 64, 1000, 4097, 30000, 120000]))
+        F = int(rng.choice([1, 3, 4, 6, 9, 16, 28, 31, 40, 64, 66, 96, 136, 200, 272, 520]))
+        if N * F > 10_000_000:
+            F = max(1, 10_000_000 // N)
+        nb = int(rng.choice([2, 5, 16, 63, 128, 255, 256])) if bb == 1 else int(rng.choice([300, 1024]))
+        bg, bh = [(2, 2), (3, 3), (4, 4), (5, 5), (3, 8), (8, 8), (2, 7), (3, 0)][int(rng.integers(0, 8))]
+        acc = int(rng.choice([0, 16, 32]))
+        bins = rng.integers(0, nb, (N, F)).astype(np.uint16 if bb == 2 else np.uint8)
+        kg, kh = 2 ** (bg - 1) - 1, (2 ** bh - 2 if bh else 1)
+        gq = rng.integers(-kg, kg + 1, N).astype(np.int8)
+        hq = rng.integers(0, kh + 1, N).astype(np.uint8) if bh else np.ones(N, np.uint8)
+        gh = torch.from_numpy(_pack_gh(gq, hq)).cuda()
+        ctx = Context(N, F, nb, max_leaves=4, bin_bytes=bb)
+        dbins = torch.from_numpy(bins).cuda()
+        kw = {}
+        if rng.random() < 0.5:
+            m = int(rng.integers(1, N + 1))
+            idx = np.sort(rng.choice(N, m, replace=False)).astype(np.int32)
+            b = int(rng.integers(0, m)); c = int(rng.integers(0, m - b + 1))
+            kw = dict(row_idx=idx, begin=b, count=c)
+        else:
+            b = int(rng.integers(0, N)); c = int(rng.integers(0, N - b + 1))
+            kw = dict(begin=b, count=c)
+        exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq, **kw))
+        gkw = dict(kw)
+        if "row_idx" in gkw:
+            gkw["row_idx"] = torch.from_numpy(gkw["row_idx"]).cuda()
+        got = ctx.build_histograms(dbins, gh, bits_g=bg, bits_h=bh, acc_width=acc, **gkw).cpu().numpy().reshape(nb, F)
+        assert np.array_equal(got, exp), dict(case=case, N=N, F=F, nb=nb, bb=bb, bits=(bg, bh), acc=acc,
+                                              begin=kw["begin"], count=kw["count"], gathered="row_idx" in kw)
+        del ctx
