@@ -378,9 +378,48 @@ __global__ __launch_bounds__(256) void transpose_bins_kernel(const T* __restrict
     }
 }
 
+// The same for 8-bit bins when both the row count and the feature count are multiples of 4: 64 x 64 tiles, a
+// dword (four features of a row) per load and a dword (four rows of a feature) per store.
+__global__ __launch_bounds__(256) void transpose_bins4_kernel(const uint8_t* __restrict__ in, uint8_t* __restrict__ out,
+                                                              int64_t N, int F) {
+    __shared__ uint8_t tile[64][68];  // [row][feature]; pitch 68 keeps the dword stores of a row aligned
+    const int c = threadIdx.x & 15, r = threadIdx.x >> 4;  // 16 dword columns x 16 rows per pass
+    const int64_t tiles_r = (N + 63) / 64;
+    const int tiles_f = (F + 63) / 64;
+    for (int64_t t = blockIdx.x; t < tiles_r * tiles_f; t += gridDim.x) {
+        const int64_t r0 = (t / tiles_f) * 64;
+        const int f0 = (int)(t % tiles_f) * 64;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int rr = r + 16 * k;
+            uint32_t v = 0u;
+            if (r0 + rr < N && f0 + 4 * c < F) v = *reinterpret_cast<const uint32_t*>(in + (r0 + rr) * F + f0 + 4 * c);
+            *reinterpret_cast<uint32_t*>(&tile[rr][4 * c]) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int ff = r + 16 * k;  // feature of the tile; c: group of four rows
+            if (f0 + ff < F && r0 + 4 * c < N) {
+                const uint32_t v = (uint32_t)tile[4 * c][ff] | ((uint32_t)tile[4 * c + 1][ff] << 8) |
+                                   ((uint32_t)tile[4 * c + 2][ff] << 16) | ((uint32_t)tile[4 * c + 3][ff] << 24);
+                *reinterpret_cast<uint32_t*>(out + (int64_t)(f0 + ff) * N + r0 + 4 * c) = v;
+            }
+        }
+    }
+}
+
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out) {
     const int64_t N = ctx->shape.n_rows;
     const int F = ctx->shape.n_features;
+    if (ctx->shape.bin_bytes == 1 && N % 4 == 0 && F % 4 == 0 && (((uintptr_t)bins | (uintptr_t)out) & 3) == 0) {
+        const int64_t tiles4 = ((N + 63) / 64) * ((F + 63) / 64);
+        hipLaunchKernelGGL(transpose_bins4_kernel, dim3((unsigned)(tiles4 < 65536 ? tiles4 : 65536)), dim3(256), 0,
+                           ctx->stream, static_cast<const uint8_t*>(bins), static_cast<uint8_t*>(out), N, F);
+        QG_HIP(ctx, hipGetLastError());
+        return QGBDT_OK;
+    }
     int64_t tiles = ((N + 31) / 32) * ((F + 31) / 32);
     const int grid = (int)(tiles < 65536 ? tiles : 65536);
     if (ctx->shape.bin_bytes == 2)
