@@ -135,7 +135,10 @@ QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
  * (n_rows * n_features * bin_bytes more workspace, allocated at the first call).  The counting pass of
  * the row partition then reads the split feature's column -- the ascending row ids of a node fall into
  * few memory sectors -- instead of one sector of the row-major matrix per row, and narrow matrices, whose
- * rows are otherwise moved into leaf order level by level, are left in place.  Results do not change.
+ * rows are otherwise moved into leaf order level by level, are left in place.  The call also samples the
+ * columns for each feature's most frequent bin; when most features have a bin that holds most of their rows,
+ * the wide-row histogram kernels leave that bin out and the entry is rebuilt from the totals.  Results do not
+ * change.
  * Call again after the matrix' contents change; a grow_tree call with another pointer simply does not
  * use the copy; bins = NULL frees it (synchronises the stream first). */
 QGBDT_API int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins);

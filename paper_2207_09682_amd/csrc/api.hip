@@ -20,18 +20,21 @@ int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...) {
     return code;
 }
 
-// sum of h~ and |g~| over a row set (only used when the a-priori bound cannot rule out overflow)
+// sums of g~, h~ and |g~| over a row set (totals[0..2]): for the overflow check when the a-priori bound cannot rule
+// overflow out, and for completing a stand-alone histogram whose most frequent bins were left out
 __global__ __launch_bounds__(256) void gh_totals_kernel(const int16_t* __restrict__ gh, const int32_t* __restrict__ idx,
                                                         int64_t begin, int64_t count, int64_t* totals) {
-    int64_t sh = 0, sa = 0;
+    int64_t sh = 0, sa = 0, sg = 0;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < count; p += (int64_t)gridDim.x * blockDim.x) {
         const int64_t i = idx ? (int64_t)idx[begin + p] : begin + p;
         const int v = gh[i];
         sh += v & 0xff;
         sa += abs(v >> 8);
+        sg += v >> 8;
     }
-    for (int o = 32; o > 0; o >>= 1) { sh += __shfl_xor(sh, o); sa += __shfl_xor(sa, o); }
+    for (int o = 32; o > 0; o >>= 1) { sh += __shfl_xor(sh, o); sa += __shfl_xor(sa, o); sg += __shfl_xor(sg, o); }
     if ((threadIdx.x & 63) == 0) {
+        atomicAdd((unsigned long long*)&totals[0], (unsigned long long)sg);
         atomicAdd((unsigned long long*)&totals[1], (unsigned long long)sh);
         atomicAdd((unsigned long long*)&totals[2], (unsigned long long)sa);
     }
@@ -51,7 +54,7 @@ static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
 
 static void free_all(qgbdt_ctx* c) {
     void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->bins_t, c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
+                    c->idx[2], c->bins_t, c->mfb, c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
                     c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->sorted_idx, c->step, c->batch, c->cand, c->hist_entries,
                     c->hist_counts, c->pwork, c->scan_items, c->leaf_node, c->refit_partial,
                     c->tmp_i64};
@@ -146,11 +149,12 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (rc == QGBDT_OK) {
         // slots of the row groups' local bins, for either accumulator width
         size_t need = 0;
-        for (int w = 16; w <= 32; w += 16) {
-            const HistPlan hp = make_hist_plan(*shape, 2, 2, w);
-            const size_t b = (size_t)hp.max_items * hp.n_tiles * hp.slot_bytes;
-            if (b > need) need = b;
-        }
+        for (int w = 16; w <= 32; w += 16)
+            for (int skew = 0; skew < 2; ++skew) {
+                const HistPlan hp = make_hist_plan(*shape, 2, 2, w, skew != 0);
+                const size_t b = (size_t)hp.max_items * hp.n_tiles * hp.slot_bytes;
+                if (b > need) need = b;
+            }
         unsigned char* pp = nullptr;
         rc = ws_alloc(c, &pp, need);
         c->hist_partials = pp;
@@ -251,20 +255,29 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     rc = launch_fill_zero(ctx, hist_out, W);
     if (rc != QGBDT_OK) return rc;
     if (count == 0) return QGBDT_OK;
-    const HistPlan plan = make_hist_plan_for(ctx->shape, bits_g, bits_h, acc_width, count);
+    // most frequent bins of the bound matrix are left out by the wide-row kernels and filled in afterwards
+    const uint16_t* mfb = (ctx->mfb_features > 0 && ctx->bound_bins == bins) ? ctx->mfb : nullptr;
+    const HistPlan plan = make_hist_plan_for(ctx->shape, bits_g, bits_h, acc_width, count, mfb != nullptr);
+    if (mfb && plan.wide_v == 0) mfb = nullptr;  // only those kernels skip
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
     RowSource rows;
     IdxSet idx;
     for (int b = 0; b < 4; ++b) { rows.bins[b] = (const uint8_t*)bins; rows.gh[b] = gh; idx.p[b] = const_cast<int32_t*>(row_idx); }
-    return launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
-                       ctx->hist_entries, ctx->hist_counts, hist_out,
-                       (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step);
+    rc = launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
+                     ctx->hist_entries, ctx->hist_counts, hist_out,
+                     (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step, mfb);
+    if (rc != QGBDT_OK || !mfb) return rc;
+    hipLaunchKernelGGL(zero3_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->tmp_i64);
+    hipLaunchKernelGGL(gh_totals_kernel, dim3(1024), dim3(256), 0, ctx->stream, gh, row_idx, begin, count, ctx->tmp_i64);
+    QG_HIP(ctx, hipGetLastError());
+    return launch_fix_frequent_bins(ctx, hist_out, ctx->tmp_i64, mfb);
 }
 
 int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     ctx->bound_bins = nullptr;
+    ctx->mfb_features = 0;
     if (!bins) {
         if (ctx->bins_t) {
             QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -281,6 +294,23 @@ int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
     }
     int rc = launch_transpose_bins(ctx, bins, ctx->bins_t);
     if (rc != QGBDT_OK) return rc;
+    // most frequent bins (left out by the wide-row histogram kernels); the host learns how many features have one
+    ctx->mfb_features = 0;
+    if (!ctx->mfb) {
+        rc = ws_alloc(ctx, &ctx->mfb, (size_t)ctx->shape.n_features);
+        if (rc != QGBDT_OK) { ctx->mfb = nullptr; return rc; }
+    }
+    rc = launch_frequent_bins(ctx, ctx->bins_t, ctx->mfb);
+    if (rc != QGBDT_OK) return rc;
+    {
+        std::vector<uint16_t> host((size_t)ctx->shape.n_features);
+        QG_HIP(ctx, hipMemcpyAsync(host.data(), ctx->mfb, host.size() * sizeof(uint16_t), hipMemcpyDeviceToHost, ctx->stream));
+        QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        int n = 0;
+        for (uint16_t v : host) n += (v != 0xffff) ? 1 : 0;
+        // worth the extra compare per bin only when many features have such a bin
+        ctx->mfb_features = (2 * n >= ctx->shape.n_features) ? n : 0;
+    }
     ctx->bound_bins = bins;
     return QGBDT_OK;
 }

@@ -158,6 +158,8 @@ struct qgbdt_ctx {
     int16_t* ogh[3];       // [N] each (ordered mode)
     int32_t* idx[3];       // [N] each
     uint8_t* bins_t;       // [F][N] feature-major copy of the bound bin matrix (qgbdt_bind_bins), else null
+    uint16_t* mfb;         // [F] most frequent bin of each feature of the bound matrix when it holds most rows, else 0xffff
+    int mfb_features;      // features with such a bin (0: no skipping)
     const void* bound_bins; // the matrix that copy was made from
     int16_t* gh;           // [N]
     float2* ghf;           // [N] (g, h) interleaved, written by the quantizer for the refit's gather
@@ -214,17 +216,17 @@ int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...);
 int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, int bits_g, int bits_h,
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
                     int64_t* totals_out, float2* pairs_out);
-HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width);
-HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows);
+HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, bool skew = false);
+HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew = false);
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
 int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,
                 bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
-                int64_t grid_items, StepState* step);
+                int64_t grid_items, StepState* step, const uint16_t* mfb = nullptr);
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess);
+                      const float* delta, int min_data, double min_sum_hess, const uint16_t* mfb = nullptr);
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
                          const float* delta, int min_data, double min_sum_hess, qgbdt_split* out);
 int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, int32_t* buf1, const PartWork* work,
@@ -233,6 +235,8 @@ int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, in
                        int feature, int bin, int64_t* n_left_out);
 int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const uint8_t* bins_t, bool ordered);
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
+int launch_frequent_bins(qgbdt_ctx* ctx, const void* bins_t, uint16_t* mfb);
+int launch_fix_frequent_bins(qgbdt_ctx* ctx, int64_t* hist, const int64_t* totals, const uint16_t* mfb);
 int ensure_ordered_buffers(qgbdt_ctx* ctx);
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,

@@ -325,11 +325,12 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 //  V = 8:  (tiles of at most 64 features, unpadded) half of the rows swap the two dwords of their
 //          piece, which together with the byte rotation spreads an instruction over 32 columns.
 template <int W, bool IDX, int V, int U>
-__global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource src, IdxSet idxs,
+__global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet idxs,
                                                                     const HistEntry* __restrict__ entries,
                                                                     const int32_t* __restrict__ table_counts,
                                                                     int64_t* hist_base, unsigned char* partials, int F,
-                                                                    int nb, HistPlan plan, StepState* step) {
+                                                                    int nb, HistPlan plan, StepState* step,
+                                                                    const uint16_t* __restrict__ mfb) {
     using word = typename Acc<W>::word;
     using vec = typename std::conditional<V == 16, uint4, uint2>::type;
     constexpr int NV = V / 4;  // dwords per lane
@@ -369,6 +370,19 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
         const int col0 = (V == 16) ? 20 * c : 8 * c + (swap ? 4 : 0);
         flk[k] = (uint32_t)(col0 + cc) * (uint32_t)sizeof(word);
     }
+    // Bins that are not accumulated (most frequent bin of a feature, when the caller bound the matrix and the
+    // bin holds most of the feature's rows): skip[i][k] is that bin for the column the lane's (i, k)-th atomic
+    // goes to, or a value no bin takes.  The split search rebuilds the skipped entry from the leaf's totals.
+    uint32_t skipb[NV][4];
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int cc = (k + rot) & 3;
+            const int dwi = (V == 16) ? i : (swap ? 1 - i : i);  // which dword of the piece the i-th handled one is
+            const int col = f0 + V * c + 4 * dwi + cc;
+            skipb[i][k] = (mfb != nullptr && lane_on && col < F) ? (uint32_t)mfb[col] : 0xffffu;
+        }
     // byte offset from the first to the second handled dword's columns (V = 8: -4 columns when swapped)
     const uint32_t step2 = (uint32_t)((swap ? -4 : 4) * (int)sizeof(word));
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);
@@ -444,7 +458,8 @@ __global__ __launch_bounds__(HIST_THREADS, 4) void hist_wide_kernel(RowSource sr
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
-                                Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k] + ioff)), v);
+                                if (b != skipb[i][k])
+                                    Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k] + ioff)), v);
                             }
                         }
                     }
@@ -742,7 +757,7 @@ static int64_t rows_fitting_word32(int bits_g, int bits_h, int* hshift) {
 }
 
 // Chooses tile width, accumulator width and launch shape for a problem shape.
-HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width) {
+HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, bool skew) {
     HistPlan p{};
     const int F = s.n_features, nb = s.n_bins;
     int hshift = 16;
@@ -765,8 +780,13 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
         if (wide_ft) { p.wide_v = 16; p.pad16 = 1; }
     } else if (F % 8 == 0 && F > 64) {
         // 8-byte pieces, at most 64 features per tile, unpadded
+        // With 64-bit words and most-frequent-bin skipping, 64-feature tiles (130 KB of local bins, one workgroup
+        // of 1024 threads per CU): whole 64-byte pieces of a row per lane group.  Without skipping the 64-bit
+        // LDS atomics of such a tile cost more than its loads save (5M x 200: 577 against 476 us; with 70 % of
+        // the entries skipped 373 us).
+        const int budget8 = (skew && wbytes == 8) ? 136 * 1024 : lds_budget;
         for (int ft = 64; ft >= 32 && !wide_ft; ft >>= 1)
-            if ((int64_t)ft * nb * wbytes <= lds_budget) wide_ft = ft;
+            if ((int64_t)ft * nb * wbytes <= budget8) wide_ft = ft;
         if (wide_ft) p.wide_v = 8;
     }
     if (wide_ft) {
@@ -816,12 +836,13 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.chunk_rows = (int32_t)((lim > 0x40000000LL) ? 0x40000000LL : lim);
     if (p.chunk_rows < 1) p.chunk_rows = 1;
     p.min_rows_per_group = 2048;
-    p.threads = HIST_THREADS;
+    p.threads = (p.lds_bytes > 80 * 1024) ? 1024 : HIST_THREADS;
     int per_cu = (160 * 1024) / (p.lds_bytes > 0 ? p.lds_bytes : 1);
     // one-tile launches: the flat kernel needs ~100 VGPRs, so 16 wavefronts per CU are resident at once and
     // twice as many row groups would only double the slots to write and reduce; tiled launches measured
     // better with the groups of 32 wavefronts per CU
-    const int by_waves = (p.n_tiles == 1 ? 16 : 32) / (p.threads / 64);
+    int by_waves = (p.n_tiles == 1 ? 16 : 32) / (p.threads / 64);
+    if (by_waves < 1) by_waves = 1;
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
     int groups = (256 * per_cu) / p.n_tiles;
@@ -849,10 +870,10 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
 // every row group can fit one chunk (the item table has room for rows / single_rows groups):
 // beyond that groups would merge their earlier chunks through global atomics, which costs more
 // than the 64-bit LDS atomics of 32|32 words (10.5 M rows, 5-bit: 236 us against 93 us).
-HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows) {
-    HistPlan p = make_hist_plan(s, bits_g, bits_h, acc_width);
+HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew) {
+    HistPlan p = make_hist_plan(s, bits_g, bits_h, acc_width, skew);
     if (acc_width == 0 && p.acc_width == 16 && rows / p.single_rows >= (int64_t)p.max_items - 2)
-        p = make_hist_plan(s, bits_g, bits_h, 32);
+        p = make_hist_plan(s, bits_g, bits_h, 32, skew);
     return p;
 }
 
@@ -881,7 +902,7 @@ int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, i
 // the number of work items; workgroups beyond the table's item count return at once.
 int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,
                 bool flat_ok, const HistEntry* entries, const int32_t* table_counts, int64_t* hist_base,
-                int64_t grid_items, StepState* step) {
+                int64_t grid_items, StepState* step, const uint16_t* mfb) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     unsigned char* partials = static_cast<unsigned char*>(ctx->hist_partials);
     int64_t groups = grid_items;
@@ -915,8 +936,13 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
 #undef QG_LAUNCH_FLAT
     } else if (fast && plan.wide_v > 0 && wide_ok) {
 #define QG_LAUNCH_WIDE(W_, IDX_, V_, U_)                                                                              \
-    hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
-                       entries, table_counts, hist_base, partials, F, nb, plan, step)
+    do {                                                                                                              \
+        if (plan.lds_bytes > 64 * 1024)                                                                               \
+            QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(hist_wide_kernel<W_, IDX_, V_, U_>),        \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, plan.lds_bytes));             \
+        hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
+                           entries, table_counts, hist_base, partials, F, nb, plan, step, mfb);                       \
+    } while (0)
 #define QG_LAUNCH_WIDE_V(W_, IDX_) \
     if (plan.wide_v == 16) QG_LAUNCH_WIDE(W_, IDX_, 16, 4); else QG_LAUNCH_WIDE(W_, IDX_, 8, 4)
         if (plan.acc_width == 16) {

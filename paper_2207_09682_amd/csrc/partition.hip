@@ -410,6 +410,85 @@ __global__ __launch_bounds__(256) void transpose_bins4_kernel(const uint8_t* __r
     }
 }
 
+// Most frequent bin of every feature, from a strided sample of at most 65536 rows of the feature-major copy (the
+// choice only steers which bin the histogram kernels leave out; any bin would be correct).  mfb[f] = that bin when
+// it holds at least half of the sampled rows, else 0xffff.  One workgroup per feature.
+template <typename T>
+__global__ __launch_bounds__(256) void frequent_bins_kernel(const T* __restrict__ bins_t, int64_t N, int nb,
+                                                            uint16_t* __restrict__ mfb) {
+    __shared__ int cnt[1024];
+    __shared__ int s_best[4], s_bin[4];
+    const int f = blockIdx.x;
+    for (int b = threadIdx.x; b < 1024; b += blockDim.x) cnt[b] = 0;
+    __syncthreads();
+    const int64_t stride = N > 65536 ? N / 65536 : 1;
+    const int64_t n_s = N > 65536 ? 65536 : N;
+    const T* col = bins_t + (int64_t)f * N;
+    for (int64_t j = threadIdx.x; j < n_s; j += blockDim.x) {
+        const int v = (int)col[j * stride];
+        // lanes with equal values are counted by one of them: same-address LDS atomics serialize
+        const unsigned long long active = __ballot(1);
+        unsigned long long rest = active;
+        const int lane = threadIdx.x & 63;
+        while (rest) {
+            const int lead = __ffsll((long long)rest) - 1;
+            const int lv = __shfl(v, lead);
+            const unsigned long long same = __ballot(v == lv) & rest;
+            if (lane == lead) atomicAdd(&cnt[lv], __popcll(same));
+            rest &= ~same;
+        }
+    }
+    __syncthreads();
+    int best = -1, bin = 0;
+    for (int b = threadIdx.x; b < nb; b += blockDim.x)
+        if (cnt[b] > best) { best = cnt[b]; bin = b; }
+    for (int o = 32; o > 0; o >>= 1) {
+        const int ob = __shfl_xor(best, o), obin = __shfl_xor(bin, o);
+        if (ob > best || (ob == best && obin < bin)) { best = ob; bin = obin; }
+    }
+    if ((threadIdx.x & 63) == 0) { s_best[threadIdx.x >> 6] = best; s_bin[threadIdx.x >> 6] = bin; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k)
+            if (s_best[k] > best || (s_best[k] == best && s_bin[k] < bin)) { best = s_best[k]; bin = s_bin[k]; }
+        mfb[f] = (2 * (int64_t)best >= n_s) ? (uint16_t)bin : (uint16_t)0xffff;
+    }
+}
+
+int launch_frequent_bins(qgbdt_ctx* ctx, const void* bins_t, uint16_t* mfb) {
+    const int64_t N = ctx->shape.n_rows;
+    const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
+    if (ctx->shape.bin_bytes == 2)
+        hipLaunchKernelGGL(frequent_bins_kernel<uint16_t>, dim3(F), dim3(256), 0, ctx->stream,
+                           static_cast<const uint16_t*>(bins_t), N, nb, mfb);
+    else
+        hipLaunchKernelGGL(frequent_bins_kernel<uint8_t>, dim3(F), dim3(256), 0, ctx->stream,
+                           static_cast<const uint8_t*>(bins_t), N, nb, mfb);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
+// Completes a stand-alone histogram whose kernels left out the most frequent bins: the entry of feature f's
+// bin mfb[f] becomes the build's totals minus the feature's other entries.  totals: (sum g~, sum h~).
+__global__ __launch_bounds__(256) void fix_frequent_bins_kernel(int64_t* hist, const int64_t* __restrict__ totals,
+                                                                const uint16_t* __restrict__ mfb, int F, int nb) {
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= F) return;
+    const int mb = mfb[f];
+    if (mb == 0xffff) return;
+    int64_t all = 0;
+    for (int b = 0; b < nb; ++b) all += hist[(int64_t)b * F + f];
+    hist[(int64_t)mb * F + f] += (totals[0] * 4294967296LL + totals[1]) - all;
+}
+
+int launch_fix_frequent_bins(qgbdt_ctx* ctx, int64_t* hist, const int64_t* totals, const uint16_t* mfb) {
+    const int F = ctx->shape.n_features;
+    hipLaunchKernelGGL(fix_frequent_bins_kernel, dim3((F + 255) / 256), dim3(256), 0, ctx->stream, hist, totals, mfb, F,
+                       ctx->shape.n_bins);
+    QG_HIP(ctx, hipGetLastError());
+    return QGBDT_OK;
+}
+
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out) {
     const int64_t N = ctx->shape.n_rows;
     const int F = ctx->shape.n_features;

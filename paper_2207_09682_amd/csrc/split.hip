@@ -40,7 +40,8 @@ __global__ void scan_items_from_stats_kernel(const qgbdt_leafstat* stats, int n,
 __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                    const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                    const float* __restrict__ delta, int64_t min_data,
-                                                   double min_sum_hess, FeatCand* cand_base, int glog) {
+                                                   double min_sum_hess, FeatCand* cand_base, int glog,
+                                                   const uint16_t* __restrict__ mfb) {
     const int n_items = *n_items_ptr;
     // Workgroup -> feature: histograms are [bin][feature], so the 16 features of a 128-byte line are
     // read by 16 workgroups; consecutive workgroup ids go round-robin to the 8 XCDs, so the ids are
@@ -79,6 +80,16 @@ __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const Sc
         if (lane == 63) wtot[wave] = pre;
         __syncthreads();
         for (int k = 0; k < wave; ++k) pre += wtot[k];
+        if (mfb != nullptr) {
+            // The histogram kernels may have left out the feature's most frequent bin: the entry is then 0 and
+            // what is missing from the feature's sum over all bins -- the leaf's totals are known -- belongs to
+            // that bin.  (Nothing is missing when the bin was accumulated.)
+            const int mb = mfb[f];
+            int64_t all = 0;
+            for (int k = 0; k < (int)(blockDim.x >> 6); ++k) all += wtot[k];
+            const int64_t missing = (it.stat.sum_g * 4294967296LL + it.stat.sum_h) - all;
+            if (mb != 0xffff && b >= mb) pre += missing;
+        }
 
         const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
         double gain = 0.0;
@@ -126,7 +137,8 @@ __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const Sc
 __global__ __launch_bounds__(1024) void scan_tile_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                          const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                          const float* __restrict__ delta, int64_t min_data,
-                                                         double min_sum_hess, FeatCand* cand_base) {
+                                                         double min_sum_hess, FeatCand* cand_base,
+                                                         const uint16_t* __restrict__ mfb) {
     const int n_items = *n_items_ptr;
     const int f0 = blockIdx.x * 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -156,6 +168,12 @@ __global__ __launch_bounds__(1024) void scan_tile_kernel(int64_t* hist_base, con
         for (int o = 1; o < 64; o <<= 1) {
             const int64_t v = __shfl_up(pre, o);
             if (lane >= o) pre += v;
+        }
+        if (mfb != nullptr) {  // the feature's most frequent bin may have been left out (see scan_kernel)
+            const int mb = mfb[f];
+            const int64_t all = __shfl(pre, 63);
+            const int64_t missing = (it.stat.sum_g * 4294967296LL + it.stat.sum_h) - all;
+            if (mb != 0xffff && lane >= mb) pre += missing;
         }
         const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
         double gain = 0.0;
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(256) void reduce_items_kernel(const FeatCand* __res
 }
 
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess) {
+                      const float* delta, int min_data, double min_sum_hess, const uint16_t* mfb) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int threads = 64;
     while (threads < nb) threads <<= 1;
@@ -266,12 +284,12 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
         if (gy > max_items) gy = max_items;
         if (gy < 1) gy = 1;
         hipLaunchKernelGGL(scan_tile_kernel, dim3(gx, gy), dim3(1024), 0, ctx->stream, hist_base, items, n_items, F, nb,
-                           delta, (int64_t)min_data, min_sum_hess, ctx->cand);
+                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, mfb);
     } else {
         const int per = 8 << glog;
         const int gx = (F + per - 1) / per * per;
         hipLaunchKernelGGL(scan_kernel, dim3(gx, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb,
-                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, glog);
+                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, glog, mfb);
     }
     int gr = F > 256 ? max_items : (max_items + 3) / 4;
     if (gr > 64) gr = 64;

@@ -798,3 +798,52 @@ def test_random_histogram_slices(seed):
         assert np.array_equal(got, exp), dict(case=case, N=N, F=F, nb=nb, bb=bb, bits=(bg, bh), acc=acc,
                                               begin=kw["begin"], count=kw["count"], gathered="row_idx" in kw)
         del ctx
+
+
+# ----------------------------------------------------------------------------
+# most-frequent-bin skipping (bound, skewed wide matrices)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,F,nb,bits", [(40000, 200, 255, (3, 8)), (25000, 2000, 63, (3, 3)), (30000, 72, 256, (4, 4)),
+                                         (20000, 136, 100, (3, 8))])
+def test_frequent_bin_skipping_on_skewed_wide_matrices(N, F, nb, bits):
+    # most features have one bin that holds most rows (a different bin per feature), some have none: the wide-row
+    # kernels leave that bin out, the stand-alone build fills it in afterwards, the split search of grow_tree
+    # rebuilds it from the leaf totals; everything bit-exact against the oracle
+    from paper_2207_09682_amd import Context
+    rng = np.random.default_rng(N + F)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint8)
+    fav = rng.integers(0, nb, F)
+    for f in range(F):
+        if f % 5 != 4:                                        # four features in five are skewed
+            bins[rng.random(N) < 0.75, f] = fav[f]
+    bg, bh = bits
+    gq, hq, gh = _rand_gh(rng, N, bg, bh, "cuda")
+    ctx = Context(N, F, nb, max_leaves=31)
+    dbins = torch.from_numpy(bins).cuda()
+    ctx.bind_bins(dbins)
+    idx = np.sort(rng.choice(N, N // 3, replace=False)).astype(np.int32)
+    didx = torch.from_numpy(idx).cuda()
+    for acc in (0, 16, 32):
+        for kw in (dict(), dict(begin=13, count=N - 50), dict(row_idx=idx), dict(row_idx=idx, begin=7, count=idx.size // 2),
+                   dict(begin=3, count=1)):
+            exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq, **kw))
+            gkw = dict(kw)
+            if "row_idx" in gkw:
+                gkw["row_idx"] = didx
+                gkw.setdefault("count", idx.size)
+            got = ctx.build_histograms(dbins, gh, bits_g=bg, bits_h=bh, acc_width=acc, **gkw).cpu().numpy().reshape(nb, F)
+            assert np.array_equal(got, exp), (kw.keys(), acc)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-((bins[:, 0] == fav[0]) * 1.5 - (bins[:, 1] > nb // 2) * 1.0)))).astype(np.float32)
+    score = np.zeros(N, np.float32)
+    for it in range(2):
+        pr = 1.0 / (1.0 + np.exp(-score.astype(np.float64)))
+        g = (pr - y).astype(np.float32); h = (pr * (1 - pr)).astype(np.float32)
+        for acc in (0, 32):
+            t = ctx.grow_tree(dbins, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), bg, bh, 5, it, 31,
+                              min_data_in_leaf=10, acc_width=acc)
+            e = oracle.grow_tree(bins, nb, g, h, bg, bh, 5, it, 31, min_data=10)
+            _compare_tree(t, e, N)
+        for l in range(e.n_leaves):
+            rows = e.row_idx[e.leaf_begin[l]: e.leaf_begin[l] + e.leaf_count[l]]
+            score[rows] += np.float32(0.3 * e.leaf_value[l])
