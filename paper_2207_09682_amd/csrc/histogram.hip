@@ -324,7 +324,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 //          spread over all 32 banks, two lanes each.
 //  V = 8:  (tiles of at most 64 features, unpadded) half of the rows swap the two dwords of their
 //          piece, which together with the byte rotation spreads an instruction over 32 columns.
-template <int W, bool IDX, int V, int U>
+template <int W, bool IDX, int V, int U, bool SKIP>
 __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet idxs,
                                                                     const HistEntry* __restrict__ entries,
                                                                     const int32_t* __restrict__ table_counts,
@@ -373,16 +373,18 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
     // Bins that are not accumulated (most frequent bin of a feature, when the caller bound the matrix and the
     // bin holds most of the feature's rows): skip[i][k] is that bin for the column the lane's (i, k)-th atomic
     // goes to, or a value no bin takes.  The split search rebuilds the skipped entry from the leaf's totals.
-    uint32_t skipb[NV][4];
+    uint32_t skipb[SKIP ? NV : 1][4];
+    if (SKIP) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i)
+        for (int i = 0; i < NV; ++i)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int cc = (k + rot) & 3;
-            const int dwi = (V == 16) ? i : (swap ? 1 - i : i);  // which dword of the piece the i-th handled one is
-            const int col = f0 + V * c + 4 * dwi + cc;
-            skipb[i][k] = (mfb != nullptr && lane_on && col < F) ? (uint32_t)mfb[col] : 0xffffu;
-        }
+            for (int k = 0; k < 4; ++k) {
+                const int cc = (k + rot) & 3;
+                const int dwi = (V == 16) ? i : (swap ? 1 - i : i);  // which dword of the piece the i-th handled one is
+                const int col = f0 + V * c + 4 * dwi + cc;
+                skipb[SKIP ? i : 0][k] = (lane_on && col < F) ? (uint32_t)mfb[col] : 0xffffu;
+            }
+    }
     // byte offset from the first to the second handled dword's columns (V = 8: -4 columns when swapped)
     const uint32_t step2 = (uint32_t)((swap ? -4 : 4) * (int)sizeof(word));
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);
@@ -458,7 +460,7 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
-                                if (b != skipb[i][k])
+                                if (!SKIP || b != skipb[SKIP ? i : 0][k])
                                     Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + flk[k] + ioff)), v);
                             }
                         }
@@ -935,13 +937,17 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         }
 #undef QG_LAUNCH_FLAT
     } else if (fast && plan.wide_v > 0 && wide_ok) {
-#define QG_LAUNCH_WIDE(W_, IDX_, V_, U_)                                                                              \
+#define QG_LAUNCH_WIDE_S(W_, IDX_, V_, U_, S_)                                                                        \
     do {                                                                                                              \
         if (plan.lds_bytes > 64 * 1024)                                                                               \
-            QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(hist_wide_kernel<W_, IDX_, V_, U_>),        \
+            QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(hist_wide_kernel<W_, IDX_, V_, U_, S_>),    \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, plan.lds_bytes));             \
-        hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
-                           entries, table_counts, hist_base, partials, F, nb, plan, step, mfb);                       \
+        hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_, S_>), grid, block, plan.lds_bytes, ctx->stream, rows,  \
+                           idx, entries, table_counts, hist_base, partials, F, nb, plan, step, mfb);                  \
+    } while (0)
+#define QG_LAUNCH_WIDE(W_, IDX_, V_, U_)                                                                              \
+    do {                                                                                                              \
+        if (mfb) QG_LAUNCH_WIDE_S(W_, IDX_, V_, U_, true); else QG_LAUNCH_WIDE_S(W_, IDX_, V_, U_, false);            \
     } while (0)
 #define QG_LAUNCH_WIDE_V(W_, IDX_) \
     if (plan.wide_v == 16) QG_LAUNCH_WIDE(W_, IDX_, 16, 4); else QG_LAUNCH_WIDE(W_, IDX_, 8, 4)
@@ -952,6 +958,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         }
 #undef QG_LAUNCH_WIDE_V
 #undef QG_LAUNCH_WIDE
+#undef QG_LAUNCH_WIDE_S
     } else if (fast) {
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
