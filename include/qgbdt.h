@@ -49,6 +49,14 @@ extern "C" {
 #define QGBDT_ROUND_STOCHASTIC 0 /* SR of Sec. 4.2 */
 #define QGBDT_ROUND_NEAREST 1    /* RN of Sec. 4.2 (half rounds up) */
 
+/* What moves when a leaf's rows are partitioned (results are identical for all of them). */
+#define QGBDT_ROWS_AUTO 0    /* ordered copies for an unbound matrix whose shape allows them, else row ids, with the
+                                packed gradients when the matrix is 128 MB or more */
+#define QGBDT_ROWS_IDS 1     /* row ids only; histogram builds gather bin rows and packed gradients */
+#define QGBDT_ROWS_IDS_GH 2  /* row ids and packed gradients; histogram builds gather the bin rows */
+#define QGBDT_ROWS_ORDERED 3 /* row ids, packed gradients and bin rows: every build reads contiguous memory
+                                (uint8 bins, 16..64 features that are a multiple of 4; else QGBDT_E_UNSUPPORTED) */
+
 typedef struct qgbdt_ctx qgbdt_ctx;
 
 /* Problem shape a context is created for. */
@@ -72,6 +80,7 @@ typedef struct {
     int32_t acc_width;        /* local accumulators: 0 auto; 16: 32-bit words (16|16 fields, or for unequal bit widths
                                  the split that takes the most rows, e.g. 13|19 for 3-bit g / 8-bit h);
                                  32: 64-bit words with 32|32 fields (Sec. 6.1, 7.4.3) */
+    int32_t row_layout;       /* QGBDT_ROWS_* */
     uint64_t seed;            /* key of the counter-based RNG */
     double min_sum_hessian;   /* minimum H~ * delta_h per child */
 } qgbdt_params;
@@ -116,10 +125,11 @@ typedef struct {
 
 /* Creates a context for `shape` on the current device and allocates its workspace
  * (three row-index buffers, quantized gradients, a pool of histograms, small
- * descriptors).  Three leaf-ordered copies of the bin rows (16..64 features that are a
- * multiple of 4, matrix not bound), the feature-major copy of a bound matrix and the
- * derivative buffers of qgbdt_boost_iteration are allocated by the first call that needs
- * them.  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
+ * descriptors).  Three copies of the packed gradients that follow the row-index buffers
+ * (2 bytes per row each) and, for 16..64 features that are a multiple of 4 when the matrix
+ * is not bound, three leaf-ordered copies of the bin rows, the feature-major copy of a
+ * bound matrix and the derivative buffers of qgbdt_boost_iteration are allocated by the
+ * first call that needs them.  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
 QGBDT_API int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream);
 /* Frees the workspace and the context.  Synchronises the stream first. */
 QGBDT_API int qgbdt_destroy(qgbdt_ctx* ctx);

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libqgbdt.so")
 
 ROUND_STOCHASTIC = 0
 ROUND_NEAREST = 1
+ROWS_AUTO, ROWS_IDS, ROWS_IDS_GH, ROWS_ORDERED = 0, 1, 2, 3
 
 EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
@@ -37,7 +38,7 @@ class Shape(C.Structure):
 class Params(C.Structure):
     _fields_ = [("bits_g", C.c_int32), ("bits_h", C.c_int32), ("rounding", C.c_int32),
                 ("num_leaves", C.c_int32), ("min_data_in_leaf", C.c_int32), ("acc_width", C.c_int32),
-                ("seed", C.c_uint64), ("min_sum_hessian", C.c_double)]
+                ("row_layout", C.c_int32), ("seed", C.c_uint64), ("min_sum_hessian", C.c_double)]
 
 
 class TreePtrs(C.Structure):
@@ -261,10 +262,11 @@ class Context:
                     z(1, torch.int64), z(self.shape.n_rows, torch.int32))
 
     def grow_tree(self, bins, g, h, bits_g, bits_h, seed, iteration, num_leaves, min_data_in_leaf=20,
-                  min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0, tree: Tree | None = None) -> Tree:
+                  min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0, tree: Tree | None = None,
+                  row_layout=ROWS_AUTO) -> Tree:
         self._sync_stream()
         tree = tree if tree is not None else self.new_tree()
-        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
+        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, row_layout, seed, min_sum_hessian)
         tp = tree.ptrs()
         self._chk(self.lib.qgbdt_grow_tree(self._h, self._bins(bins), _dev(g, torch.float32, "g"),
                                            _dev(h, torch.float32, "h"), C.byref(p), iteration, C.byref(tp),
@@ -304,12 +306,12 @@ class Context:
 
     def boost_iteration(self, bins, label, score, bits_g, bits_h, seed, iteration, num_leaves, learning_rate,
                         min_data_in_leaf=20, min_sum_hessian=0.0, rounding=ROUND_STOCHASTIC, acc_width=0,
-                        tree: Tree | None = None, group_size: int = 0) -> Tree:
+                        tree: Tree | None = None, group_size: int = 0, row_layout=ROWS_AUTO) -> Tree:
         """Loss derivatives, one tree and the score update on the device; `score` is updated in place.
         group_size > 0 selects the lambdarank loss (label = relevance), else binary cross-entropy."""
         self._sync_stream()
         tree = tree if tree is not None else self.new_tree()
-        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, seed, min_sum_hessian)
+        p = Params(bits_g, bits_h, rounding, num_leaves, min_data_in_leaf, acc_width, row_layout, seed, min_sum_hessian)
         tp = tree.ptrs()
         if group_size > 0:
             self._chk(self.lib.qgbdt_boost_iteration_lambdarank(

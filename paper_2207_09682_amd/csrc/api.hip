@@ -94,12 +94,12 @@ static void free_all(qgbdt_ctx* c) {
 
 }  // namespace qgbdt
 
-// The three leaf-ordered copies of the bin rows and packed gradients (ordered mode), allocated on first use.
-int qgbdt::ensure_ordered_buffers(qgbdt_ctx* c) {
-    if (c->obins[0] && c->obins[1] && c->obins[2] && c->ogh[0] && c->ogh[1] && c->ogh[2]) return QGBDT_OK;
+// The three rotating copies of the packed gradients in list order and, `with_bins` (ordered mode), of the bin rows;
+// allocated on first use.
+int qgbdt::ensure_ordered_buffers(qgbdt_ctx* c, bool with_bins) {
     const size_t N = (size_t)c->shape.n_rows;
     for (int b = 0; b < 3; ++b) {
-        if (!c->obins[b]) {
+        if (with_bins && !c->obins[b]) {
             int rc = qgbdt::ws_alloc(c, &c->obins[b], N * c->shape.n_features);
             if (rc != QGBDT_OK) { c->obins[b] = nullptr; return rc; }
         }
@@ -286,6 +286,7 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
     RowSource rows;
+    rows.gh_pos = 0;  // the caller's packed gradients are in original row order
     IdxSet idx;
     for (int b = 0; b < 4; ++b) { rows.bins[b] = (const uint8_t*)bins; rows.gh[b] = gh; idx.p[b] = const_cast<int32_t*>(row_idx); }
     rc = launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
@@ -388,6 +389,12 @@ int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const floa
         return set_error(ctx, QGBDT_E_INVALID_ARG, "rounding=%d", p->rounding);
     if (p->acc_width != 0 && p->acc_width != 16 && p->acc_width != 32)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "acc_width=%d (0, 16 or 32)", p->acc_width);
+    if (p->row_layout < QGBDT_ROWS_AUTO || p->row_layout > QGBDT_ROWS_ORDERED)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "row_layout=%d (QGBDT_ROWS_*)", p->row_layout);
+    if (p->row_layout == QGBDT_ROWS_ORDERED && !ctx->ordered)
+        return set_error(ctx, QGBDT_E_UNSUPPORTED,
+                         "ordered rows need uint8 bins and 16..64 features that are a multiple of 4 (n_features=%d, bin_bytes=%d)",
+                         ctx->shape.n_features, ctx->shape.bin_bytes);
     if (((uintptr_t)bins & 3) != 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "bins must be 4-byte aligned");
     int rc = check_bits(ctx, p->bits_g, p->bits_h);
     if (rc != QGBDT_OK) return rc;

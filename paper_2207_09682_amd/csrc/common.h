@@ -124,11 +124,15 @@ struct ScanItem;
 // expanded); buffer 3 is the caller's data in original row order (bin matrix, quantized
 // gradients), where the root lives in ordered mode.  Row ids of buffer 3 use array 0.
 // In ordered mode (narrow rows) buffers 0..2 hold leaf-ordered copies of the bin rows and
-// packed gradients; otherwise all four entries point at the original arrays.
+// packed gradients.  Otherwise the bin rows are gathered from the original matrix by row id;
+// with `gh_pos` set the packed gradients still travel with the row ids (gh[b][p] belongs to
+// row idx[b][p]: 2 more bytes per moved row, and a gathered build reads them in sequence
+// instead of one more cache line per row), without it they are gathered from gh[BUF_ORIGINAL].
 constexpr int BUF_ORIGINAL = 3;
 struct RowSource {
     const uint8_t* bins[4];
     const int16_t* gh[4];
+    int32_t gh_pos;
 };
 struct RowDest {
     uint8_t* bins[3];
@@ -155,7 +159,7 @@ struct qgbdt_ctx {
     // workspace
     int ordered;           // narrow rows: children get physically leaf-ordered copies of their rows
     uint8_t* obins[3];     // [N][F] each (ordered mode)
-    int16_t* ogh[3];       // [N] each (ordered mode)
+    int16_t* ogh[3];       // [N] each: packed gradients in the order of idx[b] (allocated on first tree)
     int32_t* idx[3];       // [N] each
     uint8_t* bins_t;       // [F][N] feature-major copy of the bound bin matrix (qgbdt_bind_bins), else null
     uint16_t* mfb;         // [F] most frequent bin of each feature of the bound matrix when it holds most rows, else 0xffff
@@ -237,8 +241,8 @@ int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const ui
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
 int launch_frequent_bins(qgbdt_ctx* ctx, const void* bins_t, uint16_t* mfb);
 int launch_fix_frequent_bins(qgbdt_ctx* ctx, int64_t* hist, const int64_t* totals, const uint16_t* mfb);
-int ensure_ordered_buffers(qgbdt_ctx* ctx);
-int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);
+int ensure_ordered_buffers(qgbdt_ctx* ctx, bool with_bins);
+int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);  // !ordered: row ids and, with rows.gh_pos, packed gradients
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,
                  const int32_t* n_leaves_dev, double* value_out);

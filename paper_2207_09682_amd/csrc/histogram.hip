@@ -244,7 +244,8 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
         const uint8_t* colbase = src.bins[sb] + f0 + 4 * q - back;
-        const int16_t* gh = src.gh[sb];
+        const bool gpos = IDX && src.gh_pos != 0;  // packed gradients in list order
+        const int16_t* gh = gpos ? src.gh[en.buf] + en.begin : src.gh[sb];
 
         // a group without rows still hands over its (empty) bins
         for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         d[u] = load_bins4<RAG>(colbase + rows[u] * F);
-                        gv[u] = gh[rows[u]];
+                        gv[u] = gh[gpos ? cbegin + min(wave * S + u * rpi + r, crow - 1) : rows[u]];
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSour
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         dn[u] = load_bins4<RAG>(colbase + rown[u] * F);
-                        gn[u] = gh[rown[u]];
+                        gn[u] = gh[gpos ? cbegin + min(ro + n_waves * S + u * rpi + r, crow - 1) : rown[u]];
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {  // row ids two blocks ahead (clamped when past the end)
@@ -400,7 +401,8 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
         const uint8_t* colbase = src.bins[sb] + f0 + V * c;
-        const int16_t* gh = src.gh[sb];
+        const bool gpos = IDX && src.gh_pos != 0;  // packed gradients in list order
+        const int16_t* gh = gpos ? src.gh[en.buf] + en.begin : src.gh[sb];
 
         for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
@@ -424,7 +426,7 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         d[u] = *reinterpret_cast<const vec*>(colbase + rows[u] * F);
-                        gv[u] = gh[rows[u]];
+                        gv[u] = gh[gpos ? cbegin + min(wave * S + u * rpi + r, crow - 1) : rows[u]];
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -436,7 +438,7 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         dn[u] = *reinterpret_cast<const vec*>(colbase + rown[u] * F);
-                        gn[u] = gh[rown[u]];
+                        gn[u] = gh[gpos ? cbegin + min(ro + n_waves * S + u * rpi + r, crow - 1) : rown[u]];
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -660,13 +662,14 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
         unsigned char* slot = partials + ((size_t)item * plan.n_tiles + tile) * (size_t)plan.slot_bytes;
         const int32_t* idx = use_idx ? (idxs.p[en.buf] + en.begin) : nullptr;
         const BIN* bins = reinterpret_cast<const BIN*>(src.bins[use_idx ? BUF_ORIGINAL : en.buf]);
-        const int16_t* gh = src.gh[use_idx ? BUF_ORIGINAL : en.buf];
+        const bool gpos = use_idx && src.gh_pos != 0;
+        const int16_t* gh = gpos ? src.gh[en.buf] + en.begin : src.gh[use_idx ? BUF_ORIGINAL : en.buf];
         for (int64_t cbegin = gbegin; cbegin < gend || cbegin == gbegin; cbegin += plan.chunk_rows) {
             const int64_t cend = min(gend, cbegin + (int64_t)plan.chunk_rows);
             __syncthreads();
             for (int64_t p = cbegin + wave * rpi + r; p < cend; p += n_waves * rpi) {
                 const int64_t i = idx ? (int64_t)idx[p] : en.begin + p;
-                const word v = Acc<W>::expand(gh[i], hmul);
+                const word v = Acc<W>::expand(gh[gpos ? p : i], hmul);
                 const BIN* row = bins + i * F + f0;
                 for (int f = fl; f < ft; f += C) Acc<W>::add(&lds[(uint32_t)row[f] * ft + f], v);
             }

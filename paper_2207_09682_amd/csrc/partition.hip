@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, c
 // destinations follow from one round of ballots, and then (ORDERED) the bin rows move as
 // dwords, eight independent loads per thread in flight, coalesced on the reading side and in
 // two compacted streams on the writing side; the packed gradients move with the row ids.
-template <bool ORDERED>
+template <int MODE>  // 0: row ids, 1: row ids and packed gradients, 2: those and the bin rows (ordered mode)
 __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows, RowDest out, int F, IdxSet idxs,
                                                                  const StepState* __restrict__ step,
                                                                  const BatchEntry* __restrict__ batch,
@@ -254,10 +254,10 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
         const int cbuf = child_buffer(nd.buf);
         const int32_t* src = idxs.p[nd.buf] + nd.begin;
         int32_t* dst = idxs.p[cbuf] + nd.begin;
-        const int16_t* gsrc = ORDERED ? rows.gh[nd.buf] + nd.begin : nullptr;
-        int16_t* gdst = ORDERED ? out.gh[cbuf] + nd.begin : nullptr;
-        const uint8_t* bsrc = ORDERED ? rows.bins[nd.buf] + nd.begin * (int64_t)F : nullptr;
-        uint8_t* bdst = ORDERED ? out.bins[cbuf] + nd.begin * (int64_t)F : nullptr;
+        const int16_t* gsrc = MODE >= 1 ? rows.gh[nd.buf] + nd.begin : nullptr;
+        int16_t* gdst = MODE >= 1 ? out.gh[cbuf] + nd.begin : nullptr;
+        const uint8_t* bsrc = MODE == 2 ? rows.bins[nd.buf] + nd.begin * (int64_t)F : nullptr;
+        uint8_t* bdst = MODE == 2 ? out.bins[cbuf] + nd.begin * (int64_t)F : nullptr;
         const int64_t sbegin = (int64_t)(item - be.seg_start) * PART_SEG;
         const int64_t send = min(nd.count, sbegin + PART_SEG);
         const int n = (int)(send - sbegin);
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
             if (r < n) {
                 fl[u] = flags[nd.begin + sbegin + r];
                 v[u] = src[sbegin + r];
-                if (ORDERED) g16[u] = gsrc[sbegin + r];
+                if (MODE >= 1) g16[u] = gsrc[sbegin + r];
             }
         }
 #pragma unroll
@@ -293,10 +293,11 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
             const int64_t dp = fl[u] ? lpos0 + lw + rank[u] : rpos0 + (r - (lw + rank[u]));
             if (r < n) {
                 dst[dp] = v[u];
-                if (ORDERED) { gdst[dp] = (int16_t)g16[u]; s_dpos[r] = (int)dp; }
+                if (MODE >= 1) gdst[dp] = (int16_t)g16[u];
+                if (MODE == 2) s_dpos[r] = (int)dp;
             }
         }
-        if (ORDERED) {
+        if (MODE == 2) {
             __syncthreads();
             const uint32_t* s32 = reinterpret_cast<const uint32_t*>(bsrc + sbegin * (int64_t)F);
             const int n_dw = n * dpr;
@@ -346,14 +347,14 @@ int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const ui
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered) {
     RowDest out;
     for (int b = 0; b < 3; ++b) { out.bins[b] = ctx->obins[b]; out.gh[b] = ctx->ogh[b]; }
-    if (ordered)
-        hipLaunchKernelGGL(batch_part_scatter_kernel<true>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                           out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
-                           ctx->seg_prefix);
-    else
-        hipLaunchKernelGGL(batch_part_scatter_kernel<false>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows,
-                           out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,
-                           ctx->seg_prefix);
+#define QG_SCATTER(MODE_)                                                                                              \
+    hipLaunchKernelGGL(batch_part_scatter_kernel<MODE_>, dim3(batch_part_grid(ctx)), dim3(256), 0, ctx->stream, rows, \
+                       out, ctx->shape.n_features, idx_set(ctx), ctx->step, ctx->batch, ctx->nodes, ctx->flags,       \
+                       ctx->seg_prefix)
+    if (ordered) QG_SCATTER(2);
+    else if (rows.gh_pos) QG_SCATTER(1);
+    else QG_SCATTER(0);
+#undef QG_SCATTER
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

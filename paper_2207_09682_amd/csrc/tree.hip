@@ -534,8 +534,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     const HistPlan plan = make_hist_plan(ctx->shape, p->bits_g, p->bits_h, p->acc_width, false);
     const HistPlan root_plan = make_hist_plan_for(ctx->shape, p->bits_g, p->bits_h, p->acc_width, N, skip_ok);  // the root's build alone
     const uint16_t* mfb = skip_ok ? ctx->mfb : nullptr;
-    // Row sources: buffer 2 = the caller's matrix and the quantized gradients in original order;
-    // in ordered mode buffers 0/1 are the leaf-ordered copies that the partition writes.
+    // Row sources: buffer 3 = the caller's matrix and the quantized gradients in original order;
+    // buffers 0..2 are what the partition writes (see RowSource).
     RowSource rows;
     IdxSet idxs;
     // the feature-major copy serves only the matrix it was made from
@@ -544,18 +544,29 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // sector of the row-major matrix per row; with the feature-major copy the partition is cheap without
     // moving rows, and gathering the rows of the smaller children costs less than moving all rows
     // (10.5 M x 28: 3.58 against 3.97 ms per tree).
-    const bool ordered = ctx->ordered != 0 && !bins_t;
-    if (ordered) {
-        int rc0 = ensure_ordered_buffers(ctx);
+    // Without ordered rows the packed gradients still move with the row ids (2 bytes per moved row): a gathered
+    // build then reads them in sequence, which takes one of the ~2.2 cache lines per sparse narrow row away.
+    // A matrix that the caches hold gathers cheaply anyway and gains nothing from the move (1 M x 28: 1.15 to
+    // 1.21 against 1.16 ms per tree).
+    int layout = p->row_layout;
+    if (layout == QGBDT_ROWS_AUTO)
+        layout = (ctx->ordered != 0 && !bins_t) ? QGBDT_ROWS_ORDERED
+                 : ((int64_t)N * F * ctx->shape.bin_bytes >= (int64_t)128 << 20) ? QGBDT_ROWS_IDS_GH : QGBDT_ROWS_IDS;
+    const bool ordered = layout == QGBDT_ROWS_ORDERED;
+    const bool gh_lists = layout != QGBDT_ROWS_IDS;
+    if (gh_lists) {
+        int rc0 = ensure_ordered_buffers(ctx, ordered);
         if (rc0 != QGBDT_OK) return rc0;
     }
     for (int b = 0; b < 3; ++b) {
         rows.bins[b] = ordered ? ctx->obins[b] : bins;
-        rows.gh[b] = ordered ? ctx->ogh[b] : ctx->gh;
+        rows.gh[b] = gh_lists ? ctx->ogh[b] : ctx->gh;
         idxs.p[b] = ctx->idx[b];
     }
+    rows.gh_pos = (gh_lists && !ordered) ? 1 : 0;
     rows.bins[BUF_ORIGINAL] = bins; rows.gh[BUF_ORIGINAL] = ctx->gh; idxs.p[BUF_ORIGINAL] = ctx->idx[0];
-    const int root_buf = ordered ? BUF_ORIGINAL : 0;
+    // the root's rows are the original arrays under the identity list (array 0, which its great-grandchildren reuse)
+    const int root_buf = BUF_ORIGINAL;
 
     int blocks = (int)((N + 255) / 256);
     if (blocks > 2048) blocks = 2048;

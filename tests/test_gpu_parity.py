@@ -442,6 +442,10 @@ def test_errors_are_reported_not_crashes():
         ctx.build_histograms(bins, gh, begin=10, count=995)              # slice outside the rows
     with pytest.raises(QgbdtError):
         ctx.build_histograms(bins, gh, acc_width=8)
+    with pytest.raises(QgbdtError):
+        ctx.grow_tree(bins, g, g, 3, 3, 0, 0, 8, row_layout=4)           # no such layout
+    with pytest.raises(QgbdtError):
+        ctx.grow_tree(bins, g, g, 3, 3, 0, 0, 8, row_layout=3)           # ordered rows need 16..64 features
 
 
 # ----------------------------------------------------------------------------
@@ -712,6 +716,37 @@ def test_grow_tree_with_bound_bins(N, F, nb, L, bb):
     _compare_tree(ctx.grow_tree(dbins, dg, dh, 3, 3, 4, 0, L, min_data_in_leaf=5), e2, N)
 
 
+# Every choice of what a partition moves (row ids; row ids and packed gradients; those and the bin rows) grows the
+# oracle's tree, bound or not: shapes that reach each gathered histogram kernel (dword per lane with one and with
+# several tiles, ragged feature counts, 8- and 16-byte pieces of wide rows, 16-bit bins) and 64-bit local words.
+@pytest.mark.parametrize("N,F,nb,L,bb,bits", [(70000, 28, 255, 63, 1, (3, 3)), (40000, 64, 255, 31, 1, (3, 8)),
+                                              (30000, 30, 100, 31, 1, (3, 3)), (30000, 200, 255, 31, 1, (3, 8)),
+                                              (9000, 2000, 63, 15, 1, (3, 3)), (20000, 20, 600, 31, 2, (4, 4)),
+                                              (25000, 3, 16, 15, 1, (2, 2))])
+def test_row_layouts_grow_the_same_tree(N, F, nb, L, bb, bits):
+    from paper_2207_09682_amd import Context, ROWS_IDS, ROWS_IDS_GH, ROWS_ORDERED
+    rng = np.random.default_rng(N * 7 + F)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint16 if bb == 2 else np.uint8)
+    sig = (bins[:, F // 2].astype(np.float64) / nb - 0.5) * 4 + (bins[:, 0] > nb // 2) * 0.8
+    y = (rng.random(N) < 1 / (1 + np.exp(-sig))).astype(np.float32)
+    pr = 1 / (1 + np.exp(-rng.normal(scale=0.7, size=N)))
+    g = (pr - y).astype(np.float32); h = (pr * (1 - pr)).astype(np.float32)
+    e = oracle.grow_tree(bins, nb, g, h, bits[0], bits[1], 21, 0, L, min_data=5)
+    dbins = torch.from_numpy(bins).cuda()
+    dg, dh = torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda()
+    layouts = [ROWS_IDS, ROWS_IDS_GH] + ([ROWS_ORDERED] if (bb == 1 and F % 4 == 0 and 16 <= F <= 64) else [])
+    ctx = Context(N, F, nb, max_leaves=L, bin_bytes=bb)
+    for bound in (False, True):
+        if bound:
+            ctx.bind_bins(dbins)
+        for layout in layouts + layouts[:1]:                 # and back to the first one on the same context
+            t = ctx.grow_tree(dbins, dg, dh, bits[0], bits[1], 21, 0, L, min_data_in_leaf=5, row_layout=layout)
+            try:
+                _compare_tree(t, e, N)
+            except AssertionError as err:
+                raise AssertionError(f"bound={bound} layout={layout}: {err}") from err
+
+
 # ----------------------------------------------------------------------------
 # seeded sweep over valid configurations
 # ----------------------------------------------------------------------------
@@ -719,7 +754,7 @@ def test_grow_tree_with_bound_bins(N, F, nb, L, bb):
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_valid_configurations(seed):
     # 100 seeded draws per seed of (rows, features, bins, bin type, leaf budget, bit widths, accumulator setting,
-    # bound matrix or not, rounding, minimum rows per leaf): two trees each, every output against the oracle
+    # bound matrix or not, rounding, minimum rows per leaf, what moves in a partition): two trees each, every output against the oracle
     from paper_2207_09682_amd import Context
     rng = np.random.default_rng(seed)
     for case in range(100):
@@ -735,6 +770,8 @@ def test_random_valid_configurations(seed):
         bind = bool(rng.random() < 0.5)
         rounding = int(rng.random() < 0.2)
         md = int(rng.choice([0, 1, 5, 20]))
+        can_order = bb == 1 and F % 4 == 0 and 16 <= F <= 64
+        layout = int(rng.choice([0, 0, 1, 2, 3] if can_order else [0, 0, 1, 2]))
         bins = rng.integers(0, nb, (N, F)).astype(np.uint16 if bb == 2 else np.uint8)
         if rng.random() < 0.3:
             bins[:, 0] = np.where(rng.random(N) < 0.8, 0, bins[:, 0])
@@ -743,14 +780,15 @@ def test_random_valid_configurations(seed):
         pr = 1 / (1 + np.exp(-rng.normal(scale=0.5, size=N)))
         g = (pr - y).astype(np.float32)
         h = (pr * (1 - pr)).astype(np.float32) if bits[1] != 0 else np.full(N, 1.0, np.float32)
-        what = dict(case=case, N=N, F=F, nb=nb, bb=bb, L=L, bits=bits, acc=acc, bind=bind, rounding=rounding, md=md)
+        what = dict(case=case, N=N, F=F, nb=nb, bb=bb, L=L, bits=bits, acc=acc, bind=bind, rounding=rounding, md=md,
+                    layout=layout)
         ctx = Context(N, F, nb, max_leaves=L, bin_bytes=bb)
         dbins = torch.from_numpy(bins).cuda()
         if bind:
             ctx.bind_bins(dbins)
         for it in range(2):
             t = ctx.grow_tree(dbins, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), bits[0], bits[1], 77, it, L,
-                              min_data_in_leaf=md, acc_width=acc, rounding=rounding)
+                              min_data_in_leaf=md, acc_width=acc, rounding=rounding, row_layout=layout)
             e = oracle.grow_tree(bins, nb, g, h, bits[0], bits[1], 77, it, L, min_data=md, rounding=rounding)
             try:
                 _compare_tree(t, e, N)
