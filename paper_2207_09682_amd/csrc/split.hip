@@ -130,10 +130,11 @@ __global__ __launch_bounds__(1024) void scan_kernel(int64_t* hist_base, const Sc
     }
 }
 
-// The same search for histograms of at most 64 bins and many features.  A workgroup of 16
+// The same search for histograms of at most 64 * P bins (P = 1, 2, 4) and many features.  A workgroup of 16
 // wavefronts takes 16 consecutive features of an item: the [bin][16 features] tile (one 128-byte
 // line per bin) is read -- and, for a subtracted sibling, written back -- with coalesced accesses
-// and staged in LDS; wavefront w then scans feature w of the tile, lane = bin.
+// and staged in LDS; wavefront w then scans feature w of the tile, lane l the bins l, l + 64, ...
+template <int P>
 __global__ __launch_bounds__(1024) void scan_tile_kernel(int64_t* hist_base, const ScanItem* __restrict__ items,
                                                          const int32_t* __restrict__ n_items_ptr, int F, int nb,
                                                          const float* __restrict__ delta, int64_t min_data,
@@ -144,54 +145,75 @@ __global__ __launch_bounds__(1024) void scan_tile_kernel(int64_t* hist_base, con
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t W = (int64_t)F * nb;
     const double dg = (double)delta[0], dh = (double)delta[1];
-    __shared__ int64_t tile[64 * 17];  // [bin][feature], pitch 17 words: a wavefront's column walk spreads over the banks
-    const int tf = threadIdx.x & 15, tb = threadIdx.x >> 4;  // tile loader: feature and bin of this thread
+    __shared__ int64_t tile[64 * P * 17];  // [bin][feature], pitch 17 words: a wavefront's column walk spreads over the banks
+    const int tf = threadIdx.x & 15, tb = threadIdx.x >> 4;  // tile loader: feature and (first) bin of this thread
     for (int item = blockIdx.y; item < n_items; item += gridDim.y) {
         const ScanItem it = items[item];
         if (!it.valid) continue;
-        int64_t word = 0;
-        if (tb < nb && f0 + tf < F) {
-            const int64_t at = (int64_t)tb * F + f0 + tf;
-            if (it.sub_parent >= 0) {
-                word = hist_base[it.sub_parent * W + at] - hist_base[it.sub_child * W + at];
-                hist_base[it.slot * W + at] = word;
-            } else {
-                word = hist_base[it.slot * W + at];
+        int64_t word[P];
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const int b = tb + 64 * j;
+            word[j] = 0;
+            if (b < nb && f0 + tf < F) {
+                const int64_t at = (int64_t)b * F + f0 + tf;
+                if (it.sub_parent >= 0) word[j] = hist_base[it.sub_parent * W + at] - hist_base[it.sub_child * W + at];
+                else word[j] = hist_base[it.slot * W + at];
+            }
+        }
+        if (it.sub_parent >= 0) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                const int b = tb + 64 * j;
+                if (b < nb && f0 + tf < F) hist_base[it.slot * W + (int64_t)b * F + f0 + tf] = word[j];
             }
         }
         __syncthreads();  // the previous item's tile has been read
-        tile[tb * 17 + tf] = word;
+#pragma unroll
+        for (int j = 0; j < P; ++j) tile[(tb + 64 * j) * 17 + tf] = word[j];
         __syncthreads();
         const int f = f0 + wave;
         if (f >= F) continue;  // no barrier below depends on this wavefront
-        int64_t pre = tile[lane * 17 + wave];
-        for (int o = 1; o < 64; o <<= 1) {
-            const int64_t v = __shfl_up(pre, o);
-            if (lane >= o) pre += v;
+        int64_t pre[P];
+        int64_t carry = 0;
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            int64_t v = tile[(lane + 64 * j) * 17 + wave];
+            for (int o = 1; o < 64; o <<= 1) {
+                const int64_t u = __shfl_up(v, o);
+                if (lane >= o) v += u;
+            }
+            pre[j] = v + carry;
+            carry = __shfl(pre[j], 63);
         }
         if (mfb != nullptr) {  // the feature's most frequent bin may have been left out (see scan_kernel)
             const int mb = mfb[f];
-            const int64_t all = __shfl(pre, 63);
-            const int64_t missing = (it.stat.sum_g * 4294967296LL + it.stat.sum_h) - all;
-            if (mb != 0xffff && lane >= mb) pre += missing;
+            const int64_t missing = (it.stat.sum_g * 4294967296LL + it.stat.sum_h) - carry;
+#pragma unroll
+            for (int j = 0; j < P; ++j)
+                if (mb != 0xffff && lane + 64 * j >= mb) pre[j] += missing;
         }
         const int64_t Gs = it.stat.sum_g, Hs = it.stat.sum_h, n = it.stat.n_rows;
         double gain = 0.0;
         int bin = -1;
-        if (lane + 1 < nb && Hs > 0) {
-            const int64_t GL = packed_g(pre), HL = packed_h(pre);
-            const int64_t GR = Gs - GL, HR = Hs - HL;
-            if (HL > 0 && HR > 0) {
-                const int64_t cl = count_estimate(HL, Hs, n), cr = n - cl;
-                if (cl >= min_data && cr >= min_data && !((double)HL * dh < min_sum_hess) &&
-                    !((double)HR * dh < min_sum_hess)) {
-                    const double parent = half_loss(Gs, Hs, dg, dh);
-                    const double gn = half_loss(GL, HL, dg, dh) + half_loss(GR, HR, dg, dh) - parent;
-                    if (gn > 0.0) { gain = gn; bin = lane; }
+        int64_t left = 0;
+#pragma unroll
+        for (int j = 0; j < P; ++j) {  // ascending bins: strict > keeps the lowest
+            const int b = lane + 64 * j;
+            if (b + 1 < nb && Hs > 0) {
+                const int64_t GL = packed_g(pre[j]), HL = packed_h(pre[j]);
+                const int64_t GR = Gs - GL, HR = Hs - HL;
+                if (HL > 0 && HR > 0) {
+                    const int64_t cl = count_estimate(HL, Hs, n), cr = n - cl;
+                    if (cl >= min_data && cr >= min_data && !((double)HL * dh < min_sum_hess) &&
+                        !((double)HR * dh < min_sum_hess)) {
+                        const double parent = half_loss(Gs, Hs, dg, dh);
+                        const double gn = half_loss(GL, HL, dg, dh) + half_loss(GR, HR, dg, dh) - parent;
+                        if (gn > 0.0 && gn > gain) { gain = gn; bin = b; left = pre[j]; }
+                    }
                 }
             }
         }
-        int64_t left = pre;
         for (int o = 32; o > 0; o >>= 1) {  // arg-max: largest gain, ties to the lowest bin
             const double og = __shfl_xor(gain, o);
             const int ob = __shfl_xor(bin, o);
@@ -277,14 +299,19 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
     if (gy < 1) gy = 1;
     int glog = 0;  // features per XCD group: 16 (one 128-byte line) when F >= 128, fewer for narrow matrices
     while (glog < 4 && (16 << glog) <= F) ++glog;
-    if (nb <= 64 && F >= 64) {
+    if (nb <= 256 && F >= 64) {
         const int gx = (F + 15) / 16;
         gy = 2048 / gx;
         if (gy < 2) gy = 2;
         if (gy > max_items) gy = max_items;
         if (gy < 1) gy = 1;
-        hipLaunchKernelGGL(scan_tile_kernel, dim3(gx, gy), dim3(1024), 0, ctx->stream, hist_base, items, n_items, F, nb,
-                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, mfb);
+#define QG_SCAN_TILE(P_)                                                                                          \
+    hipLaunchKernelGGL(scan_tile_kernel<P_>, dim3(gx, gy), dim3(1024), 0, ctx->stream, hist_base, items, n_items, \
+                       F, nb, delta, (int64_t)min_data, min_sum_hess, ctx->cand, mfb)
+        if (nb <= 64) QG_SCAN_TILE(1);
+        else if (nb <= 128) QG_SCAN_TILE(2);
+        else QG_SCAN_TILE(4);
+#undef QG_SCAN_TILE
     } else {
         const int per = 8 << glog;
         const int gx = (F + per - 1) / per * per;
