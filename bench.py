@@ -189,6 +189,12 @@ def main():
     # ---- root pass alone (contiguous rows): the kernel at its full-size launch -----------------
     root = root_pass(ctx, torch, bins, gs[W], hs[W], bits_g, bits_h, cfg, args, W, N, F, nb)
 
+    # ---- measured streaming-read ceiling of this machine: a plain 16-byte-load kernel over 1 GiB ------
+    probe = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    stream_read_gbps = ctx.measure_stream_read(probe, reps=10)
+    del probe
+    root["frac_of_measured_stream_read"] = root["achieved_GBps"] / stream_read_gbps if stream_read_gbps > 0 else None
+
     # ---- CPU oracle on the same inputs -----------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -253,7 +259,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "histogram build = hist_*_kernel + hist_reduce_kernel (all launches of the timed trees)",
                      "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
-                     "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1)},
+                     "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1),
+                     "measured_stream_read_GBps": stream_read_gbps},
         "root_pass": root,
         "hist_time_share": hist_ms / (elapsed * 1e3),
         "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,

@@ -283,6 +283,13 @@ QGBDT_API int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_
  * splits, nodes created.  For callers that time or tune; no paper quantity. */
 QGBDT_API int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4);
 
+/* Streaming-read rate of this device as a plain kernel reaches it: `buf` (dev, 16-byte aligned, `bytes` a
+ * multiple of 16, at least 16) is read `reps` times with 16-byte loads by one grid-stride kernel per repetition,
+ * timed with HIP events on the context's stream after one untimed repetition.  gbps_out (host) = bytes * reps
+ * / time in GB/s.  Synchronous.  The measured ceiling that the histogram kernels' rates are set against beside
+ * the published peak; no paper quantity. */
+QGBDT_API int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,7 @@ EXPORTS = [
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_boost_iteration_lambdarank",
     "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats", "qgbdt_bind_bins",
+    "qgbdt_measure_stream_read",
 ]
 
 
@@ -92,6 +93,7 @@ def load_library() -> C.CDLL:
         lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         lib.qgbdt_tree_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         lib.qgbdt_bind_bins.argtypes = [C.c_void_p, C.c_void_p]
+        lib.qgbdt_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
         _lib = lib
     return _lib
 
@@ -334,6 +336,20 @@ class Context:
         ms = C.c_double(0); n = C.c_int64(0); b = C.c_double(0)
         self._chk(self.lib.qgbdt_read_profile(self._h, C.byref(ms), C.byref(n), C.byref(b)))
         return ms.value, n.value, b.value
+
+
+def _measure_stream_read(self, buf: torch.Tensor, reps: int = 10) -> float:
+    """GB/s a plain 16-byte-load kernel reaches reading `buf` (device tensor) `reps` times."""
+    self._sync_stream()
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise ValueError("buf must be a contiguous device tensor")
+    nbytes = buf.numel() * buf.element_size() // 16 * 16
+    out = C.c_double(0)
+    self._chk(self.lib.qgbdt_measure_stream_read(self._h, C.c_void_p(buf.data_ptr()), C.c_int64(nbytes), int(reps), C.byref(out)))
+    return out.value
+
+
+Context.measure_stream_read = _measure_stream_read
 
 
 def _tree_stats(self):

@@ -123,6 +123,27 @@ static int check_bits(qgbdt_ctx* ctx, int bits_g, int bits_h) {
 
 using namespace qgbdt;
 
+namespace qgbdt {
+
+// Plain streaming read: four 16-byte loads per thread and step; the loaded values are folded into a word that is
+// stored only if it takes one particular value, which keeps the loads alive.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, int64_t n16, uint32_t* sink) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0u;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = p[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9e3779b9u) *sink = acc;
+}
+
+}  // namespace qgbdt
+
 extern "C" {
 
 int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
@@ -496,6 +517,35 @@ int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches, 
     ctx->ev_used = 0;
     st.prof_rows_contig = 0; st.prof_rows_idx = 0; st.prof_launches = 0; st.prof_builds = 0;
     QG_HIP(ctx, hipMemcpy(ctx->step, &st, sizeof(st), hipMemcpyHostToDevice));
+    return QGBDT_OK;
+}
+
+int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!buf || !gbps_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (((uintptr_t)buf & 15) != 0 || bytes < 16 || (bytes & 15) != 0 || reps < 1)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "buf must be 16-byte aligned, bytes a positive multiple of 16, reps >= 1");
+    const int64_t n16 = bytes / 16;
+    int64_t blocks = (n16 + 4 * 256 - 1) / (4 * 256);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipEvent_t e0, e1;
+    QG_HIP(ctx, hipEventCreate(&e0));
+    QG_HIP(ctx, hipEventCreate(&e1));
+    uint32_t* sink = reinterpret_cast<uint32_t*>(ctx->tmp_i64 + 7);
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const uint4*)buf, n16, sink);
+    hipError_t e = hipEventRecord(e0, ctx->stream);
+    for (int r = 0; r < reps && e == hipSuccess; ++r)
+        hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const uint4*)buf, n16, sink);
+    if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipGetLastError();
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return set_error(ctx, QGBDT_E_HIP, "stream read measurement failed: %s", hipGetErrorString(e));
+    *gbps_out = ms > 0.0f ? (double)bytes * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
     return QGBDT_OK;
 }
 

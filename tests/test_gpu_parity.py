@@ -576,6 +576,17 @@ def test_create_rejects_leaf_budgets_beyond_the_bookkeeping():
     assert ctx.workspace_bytes > 0
 
 
+def test_measured_stream_read_is_plausible():
+    from paper_2207_09682_amd import QgbdtError
+    ctx = _ctx(1000, 8, 32, L=8)
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    gbps = ctx.measure_stream_read(buf, reps=5)
+    assert 200.0 < gbps < 40000.0                                  # 64 MiB may be served by the on-die caches
+    assert ctx.measure_stream_read(buf[:16], reps=1) > 0.0
+    with pytest.raises(QgbdtError):
+        ctx.measure_stream_read(buf[8:8 + 64], reps=1)              # not 16-byte aligned
+
+
 def test_tree_stats_after_a_tree():
     cfg = workloads.CONFIGS[0]
     wl = workloads.make_workload(cfg)
