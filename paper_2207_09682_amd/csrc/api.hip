@@ -1,6 +1,7 @@
 // C-ABI entry points of libqgbdt: argument checks, context and workspace
 // management, and the stand-alone forms of the steps (the kernels themselves live
 // next to their launchers).
+#include <algorithm>
 #include <stdarg.h>
 #include <string.h>
 
@@ -312,7 +313,8 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     for (int b = 0; b < 4; ++b) { rows.bins[b] = (const uint8_t*)bins; rows.gh[b] = gh; idx.p[b] = const_cast<int32_t*>(row_idx); }
     rc = launch_hist(ctx, plan, rows, idx, row_idx != nullptr, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, hist_out,
-                     (count + plan.min_rows_per_group - 1) / plan.min_rows_per_group, ctx->step, mfb);
+                     (count + hist_target_rows(plan, count, 1) - 1) / hist_target_rows(plan, count, 1),  // the build's row groups
+                     ctx->step, mfb);
     if (rc != QGBDT_OK || !mfb) return rc;
     hipLaunchKernelGGL(zero3_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->tmp_i64);
     hipLaunchKernelGGL(gh_totals_kernel, dim3(1024), dim3(256), 0, ctx->stream, gh, row_idx, begin, count, ctx->tmp_i64);

@@ -87,7 +87,8 @@ struct HistPlan {
     int32_t threads;     // workgroup size
     int32_t lds_bytes;
     int32_t chunk_rows;  // rows accumulated between two merges of the local bins
-    int32_t max_groups;  // workgroups along the row axis
+    int32_t max_groups;  // row groups of one build: all its workgroups are resident at once
+    int32_t max_lanes;   // workgroups along the row axis of a launch with many builds (a multiple of 8)
     int32_t min_rows_per_group;
     int32_t acc_width;   // 16: packed 32-bit words in LDS (g~ sums above hshift, h~ sums below), 32: packed 32|32 words
     int32_t hshift;      // bits of the hessian field of a 32-bit local word: 16, or the split that takes more rows

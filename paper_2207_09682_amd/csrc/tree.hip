@@ -22,6 +22,8 @@
 //
 // The host enqueues whole rounds without reading anything back; after the expected
 // number of rounds it reads one status word to learn whether more are needed.
+#include <algorithm>
+
 #include "split_device.h"
 
 namespace qgbdt {
@@ -575,7 +577,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                        ctx->hist_pool, W, root_plan);
     rc = launch_hist(ctx, root_plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
-                     (N + root_plan.min_rows_per_group - 1) / root_plan.min_rows_per_group, ctx->step, mfb);
+                     (N + hist_target_rows(root_plan, N, 1) - 1) / hist_target_rows(root_plan, N, 1),  // the build's row groups
+                     ctx->step, mfb);
     if (rc != QGBDT_OK) return rc;
     rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 1, ctx->delta,
                            p->min_data_in_leaf, p->min_sum_hessian, mfb);
@@ -606,7 +609,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
             rc = launch_batch_partition_scatter(ctx, rows, ordered);
             if (rc != QGBDT_OK) return rc;
             rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
-                             ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step, mfb);
+                             ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
             if (rc != QGBDT_OK) return rc;
             rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
                                    ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, mfb);
@@ -631,7 +634,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         rc = launch_batch_partition_scatter(ctx, rows, ordered);
         if (rc != QGBDT_OK) return rc;
         rc = launch_hist(ctx, plan, rows, idxs, !ordered, ordered, ctx->hist_entries,
-                         ctx->hist_counts, ctx->hist_pool, plan.max_groups, ctx->step, mfb);
+                         ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
         if (rc != QGBDT_OK) return rc;
         rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
                                ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, mfb);
