@@ -253,7 +253,7 @@ def main():
                    "hist_units_per_tree": total_units / K,
                    "bins_bound": bind_ms is not None, "bind_ms_once": bind_ms,
                    "rows": ("in place: row ids (and, for matrices beyond the caches, the packed gradients) move, the bin rows of the "
-                            "smaller children are gathered (the faster of the two layouts for whole trees; see DESIGN.md 7)") if (bind_ms is not None or F > 64 or F % 4 or F < 16)
+                            "smaller children are gathered (the faster of the two layouts for whole trees)") if (bind_ms is not None or F > 64 or F % 4 or F < 16)
                            else "kept in leaf order: every level moves the rows, builds stream contiguous memory"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
