@@ -260,7 +260,10 @@ def main():
                      "kernel": "histogram build = hist_*_kernel + hist_reduce_kernel (all launches of the timed trees)",
                      "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
                      "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1),
-                     "measured_stream_read_GBps": stream_read_gbps},
+                     "measured_stream_read_GBps": stream_read_gbps,
+                     # rate of the bytes that actually cross the HBM interface (counter runs): what the gathered
+                     # builds are bound by -- a 128-byte line per sparse 28-byte row
+                     "traffic_GBps": (traffic / (hist_ms / hist_launches * 1e-3) / 1e9) if (traffic and hist_launches and hist_ms > 0) else None},
         "root_pass": root,
         "hist_time_share": hist_ms / (elapsed * 1e3),
         "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,
