@@ -162,7 +162,8 @@ def test_subtract_bit_exact():
 # split search
 # ----------------------------------------------------------------------------
 
-@pytest.mark.parametrize("F,nb", [(28, 255), (28, 63), (200, 255), (2000, 63), (5, 16), (3, 256), (70, 33), (300, 64)])
+@pytest.mark.parametrize("F,nb", [(28, 255), (28, 63), (200, 255), (2000, 63), (5, 16), (3, 256), (70, 33), (300, 64),
+                                  (70, 65), (90, 100), (130, 129), (64, 256)])   # tile search with 2 and 4 bins per lane
 def test_find_best_splits_matches_oracle(F, nb):
     from paper_2207_09682_amd import unpack_splits
     rng = np.random.default_rng(F * nb)
