@@ -34,12 +34,7 @@ namespace qgbdt {
 // Workgroup size of the histogram kernels, and the wavefronts per SIMD their register
 // budgets are sized for (second launch-bound: 4 -> at most 128 VGPRs, 8 -> at most 64).
 constexpr int HIST_THREADS = 512;
-#ifndef QG_HK_WAVES
-#define QG_HK_WAVES 4
-#endif
-#ifndef QG_HF_WAVES
-#define QG_HF_WAVES 4
-#endif
+constexpr int HIST_WAVES = 4;
 
 __global__ void fill_zero_kernel(int64_t* p, int64_t n) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -188,7 +183,7 @@ __device__ __forceinline__ uint32_t load_bins4(const uint8_t* p) {
 }
 
 template <int W, bool IDX, int U, bool RAG>
-__global__ __launch_bounds__(HIST_THREADS, QG_HK_WAVES) void hist_kernel(RowSource src, IdxSet idxs,
+__global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
                                                     unsigned char* partials, int F, int nb, HistPlan plan,
@@ -486,7 +481,7 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 // whole kernel; they lie in at most two consecutive rows.  Blocks of U iterations
 // are software-pipelined like in hist_kernel.
 template <int W, int U>
-__global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(RowSource src,
+__global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(RowSource src,
                                                          const HistEntry* __restrict__ entries,
                                                          const int32_t* __restrict__ table_counts,
                                                          int64_t* hist_base, unsigned char* partials, int F, int nb,
@@ -530,10 +525,11 @@ __global__ __launch_bounds__(HIST_THREADS, QG_HF_WAVES) void hist_flat_kernel(Ro
             fl4[i][k] = (uint32_t)(col + c) * (uint32_t)sizeof(word);
         }
     }
-    const int chunk = plan.chunk_rows / BR * BR > 0 ? plan.chunk_rows / BR * BR : BR;
     const int dpr = F / 4;
-
     const int align_rows = 16 / ((F % 16 == 0) ? 16 : (F % 8 == 0) ? 8 : 4);  // rows after which a row start is 16-byte aligned again
+    // rows per chunk: whole blocks, and room for the unaligned head rows (fewer than align_rows) that the
+    // first chunk of a build's first group takes on top, so that no local word sees more than chunk_rows rows
+    const int chunk = (plan.chunk_rows - (align_rows - 1)) / BR * BR > 0 ? (plan.chunk_rows - (align_rows - 1)) / BR * BR : BR;
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
@@ -910,6 +906,33 @@ int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, i
     return QGBDT_OK;
 }
 
+// The wide-row kernels may be given more local bins than the default limit of dynamic LDS (the 64-feature tiles
+// of 64-bit words that frequent-bin skipping makes worthwhile): the runtime is told so once per context.
+template <int W, bool IDX, int V, bool S>
+static hipError_t allow_lds(int bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(hist_wide_kernel<W, IDX, V, 4, S>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+int prepare_hist_kernels(qgbdt_ctx* ctx) {
+    int most = 0;
+    for (int w = 16; w <= 32; w += 16)
+        for (int skew = 0; skew < 2; ++skew) {
+            const HistPlan hp = make_hist_plan(ctx->shape, 2, 2, w, skew != 0);
+            if (hp.wide_v > 0 && hp.lds_bytes > most) most = hp.lds_bytes;
+        }
+    if (most <= 64 * 1024) return QGBDT_OK;
+    QG_HIP(ctx, (allow_lds<16, false, 16, false>(most)));  QG_HIP(ctx, (allow_lds<16, false, 16, true>(most)));
+    QG_HIP(ctx, (allow_lds<16, true, 16, false>(most)));   QG_HIP(ctx, (allow_lds<16, true, 16, true>(most)));
+    QG_HIP(ctx, (allow_lds<16, false, 8, false>(most)));   QG_HIP(ctx, (allow_lds<16, false, 8, true>(most)));
+    QG_HIP(ctx, (allow_lds<16, true, 8, false>(most)));    QG_HIP(ctx, (allow_lds<16, true, 8, true>(most)));
+    QG_HIP(ctx, (allow_lds<32, false, 16, false>(most)));  QG_HIP(ctx, (allow_lds<32, false, 16, true>(most)));
+    QG_HIP(ctx, (allow_lds<32, true, 16, false>(most)));   QG_HIP(ctx, (allow_lds<32, true, 16, true>(most)));
+    QG_HIP(ctx, (allow_lds<32, false, 8, false>(most)));   QG_HIP(ctx, (allow_lds<32, false, 8, true>(most)));
+    QG_HIP(ctx, (allow_lds<32, true, 8, false>(most)));    QG_HIP(ctx, (allow_lds<32, true, 8, true>(most)));
+    return QGBDT_OK;
+}
+
 // Launches the kernel variant for (plan, row source).  `grid_items` is the host's upper bound on
 // the number of work items; workgroups beyond the table's item count return at once.
 int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,
@@ -917,6 +940,16 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
                 int64_t grid_items, StepState* step, const uint16_t* mfb) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     unsigned char* partials = static_cast<unsigned char*>(ctx->hist_partials);
+    // The kernels address slot (item, tile) for item < max_items of the plan they are given (the tables they read
+    // are built from the same plan and never hold more items): that range must lie inside the workspace's section,
+    // and the flat grid must cut into whole XCD groups of row-group lanes.
+    if ((size_t)plan.max_items * (size_t)plan.n_tiles * (size_t)plan.slot_bytes > ctx->hist_partials_bytes)
+        return set_error(ctx, QGBDT_E_WORKSPACE,
+                         "histogram plan needs %zu bytes of row-group slots (%d items x %d tiles x %d bytes), the workspace holds %zu",
+                         (size_t)plan.max_items * plan.n_tiles * plan.slot_bytes, plan.max_items, plan.n_tiles,
+                         plan.slot_bytes, ctx->hist_partials_bytes);
+    if (plan.max_lanes % 8 != 0 || plan.max_lanes < 8 || plan.lds_bytes > 160 * 1024)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "inconsistent histogram plan (lanes %d, local bins %d bytes)", plan.max_lanes, plan.lds_bytes);
     int64_t groups = grid_items;
     if (groups > plan.max_lanes) groups = plan.max_lanes;
     if (groups < 1) groups = 1;
@@ -926,6 +959,8 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     const bool fast = !plan.bytewise;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (ctx->profiling && ctx->ev_used + 2 <= ctx->ev_cap) {
+        for (int k = 0; k < 2; ++k)
+            if (!ctx->ev[ctx->ev_used + k]) QG_HIP(ctx, hipEventCreate(&ctx->ev[ctx->ev_used + k]));
         e0 = ctx->ev[ctx->ev_used++]; e1 = ctx->ev[ctx->ev_used++];
         QG_HIP(ctx, hipEventRecord(e0, ctx->stream));
     }
@@ -949,9 +984,6 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     } else if (fast && plan.wide_v > 0 && wide_ok) {
 #define QG_LAUNCH_WIDE_S(W_, IDX_, V_, U_, S_)                                                                        \
     do {                                                                                                              \
-        if (plan.lds_bytes > 64 * 1024)                                                                               \
-            QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(hist_wide_kernel<W_, IDX_, V_, U_, S_>),    \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, plan.lds_bytes));             \
         hipLaunchKernelGGL((hist_wide_kernel<W_, IDX_, V_, U_, S_>), grid, block, plan.lds_bytes, ctx->stream, rows,  \
                            idx, entries, table_counts, hist_base, partials, F, nb, plan, step, mfb);                  \
     } while (0)
