@@ -45,17 +45,26 @@ extern "C" {
 #define QGBDT_E_OVERFLOW_RISK (-3)
 #define QGBDT_E_HIP (-4)
 #define QGBDT_E_ALLOC (-5)
+#define QGBDT_E_WORKSPACE (-6) /* no workspace set, the block is too small, or it lacks the section a call needs */
+
+/* Optional sections of the workspace (qgbdt_workspace_bytes / qgbdt_set_workspace). */
+#define QGBDT_WS_BIND 1u       /* feature-major copy of a bound matrix: qgbdt_bind_bins (n_rows * n_features * bin_bytes) */
+#define QGBDT_WS_ROW_COPIES 2u /* three leaf-ordered copies of the bin rows: row_layout QGBDT_ROWS_ORDERED, and what
+                                  QGBDT_ROWS_AUTO takes for an unbound matrix of 16..64 uint8 features (a multiple of 4);
+                                  ignored for other shapes (3 * n_rows * n_features) */
+#define QGBDT_WS_BOOST 4u      /* loss derivatives of qgbdt_boost_iteration* (2 * 4 bytes per row) */
 
 #define QGBDT_ROUND_STOCHASTIC 0 /* SR of Sec. 4.2 */
 #define QGBDT_ROUND_NEAREST 1    /* RN of Sec. 4.2 (half rounds up) */
 
 /* What moves when a leaf's rows are partitioned (results are identical for all of them). */
-#define QGBDT_ROWS_AUTO 0    /* ordered copies for an unbound matrix whose shape allows them, else row ids, with the
-                                packed gradients when the matrix is 128 MB or more */
+#define QGBDT_ROWS_AUTO 0    /* ordered copies for an unbound matrix when the workspace holds them (QGBDT_WS_ROW_COPIES),
+                                else row ids, with the packed gradients when the matrix is 128 MB or more */
 #define QGBDT_ROWS_IDS 1     /* row ids only; histogram builds gather bin rows and packed gradients */
 #define QGBDT_ROWS_IDS_GH 2  /* row ids and packed gradients; histogram builds gather the bin rows */
 #define QGBDT_ROWS_ORDERED 3 /* row ids, packed gradients and bin rows: every build reads contiguous memory
-                                (uint8 bins, 16..64 features that are a multiple of 4; else QGBDT_E_UNSUPPORTED) */
+                                (uint8 bins, 16..64 features that are a multiple of 4, else QGBDT_E_UNSUPPORTED;
+                                needs QGBDT_WS_ROW_COPIES) */
 
 typedef struct qgbdt_ctx qgbdt_ctx;
 
@@ -123,26 +132,36 @@ typedef struct {
 
 /* ---- lifecycle ---------------------------------------------------------- */
 
-/* Creates a context for `shape` on the current device and allocates its workspace
- * (three row-index buffers, quantized gradients, a pool of histograms, small
- * descriptors).  Three copies of the packed gradients that follow the row-index buffers
- * (2 bytes per row each) and, for 16..64 features that are a multiple of 4 when the matrix
- * is not bound, three leaf-ordered copies of the bin rows, the feature-major copy of a
- * bound matrix and the derivative buffers of qgbdt_boost_iteration are allocated by the
- * first call that needs them.  `stream` is a hipStream_t (NULL = default stream).  Synchronous. */
+/* Device memory: the caller owns all of it.  The library allocates no device memory anywhere; it owns only the
+ * host-side context (and a few bytes of pinned host memory for the status word grow_tree reads back).
+ *
+ * qgbdt_workspace_bytes: bytes of device workspace a context of `shape` needs (host out), from the shape alone:
+ * three row-index buffers and three lists of packed gradients that follow them, the quantized gradients, a pool of
+ * 3 * max_leaves + 1 histograms, the slots of the histogram kernels' row groups, partition flags and small
+ * descriptors, plus the optional sections named by `flags` (QGBDT_WS_*).
+ *
+ * qgbdt_create: a context for `shape` on the current device; `stream` is a hipStream_t (NULL = default stream).
+ * Allocates no device memory; tells the runtime once which kernels need more than the default dynamic LDS.
+ *
+ * qgbdt_set_workspace: hands the context a block `dev` (device memory, 256-byte aligned, at least
+ * qgbdt_workspace_bytes(shape, flags) bytes; QGBDT_E_WORKSPACE if smaller) that it carves all its buffers from.
+ * The block stays the caller's: it must live until the context is destroyed or given another block, and nothing
+ * else may write it meanwhile.  Synchronises the stream (earlier work may use the previous block), then enqueues
+ * a few bytes of initialisation.  A bound matrix is forgotten.  dev = NULL detaches the block.  Every step
+ * returns QGBDT_E_WORKSPACE while no block is set, or when it needs an optional section the block was set without. */
+QGBDT_API int qgbdt_workspace_bytes(const qgbdt_shape* shape, uint32_t flags, size_t* bytes);
 QGBDT_API int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream);
-/* Frees the workspace and the context.  Synchronises the stream first. */
+QGBDT_API int qgbdt_set_workspace(qgbdt_ctx* ctx, void* dev, size_t bytes, uint32_t flags);
+/* Frees the context (never the workspace).  Synchronises the stream first. */
 QGBDT_API int qgbdt_destroy(qgbdt_ctx* ctx);
 /* Changes the stream later calls enqueue on. */
 QGBDT_API int qgbdt_set_stream(qgbdt_ctx* ctx, void* stream);
-/* Message of the last error on this context (or of a failed create when ctx is NULL). */
+/* Message of the last error on this context (or of a failed create / workspace_bytes when ctx is NULL). */
 QGBDT_API const char* qgbdt_last_error(const qgbdt_ctx* ctx);
-/* Bytes of device workspace the context holds (host out). */
-QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
 
 /* Optional.  Declares that `bins` (dev) is the matrix of the grow_tree / boost_iteration calls that follow,
  * as it is for all trees of a boosting run, and makes a feature-major copy of it on the stream
- * (n_rows * n_features * bin_bytes more workspace, allocated at the first call).  The counting pass of
+ * (in the QGBDT_WS_BIND section of the workspace; QGBDT_E_WORKSPACE without it).  The counting pass of
  * the row partition then reads the split feature's column -- the ascending row ids of a node fall into
  * few memory sectors -- instead of one sector of the row-major matrix per row, and narrow matrices, whose
  * rows are otherwise moved into leaf order level by level, are left in place.  The call also samples the
@@ -150,7 +169,7 @@ QGBDT_API int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes);
  * the wide-row histogram kernels leave that bin out and the entry is rebuilt from the totals.  Results do not
  * change.
  * Call again after the matrix' contents change; a grow_tree call with another pointer simply does not
- * use the copy; bins = NULL frees it (synchronises the stream first). */
+ * use the copy; bins = NULL forgets the matrix. */
 QGBDT_API int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins);
 
 /* ---- steps of the path ---------------------------------------------------- */
@@ -255,8 +274,8 @@ QGBDT_API int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* r
 /* One boosting iteration for the binary cross-entropy loss without any host arithmetic:
  * loss derivatives of `score`, one tree (qgbdt_grow_tree with these derivatives), score
  * update with learning_rate times the refit leaf values.  label: dev float[n_rows] (0 / 1);
- * score: dev float[n_rows], updated in place; the rest as in qgbdt_grow_tree.  The library
- * keeps the derivatives in its workspace (2 x 4 bytes per row, allocated at the first call). */
+ * score: dev float[n_rows], updated in place; the rest as in qgbdt_grow_tree.  The derivatives
+ * live in the QGBDT_WS_BOOST section of the workspace (QGBDT_E_WORKSPACE without it). */
 QGBDT_API int qgbdt_boost_iteration(qgbdt_ctx* ctx, const void* bins, const float* label, float* score,
                           const qgbdt_params* params, uint32_t iteration, double learning_rate,
                           const qgbdt_tree* tree_out, int32_t* row_idx_out);

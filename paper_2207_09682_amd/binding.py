@@ -19,9 +19,12 @@ LIB_PATH = os.path.join(_PKG, "libqgbdt.so")
 ROUND_STOCHASTIC = 0
 ROUND_NEAREST = 1
 ROWS_AUTO, ROWS_IDS, ROWS_IDS_GH, ROWS_ORDERED = 0, 1, 2, 3
+WS_BIND, WS_ROW_COPIES, WS_BOOST = 1, 2, 4
+E_WORKSPACE = -6
 
 EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
+    "qgbdt_set_workspace",
     "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
     "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
@@ -65,7 +68,8 @@ def load_library() -> C.CDLL:
         lib.qgbdt_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Shape), C.c_void_p]
         lib.qgbdt_destroy.argtypes = [C.c_void_p]
         lib.qgbdt_set_stream.argtypes = [C.c_void_p, C.c_void_p]
-        lib.qgbdt_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+        lib.qgbdt_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_uint32, C.POINTER(C.c_size_t)]
+        lib.qgbdt_set_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_uint32]
         lib.qgbdt_quantize_gradients.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                                  C.c_uint64, C.c_uint32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.qgbdt_build_histograms.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
@@ -142,10 +146,13 @@ class Tree:
 
 
 class Context:
-    """One qgbdt context: a problem shape, its device workspace and a stream."""
+    """One qgbdt context: a problem shape, its device workspace (one torch tensor, owned here) and a stream.
+
+    `workspace_flags` names the optional sections of the workspace (WS_BIND: bind_bins, WS_ROW_COPIES: leaf-ordered
+    copies of narrow rows, WS_BOOST: boost_iteration); the default asks for all of them."""
 
     def __init__(self, n_rows: int, n_features: int, n_bins: int, max_leaves: int = 255, bin_bytes: int = 1,
-                 device: str | torch.device = "cuda:0"):
+                 device: str | torch.device = "cuda:0", workspace_flags: int = WS_BIND | WS_ROW_COPIES | WS_BOOST):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the qgbdt library runs on MI355X only (no CPU path)")
         self.lib = load_library()
@@ -157,10 +164,37 @@ class Context:
             rc = self.lib.qgbdt_create(C.byref(self._h), C.byref(self.shape), C.c_void_p(stream))
         if rc != 0:
             raise QgbdtError(rc, self.lib.qgbdt_last_error(None).decode())
+        self.workspace = None
+        self.set_workspace(flags=workspace_flags)
+
+    @staticmethod
+    def workspace_bytes_for(n_rows: int, n_features: int, n_bins: int, max_leaves: int = 255, bin_bytes: int = 1,
+                            flags: int = WS_BIND | WS_ROW_COPIES | WS_BOOST) -> int:
+        """qgbdt_workspace_bytes: device bytes a context of this shape needs (no context, no GPU call)."""
+        lib = load_library()
+        shape = Shape(n_rows, n_features, n_bins, bin_bytes, max_leaves)
+        n = C.c_size_t(0)
+        rc = lib.qgbdt_workspace_bytes(C.byref(shape), flags, C.byref(n))
+        if rc != 0:
+            raise QgbdtError(rc, lib.qgbdt_last_error(None).decode())
+        return n.value
+
+    def set_workspace(self, workspace: torch.Tensor | None = None, flags: int = WS_BIND | WS_ROW_COPIES | WS_BOOST):
+        """qgbdt_set_workspace with `workspace` (a contiguous uint8 device tensor, 256-byte aligned) or, when None,
+        with a tensor of exactly the needed size allocated here.  The tensor is kept alive by the context."""
+        if workspace is None:
+            s = self.shape
+            need = self.workspace_bytes_for(s.n_rows, s.n_features, s.n_bins, s.max_leaves, s.bin_bytes, flags)
+            workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._sync_stream()
+        self._chk(self.lib.qgbdt_set_workspace(self._h, C.c_void_p(_dev(workspace, torch.uint8, "workspace")),
+                                               workspace.numel(), flags))
+        self.workspace = workspace
+        self.workspace_flags = flags
 
     def bind_bins(self, bins: torch.Tensor | None) -> None:
         """qgbdt_bind_bins: keep a feature-major copy of `bins` for the partitions of the trees that follow
-        (None frees it).  The tensor must stay alive and unchanged while it is bound."""
+        (None forgets it).  The tensor must stay alive and unchanged while it is bound."""
         self._chk(self.lib.qgbdt_bind_bins(self._h, C.c_void_p(self._bins(bins)) if bins is not None else None))
 
     # -- helpers ---------------------------------------------------------------
@@ -177,8 +211,9 @@ class Context:
 
     def close(self):
         if self._h:
-            self.lib.qgbdt_destroy(self._h)
+            self.lib.qgbdt_destroy(self._h)   # synchronises the stream: the workspace may be released afterwards
             self._h = C.c_void_p()
+        self.workspace = None
 
     def __del__(self):
         try:
@@ -188,9 +223,8 @@ class Context:
 
     @property
     def workspace_bytes(self) -> int:
-        n = C.c_size_t(0)
-        self._chk(self.lib.qgbdt_workspace_bytes(self._h, C.byref(n)))
-        return n.value
+        """Bytes of the workspace tensor this context holds."""
+        return 0 if self.workspace is None else self.workspace.numel()
 
     # -- steps -------------------------------------------------------------------
     def quantize_gradients(self, g, h, bits_g, bits_h, seed, iteration, rounding=ROUND_STOCHASTIC, gh_out=None,

@@ -67,24 +67,105 @@ __global__ __launch_bounds__(256) void gh_totals_kernel(const int16_t* __restric
 __global__ void zero3_kernel(int64_t* t) {
     if (threadIdx.x < 3) t[threadIdx.x] = 0;
 }
-
-template <typename T>
-static int ws_alloc(qgbdt_ctx* ctx, T** p, size_t n) {
-    const size_t bytes = (n ? n : 1) * sizeof(T);
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
-    if (e != hipSuccess) return set_error(ctx, QGBDT_E_ALLOC, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
-    ctx->ws_bytes += bytes;
-    return QGBDT_OK;
+__global__ void fill_bytes_kernel(unsigned char* p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
 }
 
-static void free_all(qgbdt_ctx* c) {
-    void* ptrs[] = {c->obins[0], c->obins[1], c->obins[2], c->ogh[0], c->ogh[1], c->ogh[2], c->idx[0], c->idx[1],
-                    c->idx[2], c->bins_t, c->mfb, c->gh, c->ghf, c->gbuf, c->hbuf, c->hist_pool, c->hist_partials, c->flags, c->part_counts, c->seg_counts, c->seg_prefix,
-                    c->absmax_part, c->qtotals_part, c->qtotals, c->delta, c->nodes, c->sorted_idx, c->step, c->batch, c->cand, c->hist_entries,
-                    c->hist_counts, c->pwork, c->scan_items, c->leaf_node, c->refit_partial,
-                    c->tmp_i64};
-    for (void* p : ptrs)
-        if (p) (void)hipFree(p);
+// Sizes that follow from the shape alone.
+static void derive_sizes(qgbdt_ctx* c) {
+    const int L = c->shape.max_leaves;
+    c->batch_max = L;
+    c->max_expand = 3 * L;
+    c->max_nodes = 2 * c->max_expand + 1;
+    c->max_seg = (int)(c->shape.n_rows / PART_SEG) + c->batch_max + 2;
+}
+
+// Bytes of the row groups' slots (local bins handed over to the reduce kernel): the largest any plan of this
+// shape asks for -- either word width, with or without the large tiles of frequent-bin skipping; the tile
+// shape does not depend on the bit widths.
+static size_t partial_slot_bytes(const qgbdt_shape& shape) {
+    size_t need = 0;
+    for (int w = 16; w <= 32; w += 16)
+        for (int skew = 0; skew < 2; ++skew) {
+            const HistPlan hp = make_hist_plan(shape, 2, 2, w, skew != 0);
+            const size_t b = (size_t)hp.max_items * hp.n_tiles * hp.slot_bytes;
+            if (b > need) need = b;
+        }
+    return need;
+}
+
+// Walks the sections of the workspace in a fixed order, every section aligned to 256 bytes.  With a base
+// address it assigns the context's pointers, without one it only measures.  Returns the bytes needed.
+namespace {
+struct Carver {
+    unsigned char* base;
+    size_t off;
+    template <typename T>
+    void take(T** p, size_t n) {
+        off = (off + 255) & ~(size_t)255;
+        if (base) *p = reinterpret_cast<T*>(base + off);
+        off += (n ? n : 1) * sizeof(T);
+    }
+};
+}  // namespace
+
+static bool shape_allows_ordered(const qgbdt_shape& s) {
+    return s.bin_bytes == 1 && s.n_features % 4 == 0 && s.n_features >= 16 && s.n_features <= 64;
+}
+
+static size_t carve_workspace(qgbdt_ctx* c, void* base, uint32_t flags) {
+    Carver k{static_cast<unsigned char*>(base), 0};
+    const qgbdt_shape& sh = c->shape;
+    const size_t N = (size_t)sh.n_rows, F = (size_t)sh.n_features;
+    const size_t W = F * (size_t)sh.n_bins;
+    const size_t L = (size_t)sh.max_leaves;
+    for (int b = 0; b < 3; ++b) k.take(&c->idx[b], N);
+    for (int b = 0; b < 3; ++b) k.take(&c->ogh[b], N);
+    k.take(&c->gh, N);
+    k.take(&c->ghf, N);
+    k.take(&c->hist_pool, W * (size_t)(c->max_expand + 1));
+    {
+        unsigned char* pp = nullptr;
+        const size_t need = partial_slot_bytes(sh);
+        k.take(&pp, need);
+        if (base) { c->hist_partials = pp; c->hist_partials_bytes = need; }
+    }
+    k.take(&c->flags, N);
+    k.take(&c->part_counts, (size_t)PART_GROUPS);
+    k.take(&c->seg_counts, (size_t)c->max_seg);
+    k.take(&c->seg_prefix, (size_t)c->max_seg + 1);
+    k.take(&c->absmax_part, (size_t)2 * QUANT_PARTS);
+    k.take(&c->qtotals_part, (size_t)3 * QUANT_PARTS);
+    k.take(&c->qtotals, 4);
+    k.take(&c->delta, 2);
+    k.take(&c->nodes, (size_t)c->max_nodes);
+    k.take(&c->sorted_idx, (size_t)c->max_nodes);
+    k.take(&c->step, 1);
+    k.take(&c->batch, (size_t)c->batch_max);
+    k.take(&c->cand, (size_t)2 * c->batch_max * F);
+    k.take(&c->hist_entries, (size_t)c->batch_max);
+    k.take(&c->hist_counts, 2);
+    k.take(&c->pwork, 1);
+    k.take(&c->scan_items, (size_t)2 * c->batch_max);
+    k.take(&c->leaf_node, L);
+    k.take(&c->refit_partial, L * REFIT_PARTS * 2);
+    k.take(&c->tmp_i64, 8);
+    // optional sections
+    if (flags & QGBDT_WS_BIND) {
+        k.take(&c->bins_t, N * F * (size_t)sh.bin_bytes);
+        k.take(&c->mfb, F);
+    } else if (base) { c->bins_t = nullptr; c->mfb = nullptr; }
+    if ((flags & QGBDT_WS_ROW_COPIES) && shape_allows_ordered(sh)) {
+        for (int b = 0; b < 3; ++b) k.take(&c->obins[b], N * F);
+    } else if (base) { c->obins[0] = c->obins[1] = c->obins[2] = nullptr; }
+    if (flags & QGBDT_WS_BOOST) {
+        k.take(&c->gbuf, N);
+        k.take(&c->hbuf, N);
+    } else if (base) { c->gbuf = nullptr; c->hbuf = nullptr; }
+    return (k.off + 255) & ~(size_t)255;
+}
+
+static void free_host(qgbdt_ctx* c) {
     if (c->host_state) (void)hipHostFree(c->host_state);
     if (c->ev) {
         for (int i = 0; i < c->ev_cap; ++i)
@@ -93,24 +174,13 @@ static void free_all(qgbdt_ctx* c) {
     }
 }
 
-}  // namespace qgbdt
-
-// The three rotating copies of the packed gradients in list order and, `with_bins` (ordered mode), of the bin rows;
-// allocated on first use.
-int qgbdt::ensure_ordered_buffers(qgbdt_ctx* c, bool with_bins) {
-    const size_t N = (size_t)c->shape.n_rows;
-    for (int b = 0; b < 3; ++b) {
-        if (with_bins && !c->obins[b]) {
-            int rc = qgbdt::ws_alloc(c, &c->obins[b], N * c->shape.n_features);
-            if (rc != QGBDT_OK) { c->obins[b] = nullptr; return rc; }
-        }
-        if (!c->ogh[b]) {
-            int rc = qgbdt::ws_alloc(c, &c->ogh[b], N);
-            if (rc != QGBDT_OK) { c->ogh[b] = nullptr; return rc; }
-        }
-    }
+int require_workspace(qgbdt_ctx* ctx) {
+    if (!ctx->ws_base)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "no workspace: call qgbdt_set_workspace first (qgbdt_workspace_bytes gives its size)");
     return QGBDT_OK;
 }
+
+}  // namespace qgbdt
 
 namespace qgbdt {
 
@@ -147,15 +217,28 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
-    if (!out || !shape) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
-    *out = nullptr;
+static int check_shape(const qgbdt_shape* shape) {
+    if (!shape) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
+    if (shape->bin_bytes != 1 && shape->bin_bytes != 2)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "bin_bytes=%d: bins are uint8 (1) or uint16 (2)", shape->bin_bytes);
     if (shape->n_rows < 1 || shape->n_rows > 2147483647LL || shape->n_features < 1 || shape->n_bins < 2 ||
         shape->n_bins > (shape->bin_bytes == 2 ? 1024 : 256) || shape->max_leaves < 1)
         return set_error(nullptr, QGBDT_E_INVALID_ARG, "shape out of range (rows %lld, features %d, bins %d, leaves %d)",
                          (long long)shape->n_rows, shape->n_features, shape->n_bins, shape->max_leaves);
-    if (shape->bin_bytes != 1 && shape->bin_bytes != 2)
-        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "bin_bytes=%d: bins are uint8 (1) or uint16 (2)", shape->bin_bytes);
+    // the plan kernel keeps its sort and replay state of all nodes in LDS
+    const size_t L = (size_t)shape->max_leaves, max_nodes = 6 * L + 1, p_max = max_nodes + (max_nodes & 1);
+    const size_t plan_lds = p_max * 24 + L * 16 + max_nodes * 12 + (4 * L + 8) * 4;
+    if (plan_lds > 160 * 1024)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 690 leaves)",
+                         shape->max_leaves, plan_lds);
+    return QGBDT_OK;
+}
+
+int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
+    if (!out || !shape) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
+    *out = nullptr;
+    int rc = check_shape(shape);
+    if (rc != QGBDT_OK) return rc;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
         return set_error(nullptr, QGBDT_E_HIP, "no HIP device: this library has no CPU path");
@@ -165,73 +248,16 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     c->shape = *shape;
     c->stream = (hipStream_t)stream;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return set_error(nullptr, QGBDT_E_HIP, "hipGetDevice failed"); }
-    const int64_t N = shape->n_rows;
-    const int64_t W = (int64_t)shape->n_features * shape->n_bins;
-    const int L = shape->max_leaves;
-    c->batch_max = L;
-    c->max_expand = 3 * L;
-    c->max_nodes = 2 * c->max_expand + 1;
-    c->max_seg = (int)(N / PART_SEG) + c->batch_max + 2;
+    derive_sizes(c);
     c->rounds_hint = 10;
-    {
-        // the plan kernel keeps its sort and replay state of all nodes in LDS
-        const size_t p_max = (size_t)c->max_nodes + (c->max_nodes & 1);
-        const size_t plan_lds = p_max * 24 + (size_t)c->batch_max * 16 + (size_t)c->max_nodes * 12 + (size_t)(4 * L + 8) * 4;
-        if (plan_lds > 160 * 1024) {
-            delete c;
-            return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 690 leaves)", L, plan_lds);
-        }
-    }
-    int rc = QGBDT_OK;
-    // narrow rows may be kept in leaf order (the copies are allocated by the first tree that is grown that way)
-    c->ordered = (shape->bin_bytes == 1 && shape->n_features % 4 == 0 && shape->n_features >= 16 &&
-                  shape->n_features <= 64) ? 1 : 0;
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[0], (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[1], (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->idx[2], (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->gh, (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->ghf, (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_pool, (size_t)(W * (c->max_expand + 1)));
-    if (rc == QGBDT_OK) {
-        // slots of the row groups' local bins, for either accumulator width
-        size_t need = 0;
-        for (int w = 16; w <= 32; w += 16)
-            for (int skew = 0; skew < 2; ++skew) {
-                const HistPlan hp = make_hist_plan(*shape, 2, 2, w, skew != 0);
-                const size_t b = (size_t)hp.max_items * hp.n_tiles * hp.slot_bytes;
-                if (b > need) need = b;
-            }
-        unsigned char* pp = nullptr;
-        rc = ws_alloc(c, &pp, need);
-        c->hist_partials = pp;
-    }
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->flags, (size_t)N);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->part_counts, (size_t)PART_GROUPS);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_counts, (size_t)c->max_seg);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->seg_prefix, (size_t)c->max_seg + 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->absmax_part, (size_t)2 * QUANT_PARTS);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals_part, (size_t)3 * QUANT_PARTS);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->qtotals, 4);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->delta, 2);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->nodes, (size_t)c->max_nodes);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->sorted_idx, (size_t)c->max_nodes);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->step, 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->batch, (size_t)c->batch_max);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->cand, (size_t)2 * c->batch_max * shape->n_features);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_entries, (size_t)c->batch_max);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->hist_counts, 2);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->pwork, 1);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->scan_items, (size_t)2 * c->batch_max);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->leaf_node, (size_t)L);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->refit_partial, (size_t)L * REFIT_PARTS * 2);
-    if (rc == QGBDT_OK) rc = ws_alloc(c, &c->tmp_i64, 8);
-    if (rc == QGBDT_OK && hipMemset(c->step, 0, sizeof(StepState)) != hipSuccess)
-        rc = set_error(c, QGBDT_E_HIP, "hipMemset failed");
-    if (rc == QGBDT_OK && hipHostMalloc(reinterpret_cast<void**>(&c->host_state), sizeof(StepState), hipHostMallocDefault) != hipSuccess)
+    if (hipHostMalloc(reinterpret_cast<void**>(&c->host_state), sizeof(StepState), hipHostMallocDefault) != hipSuccess)
         rc = set_error(c, QGBDT_E_ALLOC, "hipHostMalloc failed");
+    // kernels whose local bins or bookkeeping exceed the default limit of dynamic LDS are told so once
+    if (rc == QGBDT_OK) rc = prepare_hist_kernels(c);
+    if (rc == QGBDT_OK) rc = prepare_tree_kernels(c);
     if (rc != QGBDT_OK) {
         snprintf(g_create_error, sizeof(g_create_error), "%s", c->err);
-        free_all(c);
+        free_host(c);
         delete c;
         return rc;
     }
@@ -242,7 +268,7 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
 int qgbdt_destroy(qgbdt_ctx* ctx) {
     if (!ctx) return QGBDT_OK;
     (void)hipStreamSynchronize(ctx->stream);
-    free_all(ctx);
+    free_host(ctx);
     delete ctx;
     return QGBDT_OK;
 }
@@ -255,9 +281,49 @@ int qgbdt_set_stream(qgbdt_ctx* ctx, void* stream) {
 
 const char* qgbdt_last_error(const qgbdt_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
 
-int qgbdt_workspace_bytes(const qgbdt_ctx* ctx, size_t* bytes) {
-    if (!ctx || !bytes) return QGBDT_E_INVALID_ARG;
-    *bytes = ctx->ws_bytes;
+int qgbdt_workspace_bytes(const qgbdt_shape* shape, uint32_t flags, size_t* bytes) {
+    if (!bytes) return set_error(nullptr, QGBDT_E_INVALID_ARG, "null argument");
+    int rc = check_shape(shape);
+    if (rc != QGBDT_OK) return rc;
+    if (flags & ~(uint32_t)(QGBDT_WS_BIND | QGBDT_WS_ROW_COPIES | QGBDT_WS_BOOST))
+        return set_error(nullptr, QGBDT_E_INVALID_ARG, "unknown workspace flags 0x%x", flags);
+    qgbdt_ctx tmp;
+    memset(&tmp, 0, sizeof(tmp));
+    tmp.shape = *shape;
+    derive_sizes(&tmp);
+    *bytes = carve_workspace(&tmp, nullptr, flags);
+    return QGBDT_OK;
+}
+
+int qgbdt_set_workspace(qgbdt_ctx* ctx, void* dev, size_t bytes, uint32_t flags) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (flags & ~(uint32_t)(QGBDT_WS_BIND | QGBDT_WS_ROW_COPIES | QGBDT_WS_BOOST))
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "unknown workspace flags 0x%x", flags);
+    // what was enqueued may still use the old block
+    QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->ws_base = nullptr;
+    ctx->ws_bytes = 0;
+    ctx->ws_flags = 0;
+    ctx->bound_bins = nullptr;
+    ctx->mfb_features = 0;
+    if (!dev) return QGBDT_OK;  // detached: every step refuses until a block is set again
+    if (((uintptr_t)dev & 255) != 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "the workspace must be 256-byte aligned");
+    size_t need = 0;
+    {
+        qgbdt_ctx tmp = *ctx;
+        need = carve_workspace(&tmp, nullptr, flags);
+    }
+    if (bytes < need)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "workspace of %zu bytes is too small: this shape with flags 0x%x needs %zu",
+                         bytes, flags, need);
+    carve_workspace(ctx, dev, flags);
+    ctx->ws_base = dev;
+    ctx->ws_bytes = need;
+    ctx->ws_flags = flags;
+    ctx->ordered = ctx->obins[0] ? 1 : 0;
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(1), dim3(256), 0, ctx->stream, reinterpret_cast<unsigned char*>(ctx->step),
+                       (int)sizeof(StepState));
+    QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
@@ -266,6 +332,7 @@ int qgbdt_quantize_gradients(qgbdt_ctx* ctx, const float* g, const float* h, int
                              float* delta_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!g || !h || !gh_out || !delta_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
     if (rounding != QGBDT_ROUND_STOCHASTIC && rounding != QGBDT_ROUND_NEAREST)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "rounding=%d", rounding);
@@ -279,6 +346,7 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
                            int64_t* hist_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!bins || !gh || !hist_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (begin < 0 || count < 0 || begin + count > ctx->shape.n_rows)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "slice [%lld, +%lld) outside 0..n_rows", (long long)begin, (long long)count);
     if (acc_width != 0 && acc_width != 16 && acc_width != 32)
@@ -326,31 +394,18 @@ int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     ctx->bound_bins = nullptr;
     ctx->mfb_features = 0;
-    if (!bins) {
-        if (ctx->bins_t) {
-            QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
-            const size_t bytes = (size_t)ctx->shape.n_rows * ctx->shape.n_features * ctx->shape.bin_bytes;
-            (void)hipFree(ctx->bins_t);
-            ctx->bins_t = nullptr;
-            ctx->ws_bytes -= bytes;
-        }
-        return QGBDT_OK;
-    }
-    if (!ctx->bins_t) {
-        int rc = ws_alloc(ctx, &ctx->bins_t, (size_t)ctx->shape.n_rows * ctx->shape.n_features * ctx->shape.bin_bytes);
-        if (rc != QGBDT_OK) { ctx->bins_t = nullptr; return rc; }
-    }
+    if (!bins) return QGBDT_OK;
+    if (int rcw = require_workspace(ctx)) return rcw;
+    if (!ctx->bins_t)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "the workspace has no room for the copy of a bound matrix (set it with QGBDT_WS_BIND)");
     int rc = launch_transpose_bins(ctx, bins, ctx->bins_t);
     if (rc != QGBDT_OK) return rc;
-    // most frequent bins (left out by the wide-row histogram kernels); the host learns how many features have one
-    ctx->mfb_features = 0;
-    if (!ctx->mfb) {
-        rc = ws_alloc(ctx, &ctx->mfb, (size_t)ctx->shape.n_features);
-        if (rc != QGBDT_OK) { ctx->mfb = nullptr; return rc; }
-    }
-    rc = launch_frequent_bins(ctx, ctx->bins_t, ctx->mfb);
-    if (rc != QGBDT_OK) return rc;
-    {
+    // Most frequent bins (left out by the wide-row histogram kernels); the host learns how many features have one.
+    // Only those kernels can use them, so narrow matrices skip the sampling.
+    const HistPlan probe = make_hist_plan(ctx->shape, 2, 2, 0, true);
+    if (probe.wide_v > 0) {
+        rc = launch_frequent_bins(ctx, ctx->bins_t, ctx->mfb);
+        if (rc != QGBDT_OK) return rc;
         std::vector<uint16_t> host((size_t)ctx->shape.n_features);
         QG_HIP(ctx, hipMemcpyAsync(host.data(), ctx->mfb, host.size() * sizeof(uint16_t), hipMemcpyDeviceToHost, ctx->stream));
         QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -366,6 +421,7 @@ int qgbdt_bind_bins(qgbdt_ctx* ctx, const void* bins) {
 int qgbdt_subtract_histograms(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* sibling_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!parent || !child || !sibling_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     return launch_subtract(ctx, parent, child, sibling_out, (int64_t)ctx->shape.n_features * ctx->shape.n_bins);
 }
 
@@ -373,6 +429,7 @@ int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists,
                            const float* delta, int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!hist || !stats || !delta || !out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n_hists < 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "n_hists=%d", n_hists);
     return run_find_best_splits(ctx, hist, n_hists, stats, delta, min_data_in_leaf, min_sum_hessian, out);
 }
@@ -381,6 +438,7 @@ int qgbdt_partition_rows(qgbdt_ctx* ctx, const void* bins, int32_t* row_idx, int
                          int32_t feature, int32_t bin, int64_t* n_left_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!bins || !row_idx || !n_left_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (begin < 0 || count < 0 || begin + count > ctx->shape.n_rows)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "slice [%lld, +%lld) outside 0..n_rows", (long long)begin, (long long)count);
     if (feature < 0 || feature >= ctx->shape.n_features)
@@ -393,6 +451,7 @@ int qgbdt_refit_leaves(qgbdt_ctx* ctx, const float* g, const float* h, const int
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!g || !h || !row_idx || !leaf_begin || !leaf_count || !value_out)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n_leaves < 0 || n_leaves > ctx->shape.max_leaves)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "n_leaves=%d outside 0..max_leaves", n_leaves);
     return launch_refit(ctx, g, h, nullptr, row_idx, leaf_begin, leaf_count, n_leaves, nullptr, value_out);
@@ -402,6 +461,7 @@ int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const floa
                     uint32_t iteration, const qgbdt_tree* t, int32_t* row_idx_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!bins || !g || !h || !p || !t || !row_idx_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (!t->n_leaves || !t->split_leaf || !t->split_feature || !t->split_bin || !t->split_gain || !t->split_stats ||
         !t->split_n_left || !t->leaf_begin || !t->leaf_count || !t->leaf_sum_g || !t->leaf_sum_h || !t->leaf_value ||
         !t->leaf_value_quant || !t->delta || !t->hist_units)
@@ -414,10 +474,12 @@ int qgbdt_grow_tree(qgbdt_ctx* ctx, const void* bins, const float* g, const floa
         return set_error(ctx, QGBDT_E_INVALID_ARG, "acc_width=%d (0, 16 or 32)", p->acc_width);
     if (p->row_layout < QGBDT_ROWS_AUTO || p->row_layout > QGBDT_ROWS_ORDERED)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "row_layout=%d (QGBDT_ROWS_*)", p->row_layout);
-    if (p->row_layout == QGBDT_ROWS_ORDERED && !ctx->ordered)
+    if (p->row_layout == QGBDT_ROWS_ORDERED && !shape_allows_ordered(ctx->shape))
         return set_error(ctx, QGBDT_E_UNSUPPORTED,
                          "ordered rows need uint8 bins and 16..64 features that are a multiple of 4 (n_features=%d, bin_bytes=%d)",
                          ctx->shape.n_features, ctx->shape.bin_bytes);
+    if (p->row_layout == QGBDT_ROWS_ORDERED && !ctx->ordered)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "the workspace has no room for leaf-ordered copies of the rows (set it with QGBDT_WS_ROW_COPIES)");
     if (((uintptr_t)bins & 3) != 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "bins must be 4-byte aligned");
     int rc = check_bits(ctx, p->bits_g, p->bits_h);
     if (rc != QGBDT_OK) return rc;
@@ -428,6 +490,7 @@ int qgbdt_logistic_gradients(qgbdt_ctx* ctx, const float* score, const float* la
                              float* h_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!score || !label || !g_out || !h_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
     return launch_logistic_gradients(ctx, score, label, n, g_out, h_out);
 }
@@ -437,6 +500,7 @@ int qgbdt_update_scores(qgbdt_ctx* ctx, float* score, const int32_t* row_idx, co
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!score || !row_idx || !leaf_begin || !leaf_count || !leaf_value)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n_leaves < 0 || n_leaves > ctx->shape.max_leaves)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "n_leaves=%d outside 0..max_leaves", n_leaves);
     return launch_update_scores(ctx, score, row_idx, leaf_begin, leaf_count, leaf_value, n_leaves, nullptr, learning_rate);
@@ -446,6 +510,7 @@ int qgbdt_lambdarank_gradients(qgbdt_ctx* ctx, const float* score, const float* 
                                int32_t group_size, float* g_out, float* h_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!score || !relevance || !g_out || !h_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (n < 0 || n > ctx->shape.n_rows) return set_error(ctx, QGBDT_E_INVALID_ARG, "n=%lld outside 0..n_rows", (long long)n);
     if (group_size < 1 || group_size > 1024)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "group_size=%d outside 1..1024", group_size);
@@ -461,11 +526,9 @@ static int boost_iteration(qgbdt_ctx* ctx, int loss, int group_size, const void*
     if (loss == 1 && (group_size < 1 || group_size > 1024))
         return set_error(ctx, QGBDT_E_INVALID_ARG, "group_size=%d outside 1..1024", group_size);
     const int64_t N = ctx->shape.n_rows;
-    if (!ctx->gbuf) {
-        int rc = ws_alloc(ctx, &ctx->gbuf, (size_t)N);
-        if (rc == QGBDT_OK) rc = ws_alloc(ctx, &ctx->hbuf, (size_t)N);
-        if (rc != QGBDT_OK) return rc;
-    }
+    if (int rcw = require_workspace(ctx)) return rcw;
+    if (!ctx->gbuf || !ctx->hbuf)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "the workspace has no room for the loss derivatives (set it with QGBDT_WS_BOOST)");
     int rc = loss == 0 ? launch_logistic_gradients(ctx, score, label, N, ctx->gbuf, ctx->hbuf)
                        : launch_lambdarank_gradients(ctx, score, label, N, group_size, ctx->gbuf, ctx->hbuf);
     if (rc != QGBDT_OK) return rc;
@@ -489,11 +552,11 @@ int qgbdt_boost_iteration_lambdarank(qgbdt_ctx* ctx, const void* bins, const flo
 int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (on && !ctx->ev) {
-        ctx->ev_cap = 16384;
+        // handles only; an event is created when a launch first uses its place (profile_events)
+        ctx->ev_cap = 8192;
         ctx->ev = new (std::nothrow) hipEvent_t[ctx->ev_cap];
         if (!ctx->ev) { ctx->ev_cap = 0; return set_error(ctx, QGBDT_E_ALLOC, "out of host memory"); }
         memset(ctx->ev, 0, sizeof(hipEvent_t) * ctx->ev_cap);
-        for (int i = 0; i < ctx->ev_cap; ++i) QG_HIP(ctx, hipEventCreate(&ctx->ev[i]));
     }
     ctx->profiling = on ? 1 : 0;
     return QGBDT_OK;

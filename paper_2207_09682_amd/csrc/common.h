@@ -150,7 +150,10 @@ struct qgbdt_ctx {
     qgbdt_shape shape;
     hipStream_t stream;
     int device;
+    // the caller's workspace block (qgbdt_set_workspace); every device pointer below points into it
+    void* ws_base;
     size_t ws_bytes;
+    uint32_t ws_flags;
     // sizes derived from the shape
     int batch_max;   // most nodes expanded per round
     int max_expand;  // most expansions per tree (sequential ones plus speculative ones)
@@ -158,20 +161,21 @@ struct qgbdt_ctx {
     int max_seg;
     int rounds_hint;
     // workspace
-    int ordered;           // narrow rows: children get physically leaf-ordered copies of their rows
-    uint8_t* obins[3];     // [N][F] each (ordered mode)
-    int16_t* ogh[3];       // [N] each: packed gradients in the order of idx[b] (allocated on first tree)
+    int ordered;           // the workspace holds leaf-ordered copies of the rows (narrow rows, QGBDT_WS_ROW_COPIES)
+    uint8_t* obins[3];     // [N][F] each (ordered mode), else null
+    int16_t* ogh[3];       // [N] each: packed gradients in the order of idx[b]
     int32_t* idx[3];       // [N] each
-    uint8_t* bins_t;       // [F][N] feature-major copy of the bound bin matrix (qgbdt_bind_bins), else null
+    uint8_t* bins_t;       // [F][N] feature-major copy of the bound bin matrix (QGBDT_WS_BIND, filled by qgbdt_bind_bins), else null
     uint16_t* mfb;         // [F] most frequent bin of each feature of the bound matrix when it holds most rows, else 0xffff
     int mfb_features;      // features with such a bin (0: no skipping)
     const void* bound_bins; // the matrix that copy was made from
     int16_t* gh;           // [N]
     float2* ghf;           // [N] (g, h) interleaved, written by the quantizer for the refit's gather
-    float* gbuf;           // [N] loss derivatives of a boosting iteration run by the library (allocated on first use)
+    float* gbuf;           // [N] loss derivatives of a boosting iteration run by the library (QGBDT_WS_BOOST), else null
     float* hbuf;           // [N]
     int64_t* hist_pool;    // [max_expand + 1][nb*F]
     void* hist_partials;   // [max_items][n_tiles] local bins of the row groups, summed by the reduce kernel
+    size_t hist_partials_bytes;
     uint8_t* flags;        // [N] partition flags
     int64_t* part_counts;  // [PART_GROUPS] (stand-alone partition)
     int32_t* seg_counts;   // [max_seg] left rows per partition segment
@@ -242,7 +246,9 @@ int launch_batch_partition_count(qgbdt_ctx* ctx, const RowSource& rows, const ui
 int launch_transpose_bins(qgbdt_ctx* ctx, const void* bins, void* out);
 int launch_frequent_bins(qgbdt_ctx* ctx, const void* bins_t, uint16_t* mfb);
 int launch_fix_frequent_bins(qgbdt_ctx* ctx, int64_t* hist, const int64_t* totals, const uint16_t* mfb);
-int ensure_ordered_buffers(qgbdt_ctx* ctx, bool with_bins);
+int require_workspace(qgbdt_ctx* ctx);   // QGBDT_E_WORKSPACE unless a workspace block is set
+int prepare_hist_kernels(qgbdt_ctx* ctx);  // once per context: dynamic-LDS limits of the kernels that exceed the default
+int prepare_tree_kernels(qgbdt_ctx* ctx);
 int launch_batch_partition_scatter(qgbdt_ctx* ctx, const RowSource& rows, bool ordered);  // !ordered: row ids and, with rows.gh_pos, packed gradients
 int launch_refit(qgbdt_ctx* ctx, const float* g, const float* h, const float2* pairs, const int32_t* row_idx,
                  const int64_t* leaf_begin, const int64_t* leaf_count, int n_leaves,

@@ -507,6 +507,25 @@ __global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* 
         out[S.begin + j] = src[S.begin + j];
 }
 
+// LDS of the plan kernel: sort keys and order of all nodes, the new nodes' keys, per-node replay state, and the
+// per-leaf arrays of the replay.
+static size_t plan_kernel_lds(const qgbdt_ctx* ctx, int num_leaves) {
+    const int p_max = ctx->max_nodes + (ctx->max_nodes & 1);
+    return (size_t)p_max * 24 + (size_t)ctx->batch_max * 16 + (size_t)ctx->max_nodes * 12 +
+           (size_t)(4 * num_leaves + 8) * sizeof(int);
+}
+
+int prepare_tree_kernels(qgbdt_ctx* ctx) {
+    const size_t plan_lds = plan_kernel_lds(ctx, ctx->shape.max_leaves);
+    if (plan_lds > 160 * 1024)
+        return set_error(ctx, QGBDT_E_UNSUPPORTED, "max_leaves=%d needs %zu bytes of LDS for the growth bookkeeping (limit 160 KB)",
+                         ctx->shape.max_leaves, plan_lds);
+    if (plan_lds > 48 * 1024)
+        QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(tree_plan_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan_lds));
+    return QGBDT_OK;
+}
+
 int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const float* h, const qgbdt_params* p,
                   uint32_t iteration, const qgbdt_tree* tout, int32_t* row_idx_out) {
     const int64_t N = ctx->shape.n_rows;
@@ -556,10 +575,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                  : ((int64_t)N * F * ctx->shape.bin_bytes >= (int64_t)128 << 20) ? QGBDT_ROWS_IDS_GH : QGBDT_ROWS_IDS;
     const bool ordered = layout == QGBDT_ROWS_ORDERED;
     const bool gh_lists = layout != QGBDT_ROWS_IDS;
-    if (gh_lists) {
-        int rc0 = ensure_ordered_buffers(ctx, ordered);
-        if (rc0 != QGBDT_OK) return rc0;
-    }
+    if (ordered && !ctx->ordered)
+        return set_error(ctx, QGBDT_E_WORKSPACE, "the workspace has no room for leaf-ordered copies of the rows");
     for (int b = 0; b < 3; ++b) {
         rows.bins[b] = ordered ? ctx->obins[b] : bins;
         rows.gh[b] = gh_lists ? ctx->ogh[b] : ctx->gh;
@@ -585,14 +602,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     if (rc != QGBDT_OK) return rc;
 
     const int p_max = ctx->max_nodes + (ctx->max_nodes & 1);  // even: 8-byte arrays follow 4-byte ones
-    const size_t plan_lds = (size_t)p_max * 24 + (size_t)ctx->batch_max * 16 + (size_t)ctx->max_nodes * 12 +
-                            (size_t)(4 * p->num_leaves + 8) * sizeof(int);
-    if (plan_lds > 160 * 1024)
-        return set_error(ctx, QGBDT_E_UNSUPPORTED, "max_leaves=%d needs %zu bytes of LDS for the growth bookkeeping (limit 160 KB)",
-                         ctx->shape.max_leaves, plan_lds);
-    if (plan_lds > 48 * 1024)
-        QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(tree_plan_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan_lds));
+    const size_t plan_lds = plan_kernel_lds(ctx, p->num_leaves);  // at most what prepare_tree_kernels allowed
     const int round_cap = 4 * ctx->shape.max_leaves + 8;  // every round commits or expands at least one node
     int launched = 0;
     int to_launch = ctx->rounds_hint;
