@@ -213,6 +213,18 @@ QGBDT_API int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_
                            const qgbdt_leafstat* stats, const float* delta,
                            int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out);
 
+/* The same search for callers that cannot allocate or be handed a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Works on a context with no workspace set and calls no
+ * allocating routine.  Its scratch (one item per histogram, one candidate per (histogram, feature)) lives in a
+ * fixed array of 4 MiB inside the library, of which every GPU the library runs on holds its own copy until the
+ * process ends: n_hists * (48 + 24 * n_features) + 512 bytes must fit (about 5,800 histograms of 28 features, 87 of
+ * 2000), else QGBDT_E_INVALID_ARG.  All calls on one GPU share that array and nothing in it needs clearing between
+ * calls (every entry a call reads it has written before); calls that overlap on one GPU -- two streams, two
+ * contexts, two threads -- race on it.  Arguments and results as qgbdt_find_best_splits. */
+QGBDT_API int qgbdt_find_best_splits_static(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists,
+                                  const qgbdt_leafstat* stats, const float* delta,
+                                  int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out);
+
 /* Stable partition of the slice row_idx[begin..begin+count) (the set I_s of
  * Algorithm 1): rows with bins[row][feature] <= bin first, both sides keeping their
  * order.  row_idx: dev int32, reordered in place; n_left_out: dev int64[1]. */

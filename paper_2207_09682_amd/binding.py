@@ -26,7 +26,7 @@ EXPORTS = [
     "qgbdt_create", "qgbdt_destroy", "qgbdt_set_stream", "qgbdt_last_error", "qgbdt_workspace_bytes",
     "qgbdt_set_workspace",
     "qgbdt_quantize_gradients", "qgbdt_build_histograms", "qgbdt_subtract_histograms",
-    "qgbdt_find_best_splits", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
+    "qgbdt_find_best_splits", "qgbdt_find_best_splits_static", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_boost_iteration_lambdarank",
     "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats", "qgbdt_bind_bins",
@@ -77,6 +77,7 @@ def load_library() -> C.CDLL:
         lib.qgbdt_subtract_histograms.argtypes = [C.c_void_p] * 4
         lib.qgbdt_find_best_splits.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                                C.c_double, C.c_void_p]
+        lib.qgbdt_find_best_splits_static.argtypes = lib.qgbdt_find_best_splits.argtypes
         lib.qgbdt_partition_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32,
                                              C.c_int32, C.c_void_p]
         lib.qgbdt_refit_leaves.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -194,6 +195,14 @@ class Context:
 
     def bind_bins(self, bins: torch.Tensor | None) -> None:
         """qgbdt_bind_bins: keep a feature-major copy of `bins` for the partitions of the trees that follow
+    def detach_workspace(self):
+        """qgbdt_set_workspace(NULL): the context gives its block back; every step but the ones that need no
+        workspace refuses until another block is set."""
+        self._sync_stream()
+        self._chk(self.lib.qgbdt_set_workspace(self._h, None, 0, 0))
+        self.workspace = None
+        self.workspace_flags = 0
+
         (None forgets it).  The tensor must stay alive and unchanged while it is bound."""
         self._chk(self.lib.qgbdt_bind_bins(self._h, C.c_void_p(self._bins(bins)) if bins is not None else None))
 
@@ -271,6 +280,17 @@ class Context:
 
     def partition_rows(self, bins, row_idx, begin, count, feature, bin):
         self._sync_stream()
+    def find_best_splits_static(self, hist, stats, delta, out, min_data_in_leaf=20, min_sum_hessian=0.0):
+        """qgbdt_find_best_splits_static: the same search with the library's fixed scratch; allocates nothing, so
+        the caller passes `out` (uint8 [n, 56])."""
+        self._sync_stream()
+        n = stats.shape[0]
+        self._chk(self.lib.qgbdt_find_best_splits_static(self._h, _dev(hist, torch.int64, "hist"), n,
+                                                         _dev(stats, torch.int64, "stats"),
+                                                         _dev(delta, torch.float32, "delta"), min_data_in_leaf,
+                                                         min_sum_hessian, _dev(out, torch.uint8, "out")))
+        return out
+
         n_left = torch.empty(1, dtype=torch.int64, device=self.device)
         self._chk(self.lib.qgbdt_partition_rows(self._h, self._bins(bins),
                                                 _dev(row_idx, torch.int32, "row_idx"), begin, count, feature, bin,

@@ -11,6 +11,15 @@
 
 static char g_create_error[512] = "";
 
+// Fixed scratch for the entry point that allocates nothing (qgbdt_find_best_splits_static): every GPU the
+// library runs on holds its own copy of this array until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the address kernels are given is looked up once per device (in
+// qgbdt_create, with that device current) and kept here.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+constexpr int STATIC_SCRATCH_DEVICES = 64;
+static __device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+static void* g_static_scratch_ptr[STATIC_SCRATCH_DEVICES] = {};
+
 namespace qgbdt {
 
 int set_error(qgbdt_ctx* ctx, int code, const char* fmt, ...) {
@@ -265,6 +274,17 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     return QGBDT_OK;
 }
 
+    if (c->device >= 0 && c->device < STATIC_SCRATCH_DEVICES) {
+        if (!g_static_scratch_ptr[c->device]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) {
+                delete c;
+                return set_error(nullptr, QGBDT_E_HIP, "hipGetSymbolAddress of the fixed scratch array failed");
+            }
+            g_static_scratch_ptr[c->device] = p;
+        }
+        c->static_scratch = g_static_scratch_ptr[c->device];
+    }
 int qgbdt_destroy(qgbdt_ctx* ctx) {
     if (!ctx) return QGBDT_OK;
     (void)hipStreamSynchronize(ctx->stream);
@@ -431,7 +451,31 @@ int qgbdt_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists,
     if (!hist || !stats || !delta || !out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
     if (int rcw = require_workspace(ctx)) return rcw;
     if (n_hists < 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "n_hists=%d", n_hists);
-    return run_find_best_splits(ctx, hist, n_hists, stats, delta, min_data_in_leaf, min_sum_hessian, out);
+    return run_find_best_splits(ctx, hist, n_hists, stats, delta, min_data_in_leaf, min_sum_hessian, out,
+                                2 * ctx->batch_max, ctx->scan_items, ctx->cand, reinterpret_cast<int32_t*>(ctx->tmp_i64));
+}
+
+int qgbdt_find_best_splits_static(qgbdt_ctx* ctx, const int64_t* hist, int32_t n_hists, const qgbdt_leafstat* stats,
+                                  const float* delta, int32_t min_data_in_leaf, double min_sum_hessian, qgbdt_split* out) {
+    if (!ctx) return QGBDT_E_INVALID_ARG;
+    if (!hist || !stats || !delta || !out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (n_hists < 0) return set_error(ctx, QGBDT_E_INVALID_ARG, "n_hists=%d", n_hists);
+    if (!ctx->static_scratch) return set_error(ctx, QGBDT_E_UNSUPPORTED, "no fixed scratch on device %d", ctx->device);
+    // the array holds: the item count [256 bytes], one item per histogram, one candidate per (histogram, feature)
+    const size_t F = (size_t)ctx->shape.n_features;
+    const size_t items_off = 256;
+    const size_t cand_off = (items_off + (size_t)n_hists * sizeof(ScanItem) + 255) & ~(size_t)255;
+    const size_t need = cand_off + (size_t)n_hists * F * sizeof(FeatCand);
+    if (need > STATIC_SCRATCH_BYTES)
+        return set_error(ctx, QGBDT_E_INVALID_ARG,
+                         "n_hists=%d x %d features needs %zu bytes of scratch, the fixed array holds %zu (at most %zu histograms of this shape)",
+                         n_hists, ctx->shape.n_features, need, STATIC_SCRATCH_BYTES,
+                         (STATIC_SCRATCH_BYTES - 512) / (sizeof(ScanItem) + F * sizeof(FeatCand)));
+    if (n_hists == 0) return QGBDT_OK;
+    unsigned char* base = static_cast<unsigned char*>(ctx->static_scratch);
+    return run_find_best_splits(ctx, hist, n_hists, stats, delta, min_data_in_leaf, min_sum_hessian, out, n_hists,
+                                reinterpret_cast<ScanItem*>(base + items_off), reinterpret_cast<FeatCand*>(base + cand_off),
+                                reinterpret_cast<int32_t*>(base));
 }
 
 int qgbdt_partition_rows(qgbdt_ctx* ctx, const void* bins, int32_t* row_idx, int64_t begin, int64_t count,

@@ -201,6 +201,9 @@ struct qgbdt_ctx {
     int profiling;
     hipEvent_t* ev;
     int ev_cap, ev_used;
+    unsigned char* ev_root;  // [ev_cap / 2] 1: the launch was a tree's root build (all rows, contiguous)
+    int next_hist_is_root;
+    void* static_scratch;  // this device's copy of the library's fixed scratch array (entry points that allocate nothing)
     char err[512];
 };
 
@@ -235,9 +238,11 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess, const uint16_t* mfb = nullptr);
+                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb = nullptr);
+// stand-alone search in batches of `cap` histograms; scratch: items [cap], cand [cap][F], n_items [1]
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
-                         const float* delta, int min_data, double min_sum_hess, qgbdt_split* out);
+                         const float* delta, int min_data, double min_sum_hess, qgbdt_split* out, int cap,
+                         ScanItem* items, FeatCand* cand, int32_t* n_items);
 int launch_partition_work(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* buf0, int32_t* buf1, const PartWork* work,
                           int64_t* n_left_out, int64_t max_count);
 int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, int64_t begin, int64_t count,

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void reduce_items_kernel(const FeatCand* __res
 }
 
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess, const uint16_t* mfb) {
+                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int threads = 64;
     while (threads < nb) threads <<= 1;
@@ -307,7 +307,7 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
         if (gy < 1) gy = 1;
 #define QG_SCAN_TILE(P_)                                                                                          \
     hipLaunchKernelGGL(scan_tile_kernel<P_>, dim3(gx, gy), dim3(1024), 0, ctx->stream, hist_base, items, n_items, \
-                       F, nb, delta, (int64_t)min_data, min_sum_hess, ctx->cand, mfb)
+                       F, nb, delta, (int64_t)min_data, min_sum_hess, cand, mfb)
         if (nb <= 64) QG_SCAN_TILE(1);
         else if (nb <= 128) QG_SCAN_TILE(2);
         else QG_SCAN_TILE(4);
@@ -316,28 +316,27 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
         const int per = 8 << glog;
         const int gx = (F + per - 1) / per * per;
         hipLaunchKernelGGL(scan_kernel, dim3(gx, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb,
-                           delta, (int64_t)min_data, min_sum_hess, ctx->cand, glog, mfb);
+                           delta, (int64_t)min_data, min_sum_hess, cand, glog, mfb);
     }
     int gr = F > 256 ? max_items : (max_items + 3) / 4;
     if (gr > 64) gr = 64;
-    hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, ctx->cand, items, n_items, F);
+    hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, cand, items, n_items, F);
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }
 
-// Stand-alone search over n_hists contiguous histograms, in batches of the context's item table.
+// Stand-alone search over n_hists contiguous histograms, in batches of the item table it is given.
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
-                         const float* delta, int min_data, double min_sum_hess, qgbdt_split* out) {
+                         const float* delta, int min_data, double min_sum_hess, qgbdt_split* out, int cap,
+                         ScanItem* items, FeatCand* cand, int32_t* n_items) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     const int64_t W = (int64_t)F * nb;
-    const int cap = 2 * ctx->batch_max;
-    int32_t* n_items = reinterpret_cast<int32_t*>(ctx->tmp_i64);
     for (int h0 = 0; h0 < n_hists; h0 += cap) {
         const int n = (n_hists - h0 < cap) ? (n_hists - h0) : cap;
         hipLaunchKernelGGL(scan_items_from_stats_kernel, dim3((n + 63) / 64), dim3(64), 0, ctx->stream, stats + h0, n,
-                           ctx->scan_items, out + h0, n_items);
-        int rc = launch_scan_items(ctx, const_cast<int64_t*>(hist) + h0 * W, ctx->scan_items, n_items, n, delta,
-                                   min_data, min_sum_hess);
+                           items, out + h0, n_items);
+        int rc = launch_scan_items(ctx, const_cast<int64_t*>(hist) + h0 * W, items, n_items, n, delta,
+                                   min_data, min_sum_hess, cand);
         if (rc != QGBDT_OK) return rc;
     }
     return QGBDT_OK;

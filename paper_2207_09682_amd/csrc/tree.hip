@@ -598,7 +598,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                      ctx->step, mfb);
     if (rc != QGBDT_OK) return rc;
     rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 1, ctx->delta,
-                           p->min_data_in_leaf, p->min_sum_hessian, mfb);
+                           p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
     if (rc != QGBDT_OK) return rc;
 
     const int p_max = ctx->max_nodes + (ctx->max_nodes & 1);  // even: 8-byte arrays follow 4-byte ones
@@ -622,7 +622,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                              ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
             if (rc != QGBDT_OK) return rc;
             rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
-                                   ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, mfb);
+                                   ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
             if (rc != QGBDT_OK) return rc;
         }
         launched += to_launch;
@@ -647,7 +647,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                          ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
         if (rc != QGBDT_OK) return rc;
         rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
-                               ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, mfb);
+                               ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
         if (rc != QGBDT_OK) return rc;
         launched += 1;
         to_launch = 3;
