@@ -49,24 +49,33 @@ def parse():
     return ap.parse_args()
 
 
-def root_pass(ctx, torch, bins, g, h, bits_g, bits_h, cfg, args, iteration, N, F, nb):
-    """Times the histogram build of all rows (quantized (g, h) of one iteration) with HIP events."""
+def root_pass(ctx, torch, bins, g, h, bits_g, bits_h, cfg, args, iteration, N, F, nb, copies=1):
+    """Times the histogram build of all rows (quantized (g, h) of one iteration) with HIP events.
+
+    copies = 1: the same matrix and gradients every repetition (a warm figure when they fit the memory-side
+    cache).  copies > 1: the repetitions rotate over that many distinct copies of the matrix and of the packed
+    gradients, so that a repetition finds nothing of its input in the 256 MB memory-side cache (cold figure)."""
     gh, _ = ctx.quantize_gradients(g, h, bits_g, bits_h, cfg.seed, iteration)
     hist = torch.empty(F * nb, dtype=torch.int64, device=bins.device)
-    for _ in range(3):
-        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    mats = [(bins, gh)] + [(bins.clone(), gh.clone()) for _ in range(copies - 1)]
+    for k in range(3):
+        b_, g_ = mats[k % copies]
+        ctx.build_histograms(b_, g_, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
     torch.cuda.synchronize()
     ctx.set_profiling(True)
     ctx.read_profile()
-    for _ in range(args.root_reps):
-        ctx.build_histograms(bins, gh, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
+    for k in range(args.root_reps):
+        b_, g_ = mats[k % copies]
+        ctx.build_histograms(b_, g_, bits_g=bits_g, bits_h=bits_h, acc_width=args.acc_width, hist_out=hist)
     root_ms, root_n, root_bytes = ctx.read_profile()
     ctx.set_profiling(False)
     avg_ms = root_ms / max(root_n, 1)
     gbs = root_bytes / max(root_n, 1) / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
     return {"avg_launch_us": avg_ms * 1e3, "achieved_GBps": gbs, "frac": gbs / HBM_PEAK_GBS,
             "algorithmic_bytes_per_launch": root_bytes / max(root_n, 1),
-            "rows_x_features_per_s": N * F / (avg_ms * 1e-3) if avg_ms > 0 else 0.0, "reps": root_n}
+            "rows_x_features_per_s": N * F / (avg_ms * 1e-3) if avg_ms > 0 else 0.0, "reps": root_n,
+            "distinct_input_copies": copies,
+            "input_bytes_rotated": copies * (bins.numel() * bins.element_size() + gh.numel() * 2)}
 
 
 def main():
@@ -78,6 +87,7 @@ def main():
     import torch
     import workloads
     from paper_2207_09682_amd import Context
+    from paper_2207_09682_amd import binding as qb
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -92,7 +102,9 @@ def main():
     N = wl.n_rows
     F, nb, L = cfg.n_features, cfg.n_bins, cfg.num_leaves
     bins = wl.bins.contiguous()
-    ctx = Context(N, F, nb, max_leaves=L)
+    # one workspace block, owned here (a torch tensor inside Context): the sections this run uses
+    ws_flags = qb.WS_BOOST | (qb.WS_ROW_COPIES if args.no_bind else qb.WS_BIND)
+    ctx = Context(N, F, nb, max_leaves=L, workspace_flags=ws_flags)
     K, W = args.steps, args.warmup
     sys.stderr.write(f"[bench] workload {cfg.name}: {N} x {F}, {nb} bins, generated in {time.time() - t0:.1f}s\n")
 
@@ -165,6 +177,7 @@ def main():
         stats.append(ctx.tree_stats())
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    in_tree_root_ms, in_tree_root_n = ctx.read_profile_roots()
     hist_ms, hist_launches, hist_bytes = ctx.read_profile()
     ctx.set_profiling(False)
     total_units = int(units.item())
@@ -188,12 +201,30 @@ def main():
 
     # ---- root pass alone (contiguous rows): the kernel at its full-size launch -----------------
     root = root_pass(ctx, torch, bins, gs[W], hs[W], bits_g, bits_h, cfg, args, W, N, F, nb)
+    root["what"] = ("back-to-back repetitions over ONE matrix: a warm figure when matrix + gradients "
+                    f"({(bins.numel() * bins.element_size() + 2 * N) / 1e6:.0f} MB) fit the 256 MB memory-side cache")
+    # the same launch with nothing of its input left in the memory-side cache: rotate over enough distinct copies
+    # of matrix + packed gradients that at least 1.2 GB pass between two reads of the same copy
+    one = bins.numel() * bins.element_size() + 2 * N
+    n_copies = max(2, min(8, -(-1_300_000_000 // one)))
+    root_cold = root_pass(ctx, torch, bins, gs[W], hs[W], bits_g, bits_h, cfg, args, W, N, F, nb, copies=n_copies)
+    root_cold["what"] = f"repetitions rotate over {n_copies} distinct copies of matrix + packed gradients (cold input)"
+    # the root build as it runs inside grow_tree (first histogram launch of every timed tree)
+    root_bytes_alg = N * (F * bins.element_size() + 2) + F * nb * 8
+    rit_us = in_tree_root_ms / max(in_tree_root_n, 1) * 1e3
+    root_in_tree = {"avg_launch_us": rit_us, "launches": in_tree_root_n,
+                    "achieved_GBps": root_bytes_alg / (rit_us * 1e-6) / 1e9 if rit_us > 0 else 0.0,
+                    "algorithmic_bytes_per_launch": root_bytes_alg,
+                    "what": "root build inside grow_tree: HIP events around the first histogram launch "
+                            "(kernel + reduce) of every timed tree"}
+    root_in_tree["frac"] = root_in_tree["achieved_GBps"] / HBM_PEAK_GBS
 
     # ---- measured streaming-read ceiling of this machine: a plain 16-byte-load kernel over 1 GiB ------
     probe = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
     stream_read_gbps = ctx.measure_stream_read(probe, reps=10)
     del probe
-    root["frac_of_measured_stream_read"] = root["achieved_GBps"] / stream_read_gbps if stream_read_gbps > 0 else None
+    for r_ in (root, root_cold, root_in_tree):
+        r_["frac_of_measured_stream_read"] = r_["achieved_GBps"] / stream_read_gbps if stream_read_gbps > 0 else None
 
     # ---- CPU oracle on the same inputs -----------------------------------------------------------
     cpu = None
@@ -226,7 +257,15 @@ def main():
                          f"{c_el:.1f} s", "s_per_tree": c_el / c_trees,
                "library_tree_equals_oracle_tree": bool(c_match)}
 
-    achieved = (hist_bytes / hist_launches) / (hist_ms / hist_launches * 1e-3) / 1e9 if hist_launches and hist_ms > 0 else 0.0
+    # Algorithmic bytes of the timed launches.  The launches also serve speculative builds (nodes expanded ahead of
+    # the sequential order that never become part of the tree); `achieved` counts only the builds the sequential
+    # algorithm performs (the work unit of `value`): the root and the smaller child of every committed split.
+    esz = bins.element_size()
+    committed_builds = sum(x[2] for x in stats) + K
+    rows_committed = total_units // F
+    bytes_committed = K * N * (F * esz + 2) + (rows_committed - K * N) * (F * esz + 2 + 4) + committed_builds * F * nb * 8
+    achieved_all = (hist_bytes / hist_launches) / (hist_ms / hist_launches * 1e-3) / 1e9 if hist_launches and hist_ms > 0 else 0.0
+    achieved = bytes_committed / (hist_ms * 1e-3) / 1e9 if hist_ms > 0 else 0.0
     # HBM bytes per histogram launch from the rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE scaled by a plain
     # copy; see profiles/): measured offline on this workload, so only reported for it
     traffic, root_traffic = None, None
@@ -236,6 +275,7 @@ def main():
             tj = json.load(fh)
         traffic, root_traffic = tj.get("tree_launch_traffic_bytes"), tj.get("root_pass_traffic_bytes")
     root["traffic"] = root_traffic
+    root["traffic_source"] = "rocprofv3 counter runs of another process (profiles/hbm_traffic_cfg3.json), not this run"
     out = {
         "metric": "histogram build rows*features/s over whole trees (quantize+hist+subtract+scan+partition+refit), "
                   f"{bits_g}-bit gradients",
@@ -257,14 +297,23 @@ def main():
                            else "kept in leaf order: every level moves the rows, builds stream contiguous memory"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE runs of another process on this workload "
+                                       "(profiles/hbm_traffic_cfg3.json): an offline counter value, bytes per launch "
+                                       "of one tree; FETCH_SIZE counts L2 misses, which the memory-side cache may serve",
+                     "achieved_incl_speculative_builds": achieved_all,
+                     "frac_incl_speculative_builds": achieved_all / HBM_PEAK_GBS,
                      "kernel": "histogram build = hist_*_kernel + hist_reduce_kernel (all launches of the timed trees)",
                      "launches": hist_launches, "avg_launch_us": hist_ms / max(hist_launches, 1) * 1e3,
-                     "algorithmic_bytes_per_launch": hist_bytes / max(hist_launches, 1),
+                     "algorithmic_bytes_per_launch": bytes_committed / max(hist_launches, 1),
+                     "algorithmic_bytes_per_launch_incl_speculative_builds": hist_bytes / max(hist_launches, 1),
                      "measured_stream_read_GBps": stream_read_gbps,
+                     "measured_stream_read_variant": getattr(ctx, "stream_read_variant", None),
                      # rate of the bytes that actually cross the HBM interface (counter runs): what the gathered
                      # builds are bound by -- a 128-byte line per sparse 28-byte row
-                     "traffic_GBps": (traffic / (hist_ms / hist_launches * 1e-3) / 1e9) if (traffic and hist_launches and hist_ms > 0) else None},
+                     "offline_traffic_over_this_runs_launch_time_GBps": (traffic / (hist_ms / hist_launches * 1e-3) / 1e9) if (traffic and hist_launches and hist_ms > 0) else None},
         "root_pass": root,
+        "root_pass_cold": root_cold,
+        "root_pass_in_tree": root_in_tree,
         "hist_time_share": hist_ms / (elapsed * 1e3),
         "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,
                    "committed_per_tree": sum(x[2] for x in stats) / K},

@@ -309,6 +309,12 @@ QGBDT_API int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on);
 QGBDT_API int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches,
                        double* hist_bytes);
 
+/* Of the launches timed since the last qgbdt_read_profile: the summed time (ms) and the number of those that
+ * were a tree's root build inside qgbdt_grow_tree (all rows, contiguous; its algorithmic bytes are
+ * n_rows * (n_features * bin_bytes + 2) + n_features * n_bins * 8 per launch).  Synchronises the stream; resets
+ * nothing, so call it before qgbdt_read_profile.  Host out pointers. */
+QGBDT_API int qgbdt_read_profile_roots(qgbdt_ctx* ctx, double* root_ms, int64_t* root_launches);
+
 /* Figures of the last grow_tree call on this context (host out int32[4]): rounds of
  * batched expansion, nodes expanded (committed splits plus speculative ones), committed
  * splits, nodes created.  For callers that time or tune; no paper quantity. */
@@ -316,10 +322,14 @@ QGBDT_API int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4);
 
 /* Streaming-read rate of this device as a plain kernel reaches it: `buf` (dev, 16-byte aligned, `bytes` a
  * multiple of 16, at least 16) is read `reps` times with 16-byte loads by one grid-stride kernel per repetition,
- * timed with HIP events on the context's stream after one untimed repetition.  gbps_out (host) = bytes * reps
- * / time in GB/s.  Synchronous.  The measured ceiling that the histogram kernels' rates are set against beside
- * the published peak; no paper quantity. */
-QGBDT_API int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out);
+ * timed with HIP events on the context's stream after one untimed repetition -- for every combination of 4, 8 or
+ * 16 loads in flight per thread, 4 to 32 workgroups of 256 threads per compute unit, and plain or non-temporal
+ * loads; the best rate is returned.  gbps_out (host) = bytes * reps / time in GB/s; variant_out (host int32[3],
+ * may be NULL) = loads in flight, workgroups and 1 for non-temporal loads of the best run.  Synchronous.  The
+ * measured ceiling that the histogram kernels' rates are set against beside the published peak; no paper
+ * quantity. */
+QGBDT_API int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out,
+                              int32_t* variant_out);
 
 #ifdef __cplusplus
 }

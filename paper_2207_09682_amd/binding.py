@@ -29,7 +29,7 @@ EXPORTS = [
     "qgbdt_find_best_splits", "qgbdt_find_best_splits_static", "qgbdt_partition_rows", "qgbdt_refit_leaves", "qgbdt_grow_tree",
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_boost_iteration_lambdarank",
-    "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_tree_stats", "qgbdt_bind_bins",
+    "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_read_profile_roots", "qgbdt_tree_stats", "qgbdt_bind_bins",
     "qgbdt_measure_stream_read",
 ]
 
@@ -96,9 +96,11 @@ def load_library() -> C.CDLL:
                                               C.c_uint32, C.c_double, C.POINTER(TreePtrs), C.c_void_p]
         lib.qgbdt_set_profiling.argtypes = [C.c_void_p, C.c_int32]
         lib.qgbdt_read_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        lib.qgbdt_read_profile_roots.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.qgbdt_tree_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         lib.qgbdt_bind_bins.argtypes = [C.c_void_p, C.c_void_p]
-        lib.qgbdt_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
+        lib.qgbdt_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_double),
+                                                  C.POINTER(C.c_int32)]
         _lib = lib
     return _lib
 
@@ -193,8 +195,6 @@ class Context:
         self.workspace = workspace
         self.workspace_flags = flags
 
-    def bind_bins(self, bins: torch.Tensor | None) -> None:
-        """qgbdt_bind_bins: keep a feature-major copy of `bins` for the partitions of the trees that follow
     def detach_workspace(self):
         """qgbdt_set_workspace(NULL): the context gives its block back; every step but the ones that need no
         workspace refuses until another block is set."""
@@ -203,6 +203,8 @@ class Context:
         self.workspace = None
         self.workspace_flags = 0
 
+    def bind_bins(self, bins: torch.Tensor | None) -> None:
+        """qgbdt_bind_bins: keep a feature-major copy of `bins` for the partitions of the trees that follow
         (None forgets it).  The tensor must stay alive and unchanged while it is bound."""
         self._chk(self.lib.qgbdt_bind_bins(self._h, C.c_void_p(self._bins(bins)) if bins is not None else None))
 
@@ -278,8 +280,6 @@ class Context:
                                                   min_data_in_leaf, min_sum_hessian, out.data_ptr()))
         return out
 
-    def partition_rows(self, bins, row_idx, begin, count, feature, bin):
-        self._sync_stream()
     def find_best_splits_static(self, hist, stats, delta, out, min_data_in_leaf=20, min_sum_hessian=0.0):
         """qgbdt_find_best_splits_static: the same search with the library's fixed scratch; allocates nothing, so
         the caller passes `out` (uint8 [n, 56])."""
@@ -291,6 +291,8 @@ class Context:
                                                          min_sum_hessian, _dev(out, torch.uint8, "out")))
         return out
 
+    def partition_rows(self, bins, row_idx, begin, count, feature, bin):
+        self._sync_stream()
         n_left = torch.empty(1, dtype=torch.int64, device=self.device)
         self._chk(self.lib.qgbdt_partition_rows(self._h, self._bins(bins),
                                                 _dev(row_idx, torch.int32, "row_idx"), begin, count, feature, bin,
@@ -386,6 +388,12 @@ class Context:
     def set_profiling(self, on: bool):
         self._chk(self.lib.qgbdt_set_profiling(self._h, 1 if on else 0))
 
+    def read_profile_roots(self):
+        """(ms, launches) of the timed launches that were a tree's root build; call before read_profile."""
+        ms = C.c_double(0); n = C.c_int64(0)
+        self._chk(self.lib.qgbdt_read_profile_roots(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
     def read_profile(self):
         ms = C.c_double(0); n = C.c_int64(0); b = C.c_double(0)
         self._chk(self.lib.qgbdt_read_profile(self._h, C.byref(ms), C.byref(n), C.byref(b)))
@@ -399,7 +407,10 @@ def _measure_stream_read(self, buf: torch.Tensor, reps: int = 10) -> float:
         raise ValueError("buf must be a contiguous device tensor")
     nbytes = buf.numel() * buf.element_size() // 16 * 16
     out = C.c_double(0)
-    self._chk(self.lib.qgbdt_measure_stream_read(self._h, C.c_void_p(buf.data_ptr()), C.c_int64(nbytes), int(reps), C.byref(out)))
+    var = (C.c_int32 * 3)()
+    self._chk(self.lib.qgbdt_measure_stream_read(self._h, C.c_void_p(buf.data_ptr()), C.c_int64(nbytes), int(reps),
+                                                 C.byref(out), var))
+    self.stream_read_variant = {"loads_in_flight": int(var[0]), "workgroups": int(var[1]), "non_temporal": bool(var[2])}
     return out.value
 
 

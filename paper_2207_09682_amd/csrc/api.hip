@@ -180,6 +180,7 @@ static void free_host(qgbdt_ctx* c) {
         for (int i = 0; i < c->ev_cap; ++i)
             if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
         delete[] c->ev;
+        delete[] c->ev_root;
     }
 }
 
@@ -205,15 +206,29 @@ using namespace qgbdt;
 
 namespace qgbdt {
 
-// Plain streaming read: four 16-byte loads per thread and step; the loaded values are folded into a word that is
-// stored only if it takes one particular value, which keeps the loads alive.
+// Plain streaming read: U 16-byte loads per thread in flight per step, grid-stride; the loaded values are folded
+// into a word that is stored only if it takes one particular value, which keeps the loads alive.  NT: loads
+// marked non-temporal.
+template <int U, bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, int64_t n16, uint32_t* sink) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     uint32_t acc = 0u;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (NT) {
+                const uint32_t* q = reinterpret_cast<const uint32_t*>(p + i + u * stride);
+                typedef uint32_t v4 __attribute__((ext_vector_type(4)));
+                const v4 t = __builtin_nontemporal_load(reinterpret_cast<const v4*>(q));
+                v[u] = make_uint4(t.x, t.y, t.z, t.w);
+            } else {
+                v[u] = p[i + u * stride];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n16; i += stride) {
         const uint4 a = p[i];
@@ -259,6 +274,17 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return set_error(nullptr, QGBDT_E_HIP, "hipGetDevice failed"); }
     derive_sizes(c);
     c->rounds_hint = 10;
+    if (c->device >= 0 && c->device < STATIC_SCRATCH_DEVICES) {
+        if (!g_static_scratch_ptr[c->device]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) {
+                delete c;
+                return set_error(nullptr, QGBDT_E_HIP, "hipGetSymbolAddress of the fixed scratch array failed");
+            }
+            g_static_scratch_ptr[c->device] = p;
+        }
+        c->static_scratch = g_static_scratch_ptr[c->device];
+    }
     if (hipHostMalloc(reinterpret_cast<void**>(&c->host_state), sizeof(StepState), hipHostMallocDefault) != hipSuccess)
         rc = set_error(c, QGBDT_E_ALLOC, "hipHostMalloc failed");
     // kernels whose local bins or bookkeeping exceed the default limit of dynamic LDS are told so once
@@ -274,17 +300,6 @@ int qgbdt_create(qgbdt_ctx** out, const qgbdt_shape* shape, void* stream) {
     return QGBDT_OK;
 }
 
-    if (c->device >= 0 && c->device < STATIC_SCRATCH_DEVICES) {
-        if (!g_static_scratch_ptr[c->device]) {
-            void* p = nullptr;
-            if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) {
-                delete c;
-                return set_error(nullptr, QGBDT_E_HIP, "hipGetSymbolAddress of the fixed scratch array failed");
-            }
-            g_static_scratch_ptr[c->device] = p;
-        }
-        c->static_scratch = g_static_scratch_ptr[c->device];
-    }
 int qgbdt_destroy(qgbdt_ctx* ctx) {
     if (!ctx) return QGBDT_OK;
     (void)hipStreamSynchronize(ctx->stream);
@@ -601,8 +616,28 @@ int qgbdt_set_profiling(qgbdt_ctx* ctx, int32_t on) {
         ctx->ev = new (std::nothrow) hipEvent_t[ctx->ev_cap];
         if (!ctx->ev) { ctx->ev_cap = 0; return set_error(ctx, QGBDT_E_ALLOC, "out of host memory"); }
         memset(ctx->ev, 0, sizeof(hipEvent_t) * ctx->ev_cap);
+        ctx->ev_root = new (std::nothrow) unsigned char[ctx->ev_cap / 2];
+        if (!ctx->ev_root) { delete[] ctx->ev; ctx->ev = nullptr; ctx->ev_cap = 0; return set_error(ctx, QGBDT_E_ALLOC, "out of host memory"); }
+        memset(ctx->ev_root, 0, ctx->ev_cap / 2);
     }
     ctx->profiling = on ? 1 : 0;
+    return QGBDT_OK;
+}
+
+int qgbdt_read_profile_roots(qgbdt_ctx* ctx, double* root_ms, int64_t* root_launches) {
+    if (!ctx || !root_ms || !root_launches) return QGBDT_E_INVALID_ARG;
+    QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double ms = 0.0;
+    int64_t n = 0;
+    for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
+        if (!ctx->ev_root[i / 2]) continue;
+        float t = 0.0f;
+        QG_HIP(ctx, hipEventElapsedTime(&t, ctx->ev[i], ctx->ev[i + 1]));
+        ms += t;
+        n += 1;
+    }
+    *root_ms = ms;
+    *root_launches = n;
     return QGBDT_OK;
 }
 
@@ -629,32 +664,53 @@ int qgbdt_read_profile(qgbdt_ctx* ctx, double* hist_ms, int64_t* hist_launches, 
     return QGBDT_OK;
 }
 
-int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out) {
+int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, int32_t reps, double* gbps_out,
+                              int32_t* variant_out) {
     if (!ctx) return QGBDT_E_INVALID_ARG;
     if (!buf || !gbps_out) return set_error(ctx, QGBDT_E_INVALID_ARG, "null pointer");
+    if (int rcw = require_workspace(ctx)) return rcw;
     if (((uintptr_t)buf & 15) != 0 || bytes < 16 || (bytes & 15) != 0 || reps < 1)
         return set_error(ctx, QGBDT_E_INVALID_ARG, "buf must be 16-byte aligned, bytes a positive multiple of 16, reps >= 1");
     const int64_t n16 = bytes / 16;
-    int64_t blocks = (n16 + 4 * 256 - 1) / (4 * 256);
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (blocks < 1) blocks = 1;
     hipEvent_t e0, e1;
     QG_HIP(ctx, hipEventCreate(&e0));
     QG_HIP(ctx, hipEventCreate(&e1));
     uint32_t* sink = reinterpret_cast<uint32_t*>(ctx->tmp_i64 + 7);
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const uint4*)buf, n16, sink);
-    hipError_t e = hipEventRecord(e0, ctx->stream);
-    for (int r = 0; r < reps && e == hipSuccess; ++r)
-        hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const uint4*)buf, n16, sink);
-    if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    float ms = 0.0f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e == hipSuccess) e = hipGetLastError();
+    double best = 0.0;
+    int bu = 0, bg = 0, bn = 0;
+    hipError_t e = hipSuccess;
+    // loads in flight per thread x workgroups per CU x plain / non-temporal loads; the best rate is the ceiling
+    for (int nt = 0; nt < 2 && e == hipSuccess; ++nt)
+        for (int u = 4; u <= 16 && e == hipSuccess; u *= 2)
+            for (int per_cu = 4; per_cu <= 32 && e == hipSuccess; per_cu *= 2) {
+                int64_t blocks = (n16 + (int64_t)u * 256 - 1) / ((int64_t)u * 256);
+                if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+                if (blocks < 1) blocks = 1;
+                const dim3 grid((unsigned)blocks), block(256);
+#define QG_SR(U_, NT_) hipLaunchKernelGGL((stream_read_kernel<U_, NT_>), grid, block, 0, ctx->stream, (const uint4*)buf, n16, sink)
+#define QG_SR_ANY()                                                                  \
+    do {                                                                             \
+        if (nt) { if (u == 4) QG_SR(4, true); else if (u == 8) QG_SR(8, true); else QG_SR(16, true); }   \
+        else    { if (u == 4) QG_SR(4, false); else if (u == 8) QG_SR(8, false); else QG_SR(16, false); } \
+    } while (0)
+                QG_SR_ANY();  // untimed
+                e = hipEventRecord(e0, ctx->stream);
+                for (int r = 0; r < reps && e == hipSuccess; ++r) QG_SR_ANY();
+#undef QG_SR_ANY
+#undef QG_SR
+                if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+                if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+                float ms = 0.0f;
+                if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+                if (e == hipSuccess) e = hipGetLastError();
+                const double gbps = ms > 0.0f ? (double)bytes * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
+                if (gbps > best) { best = gbps; bu = u; bg = (int)blocks; bn = nt; }
+            }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (e != hipSuccess) return set_error(ctx, QGBDT_E_HIP, "stream read measurement failed: %s", hipGetErrorString(e));
-    *gbps_out = ms > 0.0f ? (double)bytes * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
+    *gbps_out = best;
+    if (variant_out) { variant_out[0] = bu; variant_out[1] = bg; variant_out[2] = bn; }
     return QGBDT_OK;
 }
 

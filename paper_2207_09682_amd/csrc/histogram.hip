@@ -961,9 +961,11 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     if (ctx->profiling && ctx->ev_used + 2 <= ctx->ev_cap) {
         for (int k = 0; k < 2; ++k)
             if (!ctx->ev[ctx->ev_used + k]) QG_HIP(ctx, hipEventCreate(&ctx->ev[ctx->ev_used + k]));
+        ctx->ev_root[ctx->ev_used / 2] = ctx->next_hist_is_root ? 1 : 0;
         e0 = ctx->ev[ctx->ev_used++]; e1 = ctx->ev[ctx->ev_used++];
         QG_HIP(ctx, hipEventRecord(e0, ctx->stream));
     }
+    ctx->next_hist_is_root = 0;
     const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_ok;
     bool wide_ok = true;  // 16-byte loads need 16-byte aligned matrices (F is a multiple of 16 in that mode)
     for (int b = 0; b < 4; ++b) wide_ok = wide_ok && (((uintptr_t)rows.bins[b] & 15) == 0);

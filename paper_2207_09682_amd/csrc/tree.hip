@@ -592,6 +592,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                        ctx->hist_pool, W, root_plan);
+    ctx->next_hist_is_root = 1;
     rc = launch_hist(ctx, root_plan, rows, idxs, false, ((uintptr_t)bins & 15) == 0,
                      ctx->hist_entries, ctx->hist_counts, ctx->hist_pool,
                      (N + hist_target_rows(root_plan, N, 1) - 1) / hist_target_rows(root_plan, N, 1),  // the build's row groups
