@@ -172,6 +172,9 @@ __device__ __forceinline__ void store_partial(typename Acc<W>::word* lds, int ld
 // unaligned, and the last dword of a tile row is moved back to end with the tile row (it then
 // overlaps its neighbour and only its upper bytes count), so that no load leaves the row.
 // Tiles are at least 4 features wide in this mode.
+//
+// BB = 2 (16-bit bins, up to 1024 per feature): the same kernel with two bins per dword; "ragged" then means an odd
+// feature count (rows start at odd multiples of 2 bytes).
 template <bool RAG>
 __device__ __forceinline__ uint32_t load_bins4(const uint8_t* p) {
     if (RAG) {
@@ -182,13 +185,14 @@ __device__ __forceinline__ uint32_t load_bins4(const uint8_t* p) {
     return *reinterpret_cast<const uint32_t*>(p);
 }
 
-template <int W, bool IDX, int U, bool RAG>
+template <int W, bool IDX, int U, bool RAG, int BB>
 __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSource src, IdxSet idxs,
                                                     const HistEntry* __restrict__ entries,
                                                     const int32_t* __restrict__ table_counts, int64_t* hist_base,
                                                     unsigned char* partials, int F, int nb, HistPlan plan,
                                                     StepState* step) {
     using word = typename Acc<W>::word;
+    constexpr int NPD = 4 / BB;  // bins per dword
     extern __shared__ unsigned char lds_raw[];
     word* lds = reinterpret_cast<word*>(lds_raw);
 
@@ -211,22 +215,23 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
     const int n_waves = blockDim.x >> 6;
     const int rpi = plan.rows_per_it;
     int q = lane % plan.dpr, r = lane / plan.dpr;
-    const bool lane_on = (r < rpi) && (4 * q < ft);
+    const bool lane_on = (r < rpi) && (NPD * q < ft);
     if (!lane_on) { q = 0; r = 0; }
     const int rot = (q >> 3) + r;
-    const int nval = RAG ? min(4, ft - 4 * q) : 4;  // features in the lane's dword
-    const int back = 4 - nval;                      // bytes its load is moved back
-    uint32_t sh[4], fl4[4];  // bit offset of the k-th bin in the dword, byte offset of its feature column in LDS
-    bool okk[4];
+    const int nval = RAG ? min(NPD, ft - NPD * q) : NPD;  // features in the lane's dword
+    const int back = NPD - nval;                          // bins its load is moved back
+    uint32_t sh[NPD], fl4[NPD];  // bit offset of the k-th bin in the dword, byte offset of its feature column in LDS
+    bool okk[NPD];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int c = (k + rot) & 3;
+    for (int k = 0; k < NPD; ++k) {
+        const int c = (k + rot) & (NPD - 1);
         okk[k] = c < nval;
-        sh[k] = 8 * (okk[k] ? c + back : 0);
-        fl4[k] = (uint32_t)(4 * q + (okk[k] ? c : 0) + (plan.pad16 ? 4 * (q >> 2) : 0)) * (uint32_t)sizeof(word);
+        sh[k] = 8 * BB * (okk[k] ? c + back : 0);
+        fl4[k] = (uint32_t)(NPD * q + (okk[k] ? c : 0) + (plan.pad16 ? 4 * (q >> 2) : 0)) * (uint32_t)sizeof(word);
     }
     const uint32_t pitch = (uint32_t)ftp * (uint32_t)sizeof(word);  // LDS bytes per bin row
     const int S = U * rpi;                                          // rows per block of one wavefront
+    const int64_t row_bytes = (int64_t)F * BB;
 
     for (int item = glane; item < n_items; item += n_lanes) {
         const HistEntry en = entries[find_entry(entries, n_entries, item)];
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
         const int32_t* idx = IDX ? (idxs.p[en.buf] + en.begin) : nullptr;
         // gathered rows are read from the original arrays, contiguous ones from the entry's buffer
         const int sb = IDX ? BUF_ORIGINAL : en.buf;
-        const uint8_t* colbase = src.bins[sb] + f0 + 4 * q - back;
+        const uint8_t* colbase = src.bins[sb] + (f0 + NPD * q - back) * BB;
         const bool gpos = IDX && src.gh_pos != 0;  // packed gradients in list order
         const int16_t* gh = gpos ? src.gh[en.buf] + en.begin : src.gh[sb];
 
@@ -264,7 +269,7 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        d[u] = load_bins4<RAG>(colbase + rows[u] * F);
+                        d[u] = load_bins4<RAG>(colbase + rows[u] * row_bytes);
                         gv[u] = gh[gpos ? cbegin + min(wave * S + u * rpi + r, crow - 1) : rows[u]];
                     }
 #pragma unroll
@@ -276,7 +281,7 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
                 for (int ro = wave * S; ro < crow; ro += n_waves * S) {
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        dn[u] = load_bins4<RAG>(colbase + rown[u] * F);
+                        dn[u] = load_bins4<RAG>(colbase + rown[u] * row_bytes);
                         gn[u] = gh[gpos ? cbegin + min(ro + n_waves * S + u * rpi + r, crow - 1) : rown[u]];
                     }
 #pragma unroll
@@ -292,8 +297,8 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
                             const bool ok = ro + u * rpi + r < crow;
                             const word v = Acc<W>::expand(ok ? gv[u] : 0, hmul);
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) {
-                                const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u);
+                            for (int k = 0; k < NPD; ++k) {
+                                const uint32_t b = __builtin_amdgcn_ubfe(d[u], sh[k], 8u * BB);
                                 if (!RAG || okk[k])
                                     Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[k])), v);
                             }
@@ -769,11 +774,12 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     if (w == 0) w = (n16 >= 4096) ? 16 : 32;
     const int wbytes = (w == 16) ? 4 : 8;
     const int lds_budget = 64 * 1024;
-    const bool aligned = (F % 4 == 0);
-    // dword kernels: 8-bit bins, rows of any width >= 4 bytes (unaligned loads when not a multiple of 4)
-    bool fast = s.bin_bytes == 1 && (aligned || F >= 4);
+    const int npd = 4 / s.bin_bytes;  // bins per dword
+    const bool aligned = (F % npd == 0);
+    // dword kernels: rows of any width >= 4 bytes (unaligned loads when not a multiple of 4 bytes)
+    bool fast = aligned || F >= npd;
     int wide_ft = 0;
-    if (!fast) {
+    if (!fast || s.bin_bytes != 1) {
     } else if (F % 16 == 0 && F > 64) {
         // wide rows: 16-byte pieces, padded local bins (20 words per 16 features)
         for (int ft = 256; ft >= 32 && !wide_ft; ft >>= 1)
@@ -799,29 +805,32 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     } else if (fast) {
         // candidates in order of preference: the whole row when it is narrow, then wide tiles
         // (whole cache lines per row), small tiles only when nothing else fits the LDS budget
-        const int cands[] = {(F <= 64) ? F : 0, 128, 96, 64, 48, 40, 32, 24, 16, 8, 4};
+        // (8-bit bins: tiles of at most 32 features get a pitch of 32 words, so that the LDS bank is the feature;
+        // 16-bit bins have up to 1024 bin rows, a pitch of the tile width rounded up to 4 words lets wider tiles fit)
+        const int cands[] = {(F <= 64) ? F : 0, 128, 96, 64, 48, 40, 32, 24, 16, 12, 8, 6, 4, 2};
+        auto pitch_of = [&](int ft) { return (s.bin_bytes == 1 && ft <= 32) ? 32 : (ft + 3) / 4 * 4; };
         int best_ft = 0;
         for (int pass = 0; pass < 2 && best_ft == 0; ++pass) {
             double best_score = -1.0;
-            for (int c = 0; c < 11; ++c) {
+            for (int c = 0; c < 14; ++c) {
                 const int ft = cands[c];
-                if (ft <= 0 || ft > F || (ft % 4 && ft != F)) continue;
+                if (ft <= 0 || ft > F || (ft % npd && ft != F)) continue;
                 if (pass == 0 && ft < 32 && ft != F) continue;
-                const int ftp = (ft <= 32) ? 32 : (ft + 3) / 4 * 4;
-                if ((int64_t)ftp * nb * wbytes > lds_budget) continue;
-                const int dpr = (ft + 3) / 4;
+                if ((int64_t)pitch_of(ft) * nb * wbytes > lds_budget) continue;
+                const int dpr = (ft + npd - 1) / npd;
+                if (dpr > 64) continue;
                 const int rpi = 64 / dpr;
                 const int tiles = (F + ft - 1) / ft;
-                if (F - (tiles - 1) * ft < 4) continue;  // every tile row holds at least one dword
+                if (F - (tiles - 1) * ft < npd) continue;  // every tile row holds at least one dword
                 const double score = ((double)(rpi * dpr) / 64.0) * ((double)F / ((double)tiles * ft));
                 if (score > best_score + 1e-9) { best_score = score; best_ft = ft; }
             }
         }
-        if (best_ft == 0 && aligned) best_ft = 4;
+        if (best_ft == 0 && aligned && (int64_t)pitch_of(npd) * nb * wbytes <= lds_budget) best_ft = npd;
         if (best_ft == 0) fast = false;
         p.ft = best_ft;
-        p.ftp = (best_ft <= 32) ? 32 : (best_ft + 3) / 4 * 4;
-        p.dpr = (best_ft + 3) / 4;
+        p.ftp = pitch_of(best_ft > 0 ? best_ft : 1);
+        p.dpr = (best_ft + npd - 1) / npd;
         p.rows_per_it = p.dpr > 0 ? 64 / p.dpr : 0;
         p.lds_bytes = p.ftp * nb * wbytes;
     }
@@ -861,7 +870,7 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
     p.ragged = (fast && !aligned) ? 1 : 0;
     p.bytewise = fast ? 0 : 1;
     p.flat_lanes = 0; p.flat_rows = 0;
-    if (fast && aligned && p.n_tiles == 1 && F >= 16 && F <= 64) {
+    if (fast && aligned && s.bin_bytes == 1 && p.n_tiles == 1 && F >= 16 && F <= 64) {
         for (int l = 64; l >= 32; --l)
             if ((16 * l) % F == 0) { p.flat_lanes = l; p.flat_rows = 16 * l / F; break; }
     }
@@ -1006,15 +1015,16 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     } else if (fast) {
         const int cap = 64 / plan.rows_per_it;
         const int U = cap >= 8 ? 8 : cap >= 7 ? 7 : cap >= 4 ? 4 : cap >= 2 ? 2 : 1;
+#define QG_LAUNCH_HIST_K(W_, IDX_, U_, RAG_, BB_)                                                                  \
+    hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_, RAG_, BB_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx,   \
+                       entries, table_counts, hist_base, partials, F, nb, plan, step)
 #define QG_LAUNCH_HIST(W_, IDX_, U_)                                                                               \
     do {                                                                                                           \
-        if (plan.ragged)                                                                                           \
-            hipLaunchKernelGGL((hist_kernel<W_, IDX_, (U_ > 4 ? 4 : U_), true>), grid, block, plan.lds_bytes,      \
-                               ctx->stream, rows, idx, entries, table_counts, hist_base, partials, F, nb, plan,    \
-                               step);                                                                              \
-        else                                                                                                       \
-            hipLaunchKernelGGL((hist_kernel<W_, IDX_, U_, false>), grid, block, plan.lds_bytes, ctx->stream, rows, \
-                               idx, entries, table_counts, hist_base, partials, F, nb, plan, step);                \
+        if (ctx->shape.bin_bytes == 2) {                                                                           \
+            if (plan.ragged) QG_LAUNCH_HIST_K(W_, IDX_, (U_ > 4 ? 4 : U_), true, 2);                               \
+            else QG_LAUNCH_HIST_K(W_, IDX_, (U_ > 4 ? 4 : U_), false, 2);                                          \
+        } else if (plan.ragged) QG_LAUNCH_HIST_K(W_, IDX_, (U_ > 4 ? 4 : U_), true, 1);                            \
+        else QG_LAUNCH_HIST_K(W_, IDX_, U_, false, 1);                                                             \
     } while (0)
 #define QG_LAUNCH_HIST_U(W_, IDX_)                                                      \
     switch (U) {                                                                        \
@@ -1031,6 +1041,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         }
 #undef QG_LAUNCH_HIST_U
 #undef QG_LAUNCH_HIST
+#undef QG_LAUNCH_HIST_K
     } else {
 #define QG_LAUNCH_GENERIC(W_, BIN_)                                                                              \
     hipLaunchKernelGGL((hist_generic_kernel<W_, BIN_>), grid, block, plan.lds_bytes, ctx->stream, rows, idx, \
