@@ -30,7 +30,7 @@ EXPORTS = [
     "qgbdt_logistic_gradients", "qgbdt_lambdarank_gradients", "qgbdt_update_scores", "qgbdt_boost_iteration",
     "qgbdt_boost_iteration_lambdarank",
     "qgbdt_set_profiling", "qgbdt_read_profile", "qgbdt_read_profile_roots", "qgbdt_tree_stats", "qgbdt_bind_bins",
-    "qgbdt_measure_stream_read",
+    "qgbdt_measure_stream_read", "qgbdt_describe_hist_plan",
 ]
 
 
@@ -101,8 +101,27 @@ def load_library() -> C.CDLL:
         lib.qgbdt_bind_bins.argtypes = [C.c_void_p, C.c_void_p]
         lib.qgbdt_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_double),
                                                   C.POINTER(C.c_int32)]
+        lib.qgbdt_describe_hist_plan.argtypes = [C.POINTER(Shape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                                 C.c_int32, C.POINTER(C.c_int64), C.c_int32]
         _lib = lib
     return _lib
+
+
+PLAN_FIELDS = ("ft", "ftp", "dpr", "rows_per_it", "n_tiles", "threads", "lds_bytes", "chunk_rows", "max_groups",
+               "max_lanes", "min_rows_per_group", "acc_width", "hshift", "flat_lanes", "flat_rows", "max_items",
+               "slot_bytes", "single_rows", "pad16", "wide_v", "ragged", "bytewise", "target_rows", "partial_bytes")
+
+
+def describe_hist_plan(n_rows, n_features, n_bins, max_leaves=255, bin_bytes=1, bits_g=3, bits_h=3, acc_width=0,
+                       skewed=False, rows=0, n_builds=1) -> dict:
+    """qgbdt_describe_hist_plan: the histogram launch plan of a shape as a dict (host-only, needs no GPU)."""
+    lib = load_library()
+    shape = Shape(n_rows, n_features, n_bins, bin_bytes, max_leaves)
+    out = (C.c_int64 * 24)()
+    rc = lib.qgbdt_describe_hist_plan(C.byref(shape), bits_g, bits_h, acc_width, 1 if skewed else 0, rows, n_builds, out, 24)
+    if rc != 0:
+        raise QgbdtError(rc, lib.qgbdt_last_error(None).decode())
+    return dict(zip(PLAN_FIELDS, (int(x) for x in out)))
 
 
 class QgbdtError(RuntimeError):

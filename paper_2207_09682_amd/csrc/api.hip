@@ -714,6 +714,26 @@ int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, in
     return QGBDT_OK;
 }
 
+int qgbdt_describe_hist_plan(const qgbdt_shape* shape, int32_t bits_g, int32_t bits_h, int32_t acc_width, int32_t skewed,
+                             int64_t rows, int32_t n_builds, int64_t* out, int32_t n_out) {
+    if (!out || n_out < 24) return set_error(nullptr, QGBDT_E_INVALID_ARG, "out must hold 24 values");
+    int rc = check_shape(shape);
+    if (rc != QGBDT_OK) return rc;
+    if (bits_g < 2 || bits_g > 8 || !(bits_h == 0 || (bits_h >= 2 && bits_h <= 8)) ||
+        (acc_width != 0 && acc_width != 16 && acc_width != 32) || rows < 0 || n_builds < 1)
+        return set_error(nullptr, QGBDT_E_INVALID_ARG, "bits, acc_width, rows or n_builds out of range");
+    // rows > 0 with one build: the plan of a stand-alone build of that many rows (the width may fall back to 64-bit
+    // words); else the plan of the batched launches of a tree
+    const HistPlan p = (n_builds == 1 && rows > 0) ? make_hist_plan_for(*shape, bits_g, bits_h, acc_width, rows, skewed != 0)
+                                                   : make_hist_plan(*shape, bits_g, bits_h, acc_width, skewed != 0);
+    const int64_t v[24] = {p.ft, p.ftp, p.dpr, p.rows_per_it, p.n_tiles, p.threads, p.lds_bytes, p.chunk_rows,
+                           p.max_groups, p.max_lanes, p.min_rows_per_group, p.acc_width, p.hshift, p.flat_lanes,
+                           p.flat_rows, p.max_items, p.slot_bytes, p.single_rows, p.pad16, p.wide_v, p.ragged,
+                           p.bytewise, hist_target_rows(p, rows, n_builds), (int64_t)partial_slot_bytes(*shape)};
+    for (int i = 0; i < 24; ++i) out[i] = v[i];
+    return QGBDT_OK;
+}
+
 int qgbdt_tree_stats(const qgbdt_ctx* ctx, int32_t* out4) {
     if (!ctx || !out4 || !ctx->host_state) return QGBDT_E_INVALID_ARG;
     out4[0] = ctx->host_state->rounds; out4[1] = ctx->host_state->n_expanded;
