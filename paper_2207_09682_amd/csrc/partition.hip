@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, c
         const int feature = nd.best.feature, bin = nd.best.bin;
         int cnt = 0;
         for (int64_t p = sbegin + threadIdx.x; p < send; p += blockDim.x) {
-            const int64_t row = ordered ? p : (int64_t)src[p];
+            const int64_t row = (ordered || nd.buf == BUF_ORIGINAL) ? p : (int64_t)src[p];  // the root's list is the identity
             const int fl = (col ? bin_at(col, row, bb) : bin_at(brow, row * F + feature, bb)) <= bin;
             flags[nd.begin + p] = (uint8_t)fl;
             cnt += fl;
@@ -252,6 +252,7 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
         const BatchEntry be = batch[find_batch(batch, n_batch, item)];
         const Node nd = nodes[be.node];
         const int cbuf = child_buffer(nd.buf);
+        const bool identity = nd.buf == BUF_ORIGINAL;  // the root's list: row id = position, never stored
         const int32_t* src = idxs.p[nd.buf] + nd.begin;
         int32_t* dst = idxs.p[cbuf] + nd.begin;
         const int16_t* gsrc = MODE >= 1 ? rows.gh[nd.buf] + nd.begin : nullptr;
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
             fl[u] = 0; v[u] = 0; g16[u] = 0;
             if (r < n) {
                 fl[u] = flags[nd.begin + sbegin + r];
-                v[u] = src[sbegin + r];
+                v[u] = identity ? (int32_t)(nd.begin + sbegin + r) : src[sbegin + r];
                 if (MODE >= 1) g16[u] = gsrc[sbegin + r];
             }
         }

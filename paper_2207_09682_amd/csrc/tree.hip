@@ -45,14 +45,13 @@ __device__ __forceinline__ int hist_groups(int64_t count, const HistPlan& plan) 
     return (int)g;
 }
 
-__global__ __launch_bounds__(256) void tree_init_kernel(int32_t* idx0, int64_t N, int F, StepState* step, Node* nodes,
+__global__ __launch_bounds__(256) void tree_init_kernel(int64_t N, int F, StepState* step, Node* nodes,
                                                         const int64_t* qtotals, int root_buf, HistEntry* hist_entries,
                                                         int32_t* hist_counts, ScanItem* items,
                                                         int64_t* hist0, int64_t hist_words, HistPlan plan) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (int64_t i = t; i < N; i += stride) idx0[i] = (int32_t)i;
-    for (int64_t i = t; i < hist_words; i += stride) hist0[i] = 0;
+    for (int64_t i = t; i < hist_words; i += stride) hist0[i] = 0;  // (the root's row list is the identity: never stored)
     if (t == 0) {
         step->done = 0; step->n_sorted = 0; step->n_nodes = 1; step->n_leaves = 1; step->n_commits = 0; step->n_expanded = 0;
         step->n_slots = 1; step->n_batch = 0; step->rounds = 0; step->n_part_items = 0; step->n_scan_items = 1;
@@ -503,8 +502,9 @@ __global__ __launch_bounds__(256) void tree_gather_rows_kernel(const StepState* 
     if (l >= step->n_leaves) return;
     const Node S = nodes[leaf_node[l]];
     const int32_t* src = idxs.p[S.buf];
+    const bool identity = S.buf == BUF_ORIGINAL;  // a tree that is its root: the list was never stored
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < S.count; j += (int64_t)gridDim.x * blockDim.x)
-        out[S.begin + j] = src[S.begin + j];
+        out[S.begin + j] = identity ? (int32_t)(S.begin + j) : src[S.begin + j];
 }
 
 // LDS of the plan kernel: sort keys and order of all nodes, the new nodes' keys, per-node replay state, and the
@@ -587,9 +587,9 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // the root's rows are the original arrays under the identity list (array 0, which its great-grandchildren reuse)
     const int root_buf = BUF_ORIGINAL;
 
-    int blocks = (int)((N + 255) / 256);
+    int blocks = (int)((W + 255) / 256);
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->idx[0], N, F, ctx->step,
+    hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, N, F, ctx->step,
                        ctx->nodes, ctx->qtotals, root_buf, ctx->hist_entries, ctx->hist_counts, ctx->scan_items,
                        ctx->hist_pool, W, root_plan);
     ctx->next_hist_is_root = 1;
