@@ -249,6 +249,9 @@ static int check_shape(const qgbdt_shape* shape) {
         shape->n_bins > (shape->bin_bytes == 2 ? 1024 : 256) || shape->max_leaves < 1)
         return set_error(nullptr, QGBDT_E_INVALID_ARG, "shape out of range (rows %lld, features %d, bins %d, leaves %d)",
                          (long long)shape->n_rows, shape->n_features, shape->n_bins, shape->max_leaves);
+    if (shape->max_leaves > TABLE_MAX)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: at most %d (the kernels keep a round's table in LDS)",
+                         shape->max_leaves, TABLE_MAX);
     // the plan kernel keeps its sort and replay state of all nodes in LDS
     const size_t L = (size_t)shape->max_leaves, max_nodes = 6 * L + 1, p_max = max_nodes + (max_nodes & 1);
     const size_t plan_lds = p_max * 24 + L * 16 + max_nodes * 12 + (4 * L + 8) * 4;

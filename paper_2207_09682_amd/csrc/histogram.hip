@@ -80,12 +80,17 @@ struct Acc<32> {
     static __device__ __forceinline__ int64_t widen(word v, int) { return (int64_t)v; }
 };
 
-// Work item -> (table entry, row group).
-__device__ __forceinline__ int find_entry(const HistEntry* __restrict__ entries, int n_entries, int item) {
+// Work item -> (table entry, row group): the builds' first items, ascending, are copied into LDS once per workgroup
+// (one load per thread instead of a chain of dependent loads per item) and searched there.
+__device__ __forceinline__ void load_item_starts(const HistEntry* __restrict__ entries, int n_entries, int* s_start) {
+    for (int t = threadIdx.x; t < n_entries; t += blockDim.x) s_start[t] = entries[t].item_start;
+    __syncthreads();
+}
+__device__ __forceinline__ int find_entry(const int* s_start, int n_entries, int item) {
     int lo = 0, hi = n_entries - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (entries[mid].item_start <= item) lo = mid; else hi = mid - 1;
+        if (s_start[mid] <= item) lo = mid; else hi = mid - 1;
     }
     return lo;
 }
@@ -209,6 +214,8 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    __shared__ int s_start[TABLE_MAX];
+    load_item_starts(entries, n_entries, s_start);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_kernel(RowSourc
     const int64_t row_bytes = (int64_t)F * BB;
 
     for (int item = glane; item < n_items; item += n_lanes) {
-        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const HistEntry en = entries[find_entry(s_start, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
         const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
@@ -351,6 +358,8 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    __shared__ int s_start[TABLE_MAX];
+    load_item_starts(entries, n_entries, s_start);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -392,7 +401,7 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
     const int S = U * rpi;
 
     for (int item = glane; item < n_items; item += n_lanes) {
-        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const HistEntry en = entries[find_entry(s_start, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
         const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
@@ -505,6 +514,8 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(Row
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    __shared__ int s_start[TABLE_MAX];
+    load_item_starts(entries, n_entries, s_start);
 
     const int lane0 = threadIdx.x & 63;
     const bool lane_on = lane0 < L;
@@ -537,7 +548,7 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(Row
     const int chunk = (plan.chunk_rows - (align_rows - 1)) / BR * BR > 0 ? (plan.chunk_rows - (align_rows - 1)) / BR * BR : BR;
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const HistEntry en = entries[find_entry(s_start, n_entries, item)];
         const uint8_t* bins = src.bins[en.buf];
         const int16_t* gh = src.gh[en.buf];
         // the first rows up to a 16-byte aligned row start are taken by group 0, one dword at a time
@@ -649,13 +660,15 @@ __global__ __launch_bounds__(HIST_THREADS) void hist_generic_kernel(RowSource sr
     const int ft = min(plan.ft, F - f0);
     const int lds_words = ft * nb;
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    __shared__ int s_start[TABLE_MAX];
+    load_item_starts(entries, n_entries, s_start);
     int C = 1;
     while (C < ft && C < 64) C <<= 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
     const int rpi = 64 / C;                  // rows per wavefront iteration
     const int r = lane / C, fl = lane % C;   // the lane's row of the iteration and first feature
     for (int item = glane; item < n_items; item += n_lanes) {
-        const HistEntry en = entries[find_entry(entries, n_entries, item)];
+        const HistEntry en = entries[find_entry(s_start, n_entries, item)];
         const int64_t rows_per_group = (en.count + en.groups - 1) / en.groups;
         const int64_t gbegin = min(en.count, (int64_t)(item - en.item_start) * rows_per_group);
         const int64_t gend = min(en.count, gbegin + rows_per_group);
@@ -697,7 +710,9 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
     const uint32_t hmask = (1u << hs) - 1u;
     const int per = (n_items + (int)gridDim.z - 1) / (int)gridDim.z;
     const int i0 = blockIdx.z * per, i1 = min(n_items, i0 + per);
-    if (i0 >= i1) return;
+    if (i0 >= i1) return;  // uniform over the workgroup
+    __shared__ int s_start[TABLE_MAX];
+    load_item_starts(entries, n_entries, s_start);
     const int f0 = blockIdx.y * plan.ft;
     const int ft = min(plan.ft, F - f0);
     const int pitch = generic ? ft : plan.ftp;
@@ -709,7 +724,7 @@ __global__ __launch_bounds__(256) void hist_reduce_kernel(const unsigned char* _
     const size_t stride = (size_t)gridDim.y * (size_t)plan.slot_bytes;  // bytes from one item's slot to the next
     const unsigned char* base = partials + (size_t)blockIdx.y * (size_t)plan.slot_bytes + (size_t)w * sizeof(word);
     const int64_t hoff = (int64_t)b * F + f0 + f;
-    int e = find_entry(entries, n_entries, i0);
+    int e = find_entry(s_start, n_entries, i0);
     int i = i0;
     while (i < i1) {
         const int iend = min(i1, entries[e].item_start + entries[e].groups);

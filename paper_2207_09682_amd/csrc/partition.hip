@@ -169,11 +169,17 @@ int run_partition_rows(qgbdt_ctx* ctx, const uint8_t* bins, int32_t* row_idx, in
 // Work items are row segments of PART_SEG rows; segment -> (batch entry, segment of that
 // node) by binary search over the entries' first-segment numbers.
 
-__device__ __forceinline__ int find_batch(const BatchEntry* __restrict__ batch, int n_batch, int item) {
+// (The round's table is copied into LDS once per workgroup and searched there: through global memory the search is
+// a chain of dependent loads per segment.)
+__device__ __forceinline__ void load_batch(const BatchEntry* __restrict__ batch, int n_batch, BatchEntry* s_batch) {
+    for (int t = threadIdx.x; t < n_batch; t += blockDim.x) s_batch[t] = batch[t];
+    __syncthreads();
+}
+__device__ __forceinline__ int find_batch(const BatchEntry* s_batch, int n_batch, int item) {
     int lo = 0, hi = n_batch - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (batch[mid].seg_start <= item) lo = mid; else hi = mid - 1;
+        if (s_batch[mid].seg_start <= item) lo = mid; else hi = mid - 1;
     }
     return lo;
 }
@@ -200,8 +206,10 @@ __global__ __launch_bounds__(256) void batch_part_count_kernel(RowSource rows, c
             z[i] = 0;
     }
     __shared__ int sc[4];
+    __shared__ BatchEntry s_batch[TABLE_MAX];
+    load_batch(batch, n_batch, s_batch);
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const BatchEntry be = batch[find_batch(batch, n_batch, item)];
+        const BatchEntry be = s_batch[find_batch(s_batch, n_batch, item)];
         const Node nd = nodes[be.node];
         const int32_t* src = idxs.p[nd.buf] + nd.begin;
         const uint8_t* brow = rows.bins[ordered ? nd.buf : BUF_ORIGINAL] + (ordered ? nd.begin * (int64_t)F : 0);
@@ -246,10 +254,12 @@ __global__ __launch_bounds__(256) void batch_part_scatter_kernel(RowSource rows,
     __shared__ int s_dpos[PART_SEG];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int dpr = F / 4;
+    __shared__ BatchEntry s_batch[TABLE_MAX];
+    load_batch(batch, n_batch, s_batch);
     // Segments are taken from the last to the first: the count kernel has just streamed the same
     // rows front to back, so the tail of that stream is what the memory-side cache still holds.
     for (int item = n_items - 1 - (int)blockIdx.x; item >= 0; item -= (int)gridDim.x) {
-        const BatchEntry be = batch[find_batch(batch, n_batch, item)];
+        const BatchEntry be = s_batch[find_batch(s_batch, n_batch, item)];
         const Node nd = nodes[be.node];
         const int cbuf = child_buffer(nd.buf);
         const bool identity = nd.buf == BUF_ORIGINAL;  // the root's list: row id = position, never stored
