@@ -721,6 +721,8 @@ def test_measured_stream_read_is_plausible():
     buf = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
     gbps = ctx.measure_stream_read(buf, reps=5)
     assert 200.0 < gbps < 40000.0                                  # 64 MiB may be served by the on-die caches
+    v = ctx.stream_read_variant                                     # the best of the swept launch shapes
+    assert v["loads_in_flight"] in (4, 8, 16) and v["workgroups"] >= 1 and v["non_temporal"] in (False, True)
     assert ctx.measure_stream_read(buf[:16], reps=1) > 0.0
     with pytest.raises(QgbdtError):
         ctx.measure_stream_read(buf[8:8 + 64], reps=1)              # not 16-byte aligned
@@ -735,6 +737,29 @@ def test_tree_stats_after_a_tree():
     rounds, expanded, committed, nodes = ctx.tree_stats()
     n = int(t.n_leaves.item())
     assert committed == n - 1 and expanded >= committed and nodes == 2 * expanded + 1 and 1 <= rounds <= expanded + 1
+
+
+def test_profile_separates_root_builds_from_the_rounds_builds():
+    # with profiling on, every histogram launch is timed; those that are a tree's root build are reported apart
+    cfg = workloads.CONFIGS[0]
+    wl = workloads.make_workload(cfg)
+    ctx = _ctx(wl.n_rows, cfg.n_features, cfg.n_bins, L=cfg.num_leaves)
+    g, h = workloads.gradients(wl, torch.zeros(wl.n_rows))
+    dbins, dg, dh = wl.bins.cuda(), g.cuda(), h.cuda()
+    ctx.set_profiling(True)
+    ctx.read_profile()
+    rounds = 0
+    for it in range(3):
+        ctx.grow_tree(dbins, dg, dh, 2, 2, 0, it, cfg.num_leaves)
+        rounds += ctx.tree_stats()[0]
+    gh, _ = ctx.quantize_gradients(dg, dh, 2, 2, 0, 0)
+    ctx.build_histograms(dbins, gh, bits_g=2, bits_h=2)            # a stand-alone build is not a tree's root
+    root_ms, root_n = ctx.read_profile_roots()
+    ms, n, nbytes = ctx.read_profile()
+    ctx.set_profiling(False)
+    assert root_n == 3 and 0.0 < root_ms < ms
+    assert n >= 3 + rounds + 1 and nbytes > 3 * wl.n_rows * (cfg.n_features + 2)
+    assert ctx.read_profile_roots() == (0.0, 0)                     # read_profile has reset the timers
 
 
 # ----------------------------------------------------------------------------
