@@ -317,14 +317,15 @@ QGBDT_API int qgbdt_read_profile_roots(qgbdt_ctx* ctx, double* root_ms, int64_t*
 
 /* The launch plan the histogram kernels would be given for a shape (host-only: no context, no GPU call), for
  * callers and tests that check the plan against its invariants.  rows / n_builds: the rows a launch serves and
- * the number of builds they belong to (1 with rows > 0: a stand-alone build of that many rows).  out (host int64
- * [24]): features per tile, tile pitch in LDS words, dwords per tile row, rows per wavefront step, feature tiles,
+ * the number of builds they belong to (1 with rows > 0: a stand-alone build of that many contiguous rows of a
+ * 16-byte aligned matrix).  out (host int64 [25]): features per tile, tile pitch in LDS words, dwords per tile row, rows per wavefront step, feature tiles,
  * threads per workgroup, bytes of local bins, rows per chunk (width rule of Sec. 7.4.3), row groups of one build,
  * row-group lanes of a launch, least rows per group, word width of the local bins (16: 32-bit words, 32: 64-bit),
  * bits of the hessian field of a 32-bit word, lanes / rows per step of the byte-stream kernel (0: not used), most
  * work items of a launch, bytes of a row group's slot, most rows of a one-chunk group, padded pitch flag, bytes per
  * lane of the wide-row kernels (0: not used), unaligned-row flag, element-wise flag, rows per row group for
- * (rows, n_builds), bytes of the workspace section that holds the slots. */
+ * (rows, n_builds), bytes of the workspace section that holds the slots, two-level flag (32-bit working words folded
+ * into 64-bit words in LDS after every chunk: the slots then hold 64-bit words). */
 QGBDT_API int qgbdt_describe_hist_plan(const qgbdt_shape* shape, int32_t bits_g, int32_t bits_h, int32_t acc_width,
                              int32_t skewed, int64_t rows, int32_t n_builds, int64_t* out, int32_t n_out);
 

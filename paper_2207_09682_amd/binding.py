@@ -109,7 +109,8 @@ def load_library() -> C.CDLL:
 
 PLAN_FIELDS = ("ft", "ftp", "dpr", "rows_per_it", "n_tiles", "threads", "lds_bytes", "chunk_rows", "max_groups",
                "max_lanes", "min_rows_per_group", "acc_width", "hshift", "flat_lanes", "flat_rows", "max_items",
-               "slot_bytes", "single_rows", "pad16", "wide_v", "ragged", "bytewise", "target_rows", "partial_bytes")
+               "slot_bytes", "single_rows", "pad16", "wide_v", "ragged", "bytewise", "target_rows", "partial_bytes",
+               "two_level")
 
 
 def describe_hist_plan(n_rows, n_features, n_bins, max_leaves=255, bin_bytes=1, bits_g=3, bits_h=3, acc_width=0,
@@ -117,8 +118,8 @@ def describe_hist_plan(n_rows, n_features, n_bins, max_leaves=255, bin_bytes=1, 
     """qgbdt_describe_hist_plan: the histogram launch plan of a shape as a dict (host-only, needs no GPU)."""
     lib = load_library()
     shape = Shape(n_rows, n_features, n_bins, bin_bytes, max_leaves)
-    out = (C.c_int64 * 24)()
-    rc = lib.qgbdt_describe_hist_plan(C.byref(shape), bits_g, bits_h, acc_width, 1 if skewed else 0, rows, n_builds, out, 24)
+    out = (C.c_int64 * 25)()
+    rc = lib.qgbdt_describe_hist_plan(C.byref(shape), bits_g, bits_h, acc_width, 1 if skewed else 0, rows, n_builds, out, 25)
     if rc != 0:
         raise QgbdtError(rc, lib.qgbdt_last_error(None).decode())
     return dict(zip(PLAN_FIELDS, (int(x) for x in out)))

@@ -409,7 +409,8 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
     if (count == 0) return QGBDT_OK;
     // most frequent bins of the bound matrix are left out by the wide-row kernels and filled in afterwards
     const uint16_t* mfb = (ctx->mfb_features > 0 && ctx->bound_bins == bins) ? ctx->mfb : nullptr;
-    const HistPlan plan = make_hist_plan_for(ctx->shape, bits_g, bits_h, acc_width, count, mfb != nullptr);
+    const HistPlan plan = make_hist_plan_for(ctx->shape, bits_g, bits_h, acc_width, count, mfb != nullptr,
+                                             row_idx == nullptr && ((uintptr_t)bins & 15) == 0);
     if (mfb && plan.wide_v == 0) mfb = nullptr;  // only those kernels skip
     rc = launch_set_hist_table(ctx, plan, begin, count);
     if (rc != QGBDT_OK) return rc;
@@ -719,7 +720,7 @@ int qgbdt_measure_stream_read(qgbdt_ctx* ctx, const void* buf, int64_t bytes, in
 
 int qgbdt_describe_hist_plan(const qgbdt_shape* shape, int32_t bits_g, int32_t bits_h, int32_t acc_width, int32_t skewed,
                              int64_t rows, int32_t n_builds, int64_t* out, int32_t n_out) {
-    if (!out || n_out < 24) return set_error(nullptr, QGBDT_E_INVALID_ARG, "out must hold 24 values");
+    if (!out || n_out < 25) return set_error(nullptr, QGBDT_E_INVALID_ARG, "out must hold 25 values");
     int rc = check_shape(shape);
     if (rc != QGBDT_OK) return rc;
     if (bits_g < 2 || bits_g > 8 || !(bits_h == 0 || (bits_h >= 2 && bits_h <= 8)) ||
@@ -727,13 +728,13 @@ int qgbdt_describe_hist_plan(const qgbdt_shape* shape, int32_t bits_g, int32_t b
         return set_error(nullptr, QGBDT_E_INVALID_ARG, "bits, acc_width, rows or n_builds out of range");
     // rows > 0 with one build: the plan of a stand-alone build of that many rows (the width may fall back to 64-bit
     // words); else the plan of the batched launches of a tree
-    const HistPlan p = (n_builds == 1 && rows > 0) ? make_hist_plan_for(*shape, bits_g, bits_h, acc_width, rows, skewed != 0)
+    const HistPlan p = (n_builds == 1 && rows > 0) ? make_hist_plan_for(*shape, bits_g, bits_h, acc_width, rows, skewed != 0, true)
                                                    : make_hist_plan(*shape, bits_g, bits_h, acc_width, skewed != 0);
-    const int64_t v[24] = {p.ft, p.ftp, p.dpr, p.rows_per_it, p.n_tiles, p.threads, p.lds_bytes, p.chunk_rows,
+    const int64_t v[25] = {p.ft, p.ftp, p.dpr, p.rows_per_it, p.n_tiles, p.threads, p.lds_bytes, p.chunk_rows,
                            p.max_groups, p.max_lanes, p.min_rows_per_group, p.acc_width, p.hshift, p.flat_lanes,
                            p.flat_rows, p.max_items, p.slot_bytes, p.single_rows, p.pad16, p.wide_v, p.ragged,
-                           p.bytewise, hist_target_rows(p, rows, n_builds), (int64_t)partial_slot_bytes(*shape)};
-    for (int i = 0; i < 24; ++i) out[i] = v[i];
+                           p.bytewise, hist_target_rows(p, rows, n_builds), (int64_t)partial_slot_bytes(*shape), p.two_level};
+    for (int i = 0; i < 25; ++i) out[i] = v[i];
     return QGBDT_OK;
 }
 

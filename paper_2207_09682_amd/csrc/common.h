@@ -102,6 +102,8 @@ struct HistPlan {
     int32_t wide_v;       // > 0: wide rows are read in pieces of this many bytes per lane (8 or 16)
     int32_t ragged;       // feature count not a multiple of 4: unaligned dword loads, last dword of a tile row partial
     int32_t bytewise;     // no dword kernel applies (rows or a tile narrower than 4 bytes): one byte load per bin
+    int32_t two_level;    // byte-stream kernel with 32-bit working words folded into 64-bit words in LDS after every chunk
+                          // (one large contiguous build: few, long row groups; slots hold the 64-bit words)
 };
 
 // Rows per row group when `total` rows of `n_entries` builds are shared out: about max_groups
@@ -233,7 +235,8 @@ int launch_quantize(qgbdt_ctx* ctx, const float* g, const float* h, int64_t n, i
                     uint64_t seed, uint32_t iteration, int rounding, int16_t* gh, float* delta_out,
                     int64_t* totals_out, float2* pairs_out);
 HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, bool skew = false);
-HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew = false);
+HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew = false,
+                            bool stream_ok = false);  // stream_ok: contiguous rows of a 16-byte aligned matrix
 int64_t max_rows_for_width(int bits_g, int bits_h, int w);
 int launch_set_hist_table(qgbdt_ctx* ctx, const HistPlan& plan, int64_t begin, int64_t count);
 int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, const IdxSet& idx, bool use_idx,

@@ -494,8 +494,14 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 // iteration, so a lane's four dwords keep their (row, feature) position for the
 // whole kernel; they lie in at most two consecutive rows.  Blocks of U iterations
 // are software-pipelined like in hist_kernel.
-template <int W, int U>
-__global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(RowSource src,
+//
+// TWO (32-bit working words only; 1024 threads, one workgroup per CU): a second copy of the local bins with 64-bit
+// words (32|32 fields) sits next to the working copy; after every chunk the working words are widened and added into
+// it (every thread folds its own words: no atomics) and cleared, and the 64-bit copy is what the group hands over at
+// its end.  A group may then be as long as its build allows -- one group per CU instead of one per chunk -- which
+// for a build of all rows halves the bytes handed over and reduced, and no chunk is ever merged through global atomics.
+template <int W, int U, bool TWO>
+__global__ __launch_bounds__(TWO ? 1024 : HIST_THREADS, TWO ? 1 : HIST_WAVES) void hist_flat_kernel(RowSource src,
                                                          const HistEntry* __restrict__ entries,
                                                          const int32_t* __restrict__ table_counts,
                                                          int64_t* hist_base, unsigned char* partials, int F, int nb,
@@ -513,7 +519,11 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(Row
     const int BR = U * RPI;  // rows of one block of U iterations
     const int ftp = plan.ftp;
     const int lds_words = nb * ftp;
+    // (TWO) the 64-bit copy follows the working words, 16-byte aligned
+    unsigned long long* lds2 = reinterpret_cast<unsigned long long*>(lds_raw + (((size_t)lds_words * sizeof(word) + 15) & ~(size_t)15));
     for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds[w] = 0;
+    if (TWO)
+        for (int w = threadIdx.x; w < lds_words; w += blockDim.x) lds2[w] = 0ull;
     __shared__ int s_start[TABLE_MAX];
     load_item_starts(entries, n_entries, s_start);
 
@@ -629,7 +639,16 @@ __global__ __launch_bounds__(HIST_THREADS, HIST_WAVES) void hist_flat_kernel(Row
                 }
             }
             __syncthreads();
-            if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
+            if (TWO) {
+                for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
+                    const word v = lds[w];
+                    if (v != 0) { lds[w] = 0; lds2[w] += (unsigned long long)Acc<W>::widen(v, plan.hshift); }
+                }
+                if (cend >= gend) {
+                    __syncthreads();
+                    store_partial<32>(lds2, lds_words * 8, slot);
+                }
+            } else if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
             else merge_local<W>(lds, lds_words, ftp, F, 0, F, hist, plan.hshift);
             first = false;
         }
@@ -902,8 +921,29 @@ HistPlan make_hist_plan(const qgbdt_shape& s, int bits_g, int bits_h, int acc_wi
 // every row group can fit one chunk (the item table has room for rows / single_rows groups):
 // beyond that groups would merge their earlier chunks through global atomics, which costs more
 // than the 64-bit LDS atomics of 32|32 words (10.5 M rows, 5-bit: 236 us against 93 us).
-HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew) {
+//
+// A long contiguous build (stream_ok) of a narrow matrix with 32-bit working words takes the byte-stream kernel's
+// two-level form when every CU's group would span at least two chunks: 256 groups of 1024 threads, the working
+// words folded into 64-bit words in LDS after every chunk.  With the width left open that needs chunks of at least
+// 4096 rows (2- to 4-bit gradients), as for the one-level form.
+HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int acc_width, int64_t rows, bool skew,
+                            bool stream_ok) {
     HistPlan p = make_hist_plan(s, bits_g, bits_h, acc_width, skew);
+    if (stream_ok && acc_width != 32 && p.flat_lanes > 0) {
+        HistPlan q = p.acc_width == 16 ? p : make_hist_plan(s, bits_g, bits_h, 16, skew);
+        const int64_t words = (int64_t)s.n_bins * q.ftp;
+        const int64_t lds = ((words * 4 + 15) & ~(int64_t)15) + words * 8;
+        if ((acc_width == 16 || q.chunk_rows >= 4096) && rows >= (int64_t)2 * 256 * q.chunk_rows && lds <= 150 * 1024) {
+            q.two_level = 1;
+            q.threads = 1024;
+            q.lds_bytes = (int32_t)lds;
+            q.slot_bytes = (int32_t)((words * 8 + 15) & ~(int64_t)15);
+            q.max_groups = 256;
+            q.max_lanes = 256;
+            q.single_rows = 0x40000000;  // a group folds its chunks locally: no limit on its length
+            return q;
+        }
+    }
     if (acc_width == 0 && p.acc_width == 16 && rows / p.single_rows >= (int64_t)p.max_items - 2)
         p = make_hist_plan(s, bits_g, bits_h, 32, skew);
     return p;
@@ -939,6 +979,13 @@ static hipError_t allow_lds(int bytes) {
 }
 
 int prepare_hist_kernels(qgbdt_ctx* ctx) {
+    {
+        // the two-level byte-stream kernel holds a 32-bit and a 64-bit copy of the local bins
+        const HistPlan two = make_hist_plan_for(ctx->shape, 8, 8, 16, ctx->shape.n_rows, false, true);  // shortest chunks
+        if (two.two_level && two.lds_bytes > 48 * 1024)
+            QG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(hist_flat_kernel<16, 2, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+    }
     int most = 0;
     for (int w = 16; w <= 32; w += 16)
         for (int skew = 0; skew < 2; ++skew) {
@@ -991,13 +1038,18 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
     }
     ctx->next_hist_is_root = 0;
     const bool flat = fast && !use_idx && plan.flat_lanes > 0 && flat_ok;
+    if (plan.two_level && !flat)
+        return set_error(ctx, QGBDT_E_INVALID_ARG, "two-level plan for rows that the byte-stream kernel cannot read");
     bool wide_ok = true;  // 16-byte loads need 16-byte aligned matrices (F is a multiple of 16 in that mode)
     for (int b = 0; b < 4; ++b) wide_ok = wide_ok && (((uintptr_t)rows.bins[b] & 15) == 0);
     if (flat) {
 #define QG_LAUNCH_FLAT(W_, U_)                                                                                   \
-    hipLaunchKernelGGL((hist_flat_kernel<W_, U_>), grid, block, plan.lds_bytes, ctx->stream, rows, entries, \
+    hipLaunchKernelGGL((hist_flat_kernel<W_, U_, false>), grid, block, plan.lds_bytes, ctx->stream, rows, entries, \
                        table_counts, hist_base, partials, F, nb, plan, step)
-        if (plan.acc_width == 16) {
+        if (plan.two_level) {
+            hipLaunchKernelGGL((hist_flat_kernel<16, 2, true>), grid, block, plan.lds_bytes, ctx->stream, rows, entries,
+                               table_counts, hist_base, partials, F, nb, plan, step);
+        } else if (plan.acc_width == 16) {
             if (plan.flat_unroll >= 4) QG_LAUNCH_FLAT(16, 4);
             else if (plan.flat_unroll >= 2) QG_LAUNCH_FLAT(16, 2);
             else QG_LAUNCH_FLAT(16, 1);
@@ -1079,7 +1131,7 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
         if (z > items_bound) z = (int)items_bound;
         if (z < 1) z = 1;
         dim3 rgrid((unsigned)xb, (unsigned)plan.n_tiles, (unsigned)z);
-        if (plan.acc_width == 16)
+        if (plan.acc_width == 16 && !plan.two_level)  // (two-level groups hand over 64-bit words)
             hipLaunchKernelGGL(hist_reduce_kernel<16>, rgrid, dim3(256), 0, ctx->stream, partials, entries, table_counts,
                                hist_base, F, nb, plan, fast ? 0 : 1);
         else

@@ -553,7 +553,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // (the large tiles that skipping makes worthwhile pay for contiguous rows only: the gathered builds of the
     // rounds keep the ordinary tiles -- 20M x 200: 212 against 197 us per launch)
     const HistPlan plan = make_hist_plan(ctx->shape, p->bits_g, p->bits_h, p->acc_width, false);
-    const HistPlan root_plan = make_hist_plan_for(ctx->shape, p->bits_g, p->bits_h, p->acc_width, N, skip_ok);  // the root's build alone
+    const HistPlan root_plan = make_hist_plan_for(ctx->shape, p->bits_g, p->bits_h, p->acc_width, N, skip_ok,
+                                                  ((uintptr_t)bins & 15) == 0);  // the root's build alone: contiguous rows
     const uint16_t* mfb = skip_ok ? ctx->mfb : nullptr;
     // Row sources: buffer 3 = the caller's matrix and the quantized gradients in original order;
     // buffers 0..2 are what the partition writes (see RowSource).

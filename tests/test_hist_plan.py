@@ -67,6 +67,34 @@ def test_plan_invariants(shape):
             assert p["flat_rows"] * F == 16 * p["flat_lanes"]
 
 
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"{s[0]}x{s[1]}_nb{s[2]}_L{s[3]}_b{s[4]}")
+def test_plan_of_one_long_contiguous_build(shape):
+    # the plan of a stand-alone build of all rows: for narrow matrices the byte-stream kernel's two-level form
+    # (32-bit working words folded into 64-bit words in LDS), whose slots hold the 64-bit words
+    N, F, nb, L, bb = shape
+    seen_two = False
+    for (bg, bh), acc in itertools.product(BITS, (0, 16, 32)):
+        p = describe_hist_plan(N, F, nb, L, bb, bg, bh, acc, False, rows=N, n_builds=1)
+        assert p["max_items"] * p["n_tiles"] * p["slot_bytes"] <= p["partial_bytes"]
+        assert p["max_lanes"] % 8 == 0 and p["lds_bytes"] <= 160 * 1024
+        groups = -(-N // p["target_rows"])
+        assert 1 <= groups <= p["max_items"]
+        if p["two_level"]:
+            seen_two = True
+            words = nb * p["ftp"]
+            assert acc != 32 and p["acc_width"] == 16 and p["flat_lanes"] > 0 and p["n_tiles"] == 1 and p["threads"] == 1024
+            assert p["lds_bytes"] == ((4 * words + 15) // 16) * 16 + 8 * words
+            assert p["slot_bytes"] >= 8 * words and p["slot_bytes"] % 16 == 0
+            assert groups <= p["max_lanes"] == 256                                   # one group per CU, all resident
+            assert p["chunk_rows"] <= _rows_fitting_word32(bg, bh, p["hshift"])      # the working words still follow the width rule
+            assert N >= 2 * 256 * p["chunk_rows"]
+        else:
+            # without the fold a group of 32-bit words must not be longer than the item table allows one-chunk groups, or the width is 64
+            assert p["acc_width"] == 32 or acc == 16 or N // p["single_rows"] < p["max_items"] - 2
+    if bb == 1 and 16 <= F <= 64 and F % 4 == 0 and N >= 2_000_000:
+        assert seen_two
+
+
 def _lane_columns(p, F, bb, tile, dword_kernel=False):
     """(first byte of the lane's load inside the row, bytes loaded, LDS word columns it may update) per active lane of
     one tile, as the dword-per-lane and the wide-row kernels compute them."""
