@@ -496,9 +496,9 @@ __global__ __launch_bounds__(1024) void hist_wide_kernel(RowSource src, IdxSet i
 // are software-pipelined like in hist_kernel.
 //
 // TWO (32-bit working words only; 1024 threads, one workgroup per CU): a second copy of the local bins with 64-bit
-// words (32|32 fields) sits next to the working copy; after every chunk the working words are widened and added into
-// it (every thread folds its own words: no atomics) and cleared, and the 64-bit copy is what the group hands over at
-// its end.  A group may then be as long as its build allows -- one group per CU instead of one per chunk -- which
+// words (32|32 fields) sits next to the working copy; before the rows since the last fold exceed a chunk the working
+// words are widened and added into it (every thread folds its own words: no atomics) and cleared, and the 64-bit copy
+// is what the group hands over at its end.  A group may then be as long as its build allows -- one group per CU instead of one per chunk -- which
 // for a build of all rows halves the bytes handed over and reduced, and no chunk is ever merged through global atomics.
 template <int W, int U, bool TWO>
 __global__ __launch_bounds__(TWO ? 1024 : HIST_THREADS, TWO ? 1 : HIST_WAVES) void hist_flat_kernel(RowSource src,
@@ -574,6 +574,91 @@ __global__ __launch_bounds__(TWO ? 1024 : HIST_THREADS, TWO ? 1 : HIST_WAVES) vo
         unsigned char* slot = partials + (size_t)item * (size_t)plan.slot_bytes;
         bool first = true;  // a group without rows still hands over its (empty) bins
 
+        if constexpr (TWO) {
+            // One pass over the group's blocks, wavefront w taking blocks w, w + n_waves, ... in rounds that all
+            // wavefronts walk together; after every `fold_rounds` rounds the working words are folded.  The loads of a
+            // wavefront's next block stay in flight across a fold: only LDS is touched between the barriers.
+            const uint8_t* cb = bins + (en.begin + gbegin) * (int64_t)F;
+            const int16_t* gb = gh + (en.begin + gbegin);
+            const int64_t grow = gend - gbegin;
+            const int n_blocks = (int)(grow / BR);
+            const int rounds = (n_blocks + n_waves - 1) / n_waves;
+            // rows of `fold_rounds` rounds, plus the tail (< BR) and head (< align_rows) rows of the last period, fit a chunk
+            const int fold_rounds = max(1, (plan.chunk_rows - BR - align_rows) / (n_waves * BR));
+            auto fold = [&]() {
+                __syncthreads();
+                for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
+                    const word v = lds[w];
+                    if (v != 0) { lds[w] = 0; lds2[w] += (unsigned long long)Acc<W>::widen(v, plan.hshift); }
+                }
+                __syncthreads();
+            };
+            uint4 d[U], dn[U];
+            int ga[U], gbv[U], gan[U], gbn[U];
+            if (wave < n_blocks) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t row0 = (int64_t)(wave * U + u) * RPI;
+                    d[u] = *reinterpret_cast<const uint4*>(cb + (size_t)row0 * (size_t)F + 16 * lane);
+                    ga[u] = gb[row0 + rA];
+                    gbv[u] = gb[row0 + rB];
+                }
+            }
+            for (int r = 0; r < rounds; ++r) {
+                const int jb = r * n_waves + wave;  // uniform over the wavefront
+                if (jb < n_blocks) {
+                    const int jn = min(jb + n_waves, n_blocks - 1);  // the last prefetch re-reads the last block
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t row0 = (int64_t)(jn * U + u) * RPI;
+                        dn[u] = *reinterpret_cast<const uint4*>(cb + (size_t)row0 * (size_t)F + 16 * lane);
+                        gan[u] = gb[row0 + rA];
+                        gbn[u] = gb[row0 + rB];
+                    }
+                    if (lane_on) {
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const word va = Acc<W>::expand(ga[u], hmul);
+                            const word vb = Acc<W>::expand(gbv[u], hmul);
+                            const uint32_t dw[4] = {d[u].x, d[u].y, d[u].z, d[u].w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const word v = useB[i] ? vb : va;
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    const uint32_t b = __builtin_amdgcn_ubfe(dw[i], sh[k], 8u);
+                                    Acc<W>::add(reinterpret_cast<word*>(lds_raw + (__umul24(b, pitch) + fl4[i][k])), v);
+                                }
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) { d[u] = dn[u]; ga[u] = gan[u]; gbv[u] = gbn[u]; }
+                }
+                if ((r + 1) % fold_rounds == 0 && r + 1 < rounds) fold();
+            }
+            // the rows after the last whole block and (group 0) the unaligned head rows in front of the
+            // build: one dword per thread and step, into the last fold's rows
+            const int64_t tail0 = (int64_t)n_blocks * BR;
+            const int n_head = g == 0 ? (int)head : 0;
+            const int n_tail = (int)(grow - tail0);
+            for (int e = threadIdx.x; e < (n_head + n_tail) * dpr; e += blockDim.x) {
+                const int rs = e / dpr, q = e - rs * dpr;
+                const int64_t arow = rs < n_head ? (int64_t)rs : gbegin + tail0 + (rs - n_head);
+                const uint32_t dwd = *reinterpret_cast<const uint32_t*>(bins + (en.begin + arow) * (int64_t)F + 4 * q);
+                const word v = Acc<W>::expand(gh[en.begin + arow], hmul);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t b = (dwd >> (8 * k)) & 0xffu;
+                    Acc<W>::add(&lds[b * ftp + 4 * q + k], v);
+                }
+            }
+            fold();
+            store_partial<32>(lds2, lds_words * 8, slot);
+            __syncthreads();  // the next item's atomics wait for the cleared words
+            continue;
+        }
+
         for (int64_t cbegin = gbegin; first || cbegin < gend; cbegin += chunk) {
             const int64_t cend = min(gend, cbegin + (int64_t)chunk);
             const int crow = cbegin < cend ? (int)(cend - cbegin) : 0;
@@ -639,16 +724,7 @@ __global__ __launch_bounds__(TWO ? 1024 : HIST_THREADS, TWO ? 1 : HIST_WAVES) vo
                 }
             }
             __syncthreads();
-            if (TWO) {
-                for (int w = threadIdx.x; w < lds_words; w += blockDim.x) {
-                    const word v = lds[w];
-                    if (v != 0) { lds[w] = 0; lds2[w] += (unsigned long long)Acc<W>::widen(v, plan.hshift); }
-                }
-                if (cend >= gend) {
-                    __syncthreads();
-                    store_partial<32>(lds2, lds_words * 8, slot);
-                }
-            } else if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
+            if (cend >= gend) store_partial<W>(lds, plan.lds_bytes, slot);
             else merge_local<W>(lds, lds_words, ftp, F, 0, F, hist, plan.hshift);
             first = false;
         }
@@ -933,7 +1009,10 @@ HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int ac
         HistPlan q = p.acc_width == 16 ? p : make_hist_plan(s, bits_g, bits_h, 16, skew);
         const int64_t words = (int64_t)s.n_bins * q.ftp;
         const int64_t lds = ((words * 4 + 15) & ~(int64_t)15) + words * 8;
-        if ((acc_width == 16 || q.chunk_rows >= 4096) && rows >= (int64_t)2 * 256 * q.chunk_rows && lds <= 150 * 1024) {
+        // one round of the 16 wavefronts (blocks of 2 iterations) plus a tail block and the head rows must fit a chunk
+        const bool round_fits = q.chunk_rows >= 17 * 2 * q.flat_rows + 4;
+        if ((acc_width == 16 || q.chunk_rows >= 4096) && round_fits && rows >= (int64_t)2 * 256 * q.chunk_rows &&
+            lds <= 150 * 1024) {
             q.two_level = 1;
             q.threads = 1024;
             q.lds_bytes = (int32_t)lds;

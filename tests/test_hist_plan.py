@@ -67,6 +67,38 @@ def test_plan_invariants(shape):
             assert p["flat_rows"] * F == 16 * p["flat_lanes"]
 
 
+def _walk_two_level_groups(p, F, count, begin, groups):
+    """The two-level byte-stream kernel's walk over one build of `count` rows from row `begin`: every row lies in
+    exactly one group, whole blocks start 16-byte aligned, and no more rows than a chunk holds are added to the 32-bit
+    working words between two folds."""
+    n_waves, U = 16, 2
+    align_rows = 16 // (16 if F % 16 == 0 else 8 if F % 8 == 0 else 4)
+    BR = U * p["flat_rows"]
+    head = min(count, (align_rows - begin % align_rows) % align_rows)
+    rpg = max(BR, -(-(-(-(count - head) // groups)) // BR) * BR)
+    fold_rounds = max(1, (p["chunk_rows"] - BR - align_rows) // (n_waves * BR))
+    covered = head
+    for g in range(groups):
+        gbegin = min(count, head + g * rpg)
+        gend = min(count, gbegin + rpg)
+        grow = gend - gbegin
+        n_blocks = grow // BR
+        rounds = -(-n_blocks // n_waves)
+        if n_blocks:
+            assert ((begin + gbegin) * F) % 16 == 0
+        since_fold = 0
+        for r in range(rounds):
+            since_fold += BR * max(0, min(n_waves, n_blocks - r * n_waves))
+            if (r + 1) % fold_rounds == 0 and r + 1 < rounds:
+                assert since_fold <= p["chunk_rows"]
+                since_fold = 0
+        since_fold += (grow - n_blocks * BR) + (head if g == 0 else 0)
+        assert since_fold <= p["chunk_rows"], (F, count, begin, g)
+        assert (begin + gend) * F <= (begin + count) * F                             # the last load ends inside the slice
+        covered += grow
+    assert covered == count
+
+
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"{s[0]}x{s[1]}_nb{s[2]}_L{s[3]}_b{s[4]}")
 def test_plan_of_one_long_contiguous_build(shape):
     # the plan of a stand-alone build of all rows: for narrow matrices the byte-stream kernel's two-level form
@@ -88,6 +120,8 @@ def test_plan_of_one_long_contiguous_build(shape):
             assert groups <= p["max_lanes"] == 256                                   # one group per CU, all resident
             assert p["chunk_rows"] <= _rows_fitting_word32(bg, bh, p["hshift"])      # the working words still follow the width rule
             assert N >= 2 * 256 * p["chunk_rows"]
+            for begin in (0, 1, 3):                                                  # a slice that starts off a 16-byte boundary
+                _walk_two_level_groups(p, F, N - begin, begin, -(-(N - begin) // p["target_rows"]))
         else:
             # without the fold a group of 32-bit words must not be longer than the item table allows one-chunk groups, or the width is 64
             assert p["acc_width"] == 32 or acc == 16 or N // p["single_rows"] < p["max_items"] - 2
