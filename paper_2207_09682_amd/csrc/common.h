@@ -245,7 +245,8 @@ int launch_hist(qgbdt_ctx* ctx, const HistPlan& plan, const RowSource& rows, con
 int launch_fill_zero(qgbdt_ctx* ctx, int64_t* p, int64_t n_words);
 int launch_subtract(qgbdt_ctx* ctx, const int64_t* parent, const int64_t* child, int64_t* out, int64_t n);
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb = nullptr);
+                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb = nullptr,
+                      bool reduce = true);  // reduce = false: the caller's next kernel reduces the per-feature candidates
 // stand-alone search in batches of `cap` histograms; scratch: items [cap], cand [cap][F], n_items [1]
 int run_find_best_splits(qgbdt_ctx* ctx, const int64_t* hist, int n_hists, const qgbdt_leafstat* stats,
                          const float* delta, int min_data, double min_sum_hess, qgbdt_split* out, int cap,

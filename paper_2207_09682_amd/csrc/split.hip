@@ -287,7 +287,8 @@ __global__ __launch_bounds__(256) void reduce_items_kernel(const FeatCand* __res
 }
 
 int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items, const int32_t* n_items, int max_items,
-                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb) {
+                      const float* delta, int min_data, double min_sum_hess, FeatCand* cand, const uint16_t* mfb,
+                      bool reduce) {
     const int F = ctx->shape.n_features, nb = ctx->shape.n_bins;
     int threads = 64;
     while (threads < nb) threads <<= 1;
@@ -318,9 +319,11 @@ int launch_scan_items(qgbdt_ctx* ctx, int64_t* hist_base, const ScanItem* items,
         hipLaunchKernelGGL(scan_kernel, dim3(gx, gy), dim3(threads), 0, ctx->stream, hist_base, items, n_items, F, nb,
                            delta, (int64_t)min_data, min_sum_hess, cand, glog, mfb);
     }
-    int gr = F > 256 ? max_items : (max_items + 3) / 4;
-    if (gr > 64) gr = 64;
-    hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, cand, items, n_items, F);
+    if (reduce) {  // (tree growth leaves the candidates of narrow matrices to its next kernel)
+        int gr = F > 256 ? max_items : (max_items + 3) / 4;
+        if (gr > 64) gr = 64;
+        hipLaunchKernelGGL(reduce_items_kernel, dim3(gr), dim3(256), 0, ctx->stream, cand, items, n_items, F);
+    }
     QG_HIP(ctx, hipGetLastError());
     return QGBDT_OK;
 }

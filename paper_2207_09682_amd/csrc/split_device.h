@@ -65,4 +65,37 @@ __device__ inline void reduce_features_wave(const FeatCand* cand, int F, const q
     }
 }
 
+// The same reduction by a group of `sub` consecutive lanes (a power of two, 64 at most; `sl` = lane inside
+// the group), so that one wavefront serves 64 / sub leaves at a time.  The winner's candidate travels with
+// the comparison: no load depends on another.
+__device__ inline void reduce_features_lanes(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
+                                             int sl, int sub) {
+    double bg = 0.0;
+    int bf = -1, bb = -1;
+    int64_t bl = 0;
+    for (int f = sl; f < F; f += sub) {
+        const FeatCand c = cand[f];
+        if (c.bin >= 0 && (c.gain > bg)) { bg = c.gain; bf = f; bb = c.bin; bl = c.left; }
+    }
+    for (int o = sub >> 1; o > 0; o >>= 1) {
+        const double og = __shfl_xor(bg, o);
+        const int of = __shfl_xor(bf, o);
+        const int ob = __shfl_xor(bb, o);
+        const int64_t ol = __shfl_xor(bl, o);
+        if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) { bg = og; bf = of; bb = ob; bl = ol; }
+    }
+    if (sl == 0) {
+        qgbdt_split s;
+        s.gain = 0.0; s.feature = -1; s.bin = -1;
+        s.left_g = s.left_h = s.right_g = s.right_h = s.left_count = 0;
+        if (bf >= 0) {
+            s.gain = bg; s.feature = bf; s.bin = bb;
+            s.left_g = packed_g(bl); s.left_h = packed_h(bl);
+            s.right_g = st.sum_g - s.left_g; s.right_h = st.sum_h - s.left_h;
+            s.left_count = count_estimate(s.left_h, st.sum_h, st.n_rows);
+        }
+        *out = s;
+    }
+}
+
 }  // namespace qgbdt

@@ -139,9 +139,26 @@ __device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
 __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* nodes, BatchEntry* batch,
                                                          int32_t* __restrict__ sorted_idx, int32_t* hist_counts, int F,
                                                          int num_leaves, int batch_max, int max_expand, int p_max,
-                                                         TreeOut out) {
+                                                         TreeOut out, const FeatCand* __restrict__ cand,
+                                                         const ScanItem* __restrict__ scan_items) {
     if (step->done) return;
     extern __shared__ unsigned char plan_lds[];
+    if (cand) {
+        // 0. (matrices of at most 256 features) the per-feature candidates that the split scan has just left are
+        //    reduced here instead of in a launch of their own: groups of lanes as wide as the feature count (a power
+        //    of two, one wavefront at most) take a scanned histogram each and write its node's best split.
+        const int n_items = step->n_scan_items;
+        int sub = 1;
+        while (sub < F && sub < 64) sub <<= 1;
+        const int per_pass = (int)blockDim.x / sub;
+        const int grp = (int)threadIdx.x / sub, sl = (int)threadIdx.x % sub;
+        for (int item = grp; item < n_items; item += per_pass) {
+            const ScanItem it = scan_items[item];
+            if (!it.valid) continue;  // uniform over the group of lanes
+            reduce_features_lanes(cand + (int64_t)item * F, F, it.stat, it.out, sl, sub);
+        }
+        __syncthreads();  // the nodes' best splits are read below by other wavefronts of this workgroup
+    }
     const int n_nodes0 = step->n_nodes;
     const int n_old = step->n_sorted;        // nodes already in the sorted order (all but last round's children)
     const int m_new = n_nodes0 - n_old;
@@ -588,6 +605,8 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
     // the root's rows are the original arrays under the identity list (array 0, which its great-grandchildren reuse)
     const int root_buf = BUF_ORIGINAL;
 
+    // up to 256 features the plan kernel reduces the scan's per-feature candidates itself (one launch less per round)
+    const FeatCand* fused_cand = F <= 256 ? ctx->cand : nullptr;
     int blocks = (int)((W + 255) / 256);
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(tree_init_kernel, dim3(blocks), dim3(256), 0, ctx->stream, N, F, ctx->step,
@@ -600,7 +619,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                      ctx->step, mfb);
     if (rc != QGBDT_OK) return rc;
     rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 1, ctx->delta,
-                           p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
+                           p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb, fused_cand == nullptr);
     if (rc != QGBDT_OK) return rc;
 
     const int p_max = ctx->max_nodes + (ctx->max_nodes & 1);  // even: 8-byte arrays follow 4-byte ones
@@ -612,7 +631,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
         for (int r = 0; r < to_launch; ++r) {
             hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                                ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
-                               ctx->max_expand, p_max, out);
+                               ctx->max_expand, p_max, out, fused_cand, ctx->scan_items);
             rc = launch_batch_partition_count(ctx, rows, bins_t, ordered);
             if (rc != QGBDT_OK) return rc;
             hipLaunchKernelGGL(tree_mid_kernel, dim3(1), dim3(1024), 0, ctx->stream, ctx->step, ctx->nodes, ctx->batch,
@@ -624,14 +643,14 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                              ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
             if (rc != QGBDT_OK) return rc;
             rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
-                                   ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
+                                   ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb, fused_cand == nullptr);
             if (rc != QGBDT_OK) return rc;
         }
         launched += to_launch;
         // one more plan: commits what the last round made known and tells whether the tree is finished
         hipLaunchKernelGGL(tree_plan_kernel, dim3(1), dim3(1024), plan_lds, ctx->stream, ctx->step, ctx->nodes,
                            ctx->batch, ctx->sorted_idx, ctx->hist_counts, F, p->num_leaves, ctx->batch_max,
-                           ctx->max_expand, p_max, out);
+                           ctx->max_expand, p_max, out, fused_cand, ctx->scan_items);
         QG_HIP(ctx, hipGetLastError());
         QG_HIP(ctx, hipMemcpyAsync(ctx->host_state, ctx->step, sizeof(StepState), hipMemcpyDeviceToHost, ctx->stream));
         QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -649,7 +668,7 @@ int run_grow_tree(qgbdt_ctx* ctx, const uint8_t* bins, const float* g, const flo
                          ctx->hist_counts, ctx->hist_pool, plan.max_lanes, ctx->step, mfb);
         if (rc != QGBDT_OK) return rc;
         rc = launch_scan_items(ctx, ctx->hist_pool, ctx->scan_items, &ctx->step->n_scan_items, 2 * ctx->batch_max,
-                               ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb);
+                               ctx->delta, p->min_data_in_leaf, p->min_sum_hessian, ctx->cand, mfb, fused_cand == nullptr);
         if (rc != QGBDT_OK) return rc;
         launched += 1;
         to_launch = 3;
