@@ -67,10 +67,14 @@ __global__ __launch_bounds__(256) void gh_totals_kernel(const int16_t* __restric
         sg += v >> 8;
     }
     for (int o = 32; o > 0; o >>= 1) { sh += __shfl_xor(sh, o); sa += __shfl_xor(sa, o); sg += __shfl_xor(sg, o); }
-    if ((threadIdx.x & 63) == 0) {
-        atomicAdd((unsigned long long*)&totals[0], (unsigned long long)sg);
-        atomicAdd((unsigned long long*)&totals[1], (unsigned long long)sh);
-        atomicAdd((unsigned long long*)&totals[2], (unsigned long long)sa);
+    // one set of atomics per workgroup: atomics on one address serialize at the memory side (~20 ns each)
+    __shared__ int64_t part[3][4];
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { part[0][wave] = sg; part[1][wave] = sh; part[2][wave] = sa; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        const int64_t v = part[threadIdx.x][0] + part[threadIdx.x][1] + part[threadIdx.x][2] + part[threadIdx.x][3];
+        if (v != 0) atomicAdd((unsigned long long*)&totals[threadIdx.x], (unsigned long long)v);
     }
 }
 __global__ void zero3_kernel(int64_t* t) {
@@ -397,7 +401,7 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
         // the a-priori bound fails: use the exact totals of these rows (synchronises)
         int64_t tot[3];
         hipLaunchKernelGGL(zero3_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->tmp_i64);
-        hipLaunchKernelGGL(gh_totals_kernel, dim3(1024), dim3(256), 0, ctx->stream, gh, row_idx, begin, count,
+        hipLaunchKernelGGL(gh_totals_kernel, dim3(512), dim3(256), 0, ctx->stream, gh, row_idx, begin, count,
                            ctx->tmp_i64);
         QG_HIP(ctx, hipMemcpyAsync(tot, ctx->tmp_i64, sizeof(tot), hipMemcpyDeviceToHost, ctx->stream));
         QG_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -424,7 +428,7 @@ int qgbdt_build_histograms(qgbdt_ctx* ctx, const void* bins, const int16_t* gh, 
                      ctx->step, mfb);
     if (rc != QGBDT_OK || !mfb) return rc;
     hipLaunchKernelGGL(zero3_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->tmp_i64);
-    hipLaunchKernelGGL(gh_totals_kernel, dim3(1024), dim3(256), 0, ctx->stream, gh, row_idx, begin, count, ctx->tmp_i64);
+    hipLaunchKernelGGL(gh_totals_kernel, dim3(512), dim3(256), 0, ctx->stream, gh, row_idx, begin, count, ctx->tmp_i64);
     QG_HIP(ctx, hipGetLastError());
     return launch_fix_frequent_bins(ctx, hist_out, ctx->tmp_i64, mfb);
 }
