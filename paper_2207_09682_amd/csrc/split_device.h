@@ -67,15 +67,22 @@ __device__ inline void reduce_features_wave(const FeatCand* cand, int F, const q
 
 // The same reduction by a group of `sub` consecutive lanes (a power of two, 64 at most; `sl` = lane inside
 // the group), so that one wavefront serves 64 / sub leaves at a time.  The winner's candidate travels with
-// the comparison: no load depends on another.
+// the comparison: no load depends on another.  Every lane of the group returns the winner's gain and feature
+// (feature < 0: no split).
 __device__ inline void reduce_features_lanes(const FeatCand* cand, int F, const qgbdt_leafstat& st, qgbdt_split* out,
-                                             int sl, int sub) {
+                                             int sl, int sub, double& gain, int& feature) {
     double bg = 0.0;
     int bf = -1, bb = -1;
     int64_t bl = 0;
-    for (int f = sl; f < F; f += sub) {
-        const FeatCand c = cand[f];
-        if (c.bin >= 0 && (c.gain > bg)) { bg = c.gain; bf = f; bb = c.bin; bl = c.left; }
+    for (int f0 = sl; f0 < F; f0 += 4 * sub) {  // four loads in flight
+        FeatCand c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = cand[min(f0 + u * sub, F - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {  // ascending features: strict > keeps the lowest
+            const int f = f0 + u * sub;
+            if (f < F && c[u].bin >= 0 && (c[u].gain > bg)) { bg = c[u].gain; bf = f; bb = c[u].bin; bl = c[u].left; }
+        }
     }
     for (int o = sub >> 1; o > 0; o >>= 1) {
         const double og = __shfl_xor(bg, o);
@@ -96,6 +103,8 @@ __device__ inline void reduce_features_lanes(const FeatCand* cand, int F, const 
         }
         *out = s;
     }
+    gain = bg;  // (all lanes of the group hold the winner)
+    feature = bf;
 }
 
 }  // namespace qgbdt

@@ -125,13 +125,15 @@ __device__ __forceinline__ uint32_t replay_key(int rank, int leaf) {
 }
 
 // Commit phase and choice of the round's batch.  One workgroup of 1024 threads.
+//  0. (at most 256 features) Half of the workgroup reduces the per-feature candidates of the histograms scanned
+//     last to their nodes' best splits, which saves the launch that would do it.
 //  1. All known nodes are kept sorted by the gain of their best split: a node's gain never changes, so
 //     the order of the previous call is read back and last round's children are merged in (each
 //     finds its place by a binary search and a count; old entries shift by the number of new ones
 //     in front of them).  A node's rank is the number of nodes with a strictly larger gain.
 //  2. One wavefront replays best-first selection: the open leaves are kept in an array indexed
-//     by leaf id whose entries combine (rank, leaf id), so the leaf with the largest gain (ties:
-//     lowest leaf id) is one wavefront-wide maximum; it is committed if it has been expanded
+//     by leaf id whose entries combine (rank, leaf id) and carry the node, so the leaf with the largest gain
+//     (ties: lowest leaf id) is one wavefront-wide maximum; it is committed if it has been expanded
 //     (its children become open leaves: the left one in its place, the right one as the next
 //     leaf id), else the replay stops.  Only the order is recorded.
 //  3. All threads write the outputs of the committed splits.
@@ -141,26 +143,13 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
                                                          int num_leaves, int batch_max, int max_expand, int p_max,
                                                          TreeOut out, const FeatCand* __restrict__ cand,
                                                          const ScanItem* __restrict__ scan_items) {
-    if (step->done) return;
+    // the fields of the growth state this kernel needs, in three loads that are in flight together
+    const int4* sp = reinterpret_cast<const int4*>(step);
+    const int4 st0 = sp[0], st1 = sp[1], st2 = sp[2];
+    if (st0.x) return;  // done
     extern __shared__ unsigned char plan_lds[];
-    if (cand) {
-        // 0. (matrices of at most 256 features) the per-feature candidates that the split scan has just left are
-        //    reduced here instead of in a launch of their own: groups of lanes as wide as the feature count (a power
-        //    of two, one wavefront at most) take a scanned histogram each and write its node's best split.
-        const int n_items = step->n_scan_items;
-        int sub = 1;
-        while (sub < F && sub < 64) sub <<= 1;
-        const int per_pass = (int)blockDim.x / sub;
-        const int grp = (int)threadIdx.x / sub, sl = (int)threadIdx.x % sub;
-        for (int item = grp; item < n_items; item += per_pass) {
-            const ScanItem it = scan_items[item];
-            if (!it.valid) continue;  // uniform over the group of lanes
-            reduce_features_lanes(cand + (int64_t)item * F, F, it.stat, it.out, sl, sub);
-        }
-        __syncthreads();  // the nodes' best splits are read below by other wavefronts of this workgroup
-    }
-    const int n_nodes0 = step->n_nodes;
-    const int n_old = step->n_sorted;        // nodes already in the sorted order (all but last round's children)
+    const int n_nodes0 = st0.y;
+    const int n_old = st2.z;             // nodes already in the sorted order (all but last round's children)
     const int m_new = n_nodes0 - n_old;
     const int cap = 2 * max_expand + 1;  // nodes
     const int P = n_nodes0;              // sorted positions in use
@@ -169,12 +158,15 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     unsigned long long* okeys = reinterpret_cast<unsigned long long*>(sidx + p_max);  // [p_max] the order so far
     int* oidx = reinterpret_cast<int*>(okeys + p_max);                                // [p_max]
     unsigned long long* nkey = reinterpret_cast<unsigned long long*>(oidx + p_max);   // [2*batch_max] keys of the new nodes
-    int* rankof = reinterpret_cast<int*>(nkey + 2 * batch_max);                  // [cap] -1: cannot be split, -2: split
+    // open leaves by leaf id: replay key (upper word; 0: no gain) and node (lower word)
+    unsigned long long* open = nkey + 2 * batch_max;                             // [num_leaves+1]
+    int* open_node = reinterpret_cast<int*>(open);                               // (the lower word of entry l is open_node[2 * l])
+    int* rankof = reinterpret_cast<int*>(open + num_leaves + 1);                 // [cap] -1: cannot be split, -2: split
     int* posof = rankof + cap;                                                   // [cap] sorted position
     int* child = posof + cap;                                                    // [cap] left child, -1 if not expanded
-    uint32_t* okey = reinterpret_cast<uint32_t*>(child + cap);                   // [num_leaves+1] by leaf id, 0: no gain
-    int* onode = reinterpret_cast<int*>(okey + num_leaves + 1);                  // [num_leaves+1] node of a leaf id
-    int* commit = onode + num_leaves + 1;                                        // [num_leaves] nodes committed, in order
+    int* commit = child + cap;                                                   // [num_leaves] nodes committed, in order
+    // per node, once the ranks are known (reuses the sorted keys): left child and the ranks of both children
+    unsigned long long* ninfo = skey;                                            // [cap]; ~0: not expanded
     int* commit_lid = commit + num_leaves;                                       // [num_leaves] their leaf ids
     int* flag = reinterpret_cast<int*>(okeys);  // [P] per sorted position, reuses the old order once it is merged
     int* flag2 = flag + p_max;                  // [P]
@@ -182,20 +174,68 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     __shared__ int s_done, s_ncommit, s_nleaves;
     __shared__ unsigned long long s_units;
     const int tid = threadIdx.x;
-    const int commits0 = step->n_commits, leaves0 = step->n_leaves;
+    const int commits0 = st0.w, leaves0 = st0.z;
     if (tid == 0) { s_done = 0; s_ncommit = 0; s_units = 0ull; }
     // A node's sort key never changes: the gain of its best split (0 bits when it has none).  The order of
     // the nodes known at the previous call is kept in global memory; only last round's children are new.
-    for (int i = tid; i < n_nodes0; i += blockDim.x) {
-        const Node* nd = &nodes[i];
-        const int st = nd->state;
-        const bool splittable = nd->best.feature >= 0 && nd->best.gain > 0.0;
-        const unsigned long long kb = splittable ? (unsigned long long)__double_as_longlong(nd->best.gain) : 0ull;
-        child[i] = nd->expanded ? nd->child : -1;
-        if (st == 1) onode[nd->leaf_id] = i;
-        rankof[i] = st == 2 ? -2 : (splittable ? 0 : -1);  // ranks are filled in below
-        if (i >= n_old) nkey[i - n_old] = kb;
-        else skey[i] = kb;  // by node id for now; gathered into the kept order next
+    //
+    // (matrices of at most 256 features) The new nodes' best splits are not in memory yet: the split scan has left
+    // one candidate per feature, which the lower half of the workgroup reduces here instead of in a launch of its
+    // own -- groups of lanes as wide as the feature count (a power of two, one wavefront at most) take a scanned
+    // histogram each, write its node's best split and this kernel's entries of the node -- while the upper half
+    // reads the known nodes back.  A node that has just been scanned is not expanded, and an open leaf only if it
+    // is the root.
+    const bool fused = cand != nullptr;
+    const int half = (int)blockDim.x / 2;
+    if (fused && tid < half) {
+        // as few lanes per histogram as lets all histograms be reduced at once (a lane then takes several
+        // features, four loads in flight): a second pass would wait for a second round of memory latencies
+        const int n_scan = st2.y;  // histograms scanned in the last round
+        int sub = 64;
+        while (sub > 1 && (sub / 2 >= F || (half / sub) < n_scan)) sub >>= 1;
+        const int per_pass = half / sub;
+        const int grp = tid / sub, sl = tid % sub;
+        for (int item = grp; item < n_scan; item += per_pass) {
+            const ScanItem it = scan_items[item];
+            double gain = 0.0;
+            int feature = -1;
+            if (it.valid)  // uniform over the group of lanes (a histogram that was not scanned leaves its node without a split)
+                reduce_features_lanes(cand + (int64_t)item * F, F, it.stat, it.out, sl, sub, gain, feature);
+            if (sl == 0) {
+                const int i = (int)((reinterpret_cast<const char*>(it.out) - reinterpret_cast<const char*>(&nodes[0].best)) /
+                                    (ptrdiff_t)sizeof(Node));
+                const bool splittable = feature >= 0 && gain > 0.0;
+                child[i] = -1;
+                if (i == 0) open_node[0] = 0;
+                rankof[i] = splittable ? 0 : -1;
+                nkey[i - n_old] = splittable ? (unsigned long long)__double_as_longlong(gain) : 0ull;
+            }
+        }
+    } else {
+        const int first = fused ? tid - half : tid, stride = fused ? half : (int)blockDim.x;
+        const int n_read = fused ? n_old : n_nodes0;
+        for (int i0 = first; i0 < n_read; i0 += 2 * stride) {  // two nodes per step: their loads are in flight together
+            int st[2], ex[2], ch[2], lid[2], ft[2];
+            double gn[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const Node* nd = &nodes[min(i0 + u * stride, n_read - 1)];
+                st[u] = nd->state; ex[u] = nd->expanded; ch[u] = nd->child; lid[u] = nd->leaf_id;
+                ft[u] = nd->best.feature; gn[u] = nd->best.gain;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int i = i0 + u * stride;
+                if (i >= n_read) break;
+                const bool splittable = ft[u] >= 0 && gn[u] > 0.0;
+                const unsigned long long kb = splittable ? (unsigned long long)__double_as_longlong(gn[u]) : 0ull;
+                child[i] = ex[u] ? ch[u] : -1;
+                if (st[u] == 1) open_node[2 * lid[u]] = i;
+                rankof[i] = st[u] == 2 ? -2 : (splittable ? 0 : -1);  // ranks are filled in below
+                if (i >= n_old) nkey[i - n_old] = kb;
+                else skey[i] = kb;  // by node id for now; gathered into the kept order next
+            }
+        }
     }
     __syncthreads();
     for (int p = tid; p < n_old; p += blockDim.x) {
@@ -211,7 +251,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         for (int u = 0; u < m_new; ++u) c += nkey[u] > kb ? 1 : 0;
         posof[oidx[p]] = p + c;
     }
-    for (int t = tid; t < m_new; t += blockDim.x) {
+    for (int t = (int)blockDim.x - 1 - tid; t < m_new; t += blockDim.x) {  // (from the last thread down: other wavefronts than the loop above, mostly)
         const unsigned long long kb = nkey[t];
         int lo = 0, hi = n_old;  // first old position with a smaller key
         while (lo < hi) {
@@ -246,8 +286,14 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     if (tid == 0) step->n_sorted = n_nodes0;
     __syncthreads();
     for (int l = tid; l < leaves0; l += blockDim.x) {
-        const int r = rankof[onode[l]];
-        okey[l] = r >= 0 ? replay_key(r, l) : 0u;
+        const int i = open_node[2 * l];
+        const int r = rankof[i];
+        open[l] = ((unsigned long long)(r >= 0 ? replay_key(r, l) : 0u) << 32) | (uint32_t)i;
+    }
+    for (int i = tid; i < n_nodes0; i += blockDim.x) {  // (overwrites the sorted keys: the ranks made from them are final)
+        const int c0 = child[i];
+        ninfo[i] = c0 < 0 ? ~0ull
+                          : ((unsigned long long)(uint32_t)c0 << 32) | ((uint32_t)(rankof[c0] + 2) << 16) | (uint32_t)(rankof[c0 + 1] + 2);
     }
     __syncthreads();
 
@@ -255,23 +301,35 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         int n_commits = commits0, n_leaves = leaves0;
         for (;;) {
             if (n_commits >= num_leaves - 1) { if (tid == 0) s_done = 1; break; }
-            uint32_t m = 0u;
-            for (int l = tid; l < n_leaves; l += 64) m = max(m, okey[l]);
-            m = wave_max_u32(m);
+            // a lane's best open leaf (four loads in flight per step), then the wavefront's
+            uint32_t mk = 0u;
+            int mn = 0;
+            for (int l0 = tid; l0 < n_leaves; l0 += 256) {
+                unsigned long long e[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) e[u] = (l0 + 64 * u < n_leaves) ? open[l0 + 64 * u] : 0ull;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t k = (uint32_t)(e[u] >> 32);
+                    if (k > mk) { mk = k; mn = (int)(uint32_t)e[u]; }
+                }
+            }
+            const uint32_t m = wave_max_u32(mk);
             if (m == 0u) { if (tid == 0) s_done = 1; break; }  // no open leaf has a gain > 0
+            // keys are distinct (they hold the leaf id): exactly one lane has the maximum, and its node
+            const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(mk == m)) - 1);
+            const int bi = __builtin_amdgcn_readlane(mn, src);
             const int wl = 0xffff - (int)(m & 0xffffu);
-            const int bi = onode[wl];
-            const int c0 = child[bi];
-            if (c0 < 0) break;  // the next split is not known yet
+            const unsigned long long info = ninfo[bi];
+            if (info == ~0ull) break;  // the next split is not known yet
             // commit: the left child takes the leaf's place, the right child the next leaf id
-            const int r0 = rankof[c0], r1 = rankof[c0 + 1];
+            const int c0 = (int)(info >> 32);
+            const int r0 = (int)((info >> 16) & 0xffffu) - 2, r1 = (int)(info & 0xffffu) - 2;
             if (tid == 0) {
                 commit[n_commits - commits0] = bi;
                 commit_lid[n_commits - commits0] = wl;
-                okey[wl] = r0 >= 0 ? replay_key(r0, wl) : 0u;
-                onode[wl] = c0;
-                okey[n_leaves] = r1 >= 0 ? replay_key(r1, n_leaves) : 0u;
-                onode[n_leaves] = c0 + 1;
+                open[wl] = ((unsigned long long)(r0 >= 0 ? replay_key(r0, wl) : 0u) << 32) | (uint32_t)c0;
+                open[n_leaves] = ((unsigned long long)(r1 >= 0 ? replay_key(r1, n_leaves) : 0u) << 32) | (uint32_t)(c0 + 1);
             }
             n_commits += 1; n_leaves += 1;
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -310,7 +368,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     // Batch.  One expansion is certain (the leaf the replay stopped at); expansions beyond those
     // that the remaining certain ones will need may be spent on speculation.
     const int remaining = (num_leaves - 1) - (commits0 + n_commit);
-    const int n_expanded0 = step->n_expanded;
+    const int n_expanded0 = st1.x;
     const int spare = (max_expand - n_expanded0) - remaining;
     int want = 1 + (spare > 0 ? spare : 0);
     if (want > remaining) want = remaining;
@@ -327,8 +385,9 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         if (rankof[i] == -2) flag[posof[i]] = 1;  // split in an earlier call
     const int n_leaves_now = s_nleaves;
     for (int l = tid; l < n_leaves_now; l += blockDim.x) {
-        if (okey[l] == 0u) continue;
-        const int i = onode[l];
+        const unsigned long long e = open[l];
+        if ((e >> 32) == 0ull) continue;
+        const int i = (int)(uint32_t)e;
         const int c0 = child[i];
         if (c0 < 0) {
             const int p = posof[i];
@@ -373,7 +432,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
     int nseg = 0;
     if (tid < n_batch) nseg = (int)((nodes[batch[tid].node].count + PART_SEG - 1) / PART_SEG);
     const int incl = block_scan_incl(nseg, s_tmp);
-    const int n_nodes = n_nodes0, n_slots = step->n_slots;
+    const int n_nodes = n_nodes0, n_slots = st1.y;
     if (tid < n_batch) {
         const int i = batch[tid].node;
         batch[tid].seg_start = incl - nseg;
@@ -389,7 +448,7 @@ __global__ __launch_bounds__(1024) void tree_plan_kernel(StepState* step, Node* 
         step->n_nodes = n_nodes + 2 * n_batch;
         step->n_slots = n_slots + n_batch;
         step->n_expanded = n_expanded0 + n_batch;
-        step->rounds += 1;
+        step->rounds = st1.w + 1;
         step->n_scan_items = 2 * n_batch;
     }
 }
