@@ -183,6 +183,22 @@ def main():
     total_units = int(units.item())
     n_leaves_last = int(tree.n_leaves.item())
 
+    # ---- the first tree of a run (every |g| = 1/2, h = 1/4 for the logistic loss: all rows carry the extreme
+    # quantized values, the tightest case of the accumulator bounds), which the timed steps above leave out
+    # when there is a warm-up step ----
+    first_tree = None
+    if W > 0:
+        ctx.grow_tree(bins, gs[0], hs[0], bits_g, bits_h, cfg.seed, 0, L, cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
+        torch.cuda.synchronize()
+        f0 = time.perf_counter()
+        for _ in range(3):
+            ctx.grow_tree(bins, gs[0], hs[0], bits_g, bits_h, cfg.seed, 0, L, cfg.min_data_in_leaf, acc_width=args.acc_width, tree=tree)
+        torch.cuda.synchronize()
+        first_tree = {"ms_per_tree": (time.perf_counter() - f0) / 3 * 1e3, "repetitions": 3,
+                      "leaves": int(tree.n_leaves.item()), "hist_units": int(tree.hist_units.item()),
+                      "what": "iteration 0 (scores all zero), timed apart: the timed steps are iterations "
+                              f"{W}..{W + K - 1} of the same boosting run"}
+
     # ---- whole boosting iterations on the device (derivatives + tree + score update) ----
     sc = torch.zeros(N, device=dev)
     label = wl.label.to(dev).float().contiguous()
@@ -318,6 +334,7 @@ def main():
         "growth": {"rounds_per_tree": sum(x[0] for x in stats) / K, "expanded_per_tree": sum(x[1] for x in stats) / K,
                    "committed_per_tree": sum(x[2] for x in stats) / K},
         "boost_iteration": boost,
+        "first_tree": first_tree,
         "cpu_baseline": cpu,
         "paper_context": "paper: V100, Higgs 10.5M x 28, 3-bit: 4.74 s histogram time / 500 trees = 9.5 ms per tree "
                          "(another machine; context, not the target)",
