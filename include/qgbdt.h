@@ -74,7 +74,7 @@ typedef struct {
     int32_t n_features; /* J of Algorithm 1 */
     int32_t n_bins;     /* bins per feature, 2 .. 256 (uint8 bins) or 2 .. 1024 (uint16 bins) */
     int32_t bin_bytes;  /* 1: uint8 bins; 2: uint16 bins (every `bins` argument is then uint16 [n_rows][n_features]) */
-    int32_t max_leaves; /* largest num_leaves grow_tree will be asked for (at most ~680: the growth
+    int32_t max_leaves; /* largest num_leaves grow_tree will be asked for (at most 658: the growth
                            bookkeeping of all nodes lives in one workgroup's LDS) */
 } qgbdt_shape;
 

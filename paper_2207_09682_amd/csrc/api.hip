@@ -259,8 +259,8 @@ static int check_shape(const qgbdt_shape* shape) {
     // the plan kernel keeps its sort and replay state of all nodes in LDS
     const size_t L = (size_t)shape->max_leaves, max_nodes = 6 * L + 1, p_max = max_nodes + (max_nodes & 1);
     const size_t plan_lds = p_max * 24 + L * 16 + max_nodes * 12 + (4 * L + 8) * 4;
-    if (plan_lds > 160 * 1024)
-        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB, about 690 leaves)",
+    if (plan_lds + 512 > 160 * 1024)  // (the kernel's few static words come on top)
+        return set_error(nullptr, QGBDT_E_UNSUPPORTED, "max_leaves=%d: the growth bookkeeping would need %zu bytes of LDS (limit 160 KB: at most 658 leaves)",
                          shape->max_leaves, plan_lds);
     return QGBDT_OK;
 }

@@ -216,7 +216,7 @@ constexpr int REFIT_PARTS = 32;
 constexpr int QUANT_PARTS = 2048;  // most workgroups of the quantizer kernels
 constexpr int PART_SEG = 1024;  // rows per partition segment of the batched partition
 // Most nodes expanded in one round = most builds of a histogram launch (the leaf budget; the growth bookkeeping
-// limits it to about 690).  Kernels keep the first work item of every build / node in LDS and search there: a binary
+// limits it to 658).  Kernels keep the first work item of every build / node in LDS and search there: a binary
 // search through global memory costs a chain of dependent loads per work item.
 constexpr int TABLE_MAX = 768;
 

@@ -593,7 +593,7 @@ static size_t plan_kernel_lds(const qgbdt_ctx* ctx, int num_leaves) {
 
 int prepare_tree_kernels(qgbdt_ctx* ctx) {
     const size_t plan_lds = plan_kernel_lds(ctx, ctx->shape.max_leaves);
-    if (plan_lds > 160 * 1024)
+    if (plan_lds + 512 > 160 * 1024)  // (the kernel's few static words come on top)
         return set_error(ctx, QGBDT_E_UNSUPPORTED, "max_leaves=%d needs %zu bytes of LDS for the growth bookkeeping (limit 160 KB)",
                          ctx->shape.max_leaves, plan_lds);
     if (plan_lds > 48 * 1024)

@@ -461,6 +461,29 @@ def test_grow_tree_cfg5_full_leaf_budget():
     _lockstep(cfg, 150_000, 40, 1, 511)
 
 
+def test_grow_tree_bushy_tree_near_the_leaf_limit():
+    # 658 leaves (the most the LDS of the growth bookkeeping holds) on twelve two-valued features of about equal
+    # weight: nodes of one depth have about the same gain, the tree grows level by level, and the late rounds expand
+    # a hundred nodes and more at once -- so many scanned histograms that the plan kernel's feature reduce gives each
+    # of them one or two lanes only
+    N, F, nb, L = 300_000, 12, 2, 658
+    rng = np.random.default_rng(77)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint8)
+    w = 1.0 - 0.03 * np.arange(F)
+    logit = ((bins.astype(np.float64) - 0.5) * w).sum(axis=1)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-logit))).astype(np.float32)
+    g = (0.5 - y).astype(np.float32); h = np.full(N, 0.25, np.float32)
+    ctx = _ctx(N, F, nb, L=L)
+    t = ctx.grow_tree(torch.from_numpy(bins).cuda(), torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), 3, 3, 5, 0, L,
+                      min_data_in_leaf=1)
+    e = oracle.grow_tree(bins, nb, g, h, 3, 3, 5, 0, L, min_data=1)
+    _compare_tree(t, e, N)
+    rounds, expanded, committed, _ = ctx.tree_stats()
+    assert committed == L - 1 and expanded >= committed
+    # the first eight rounds can expand 255 nodes at most (a node's parent is expanded in an earlier round)
+    assert rounds <= 16 and (expanded - 255) / (rounds - 8) >= 64, (rounds, expanded)
+
+
 def test_quantize_unaligned_pointers():
     # g, h that do not start on a 16-byte boundary take the scalar kernels
     N = 70_001
