@@ -518,7 +518,9 @@ def test_grow_tree_degenerate_cases():
 
 
 @pytest.mark.parametrize("N,F,nb,L", [(1, 1, 2, 4), (2, 1, 2, 4), (64, 3, 4, 8), (1000, 5, 16, 15), (3000, 30, 63, 31),
-                                      (5000, 65, 32, 31), (4000, 17, 255, 63), (2500, 130, 8, 15)])
+                                      (5000, 65, 32, 31), (4000, 17, 255, 63), (2500, 130, 8, 15),
+                                      (3000, 4096, 16, 7), (2000, 255, 256, 7), (4000, 124, 255, 15), (4000, 132, 200, 15),
+                                      (1500, 2, 2, 4), (6000, 16, 256, 31)])
 def test_grow_tree_small_and_ragged_shapes(N, F, nb, L):
     # every kernel variant of the tree path at small sizes: rows narrower than a dword, ragged rows,
     # tiles cut so that none is narrower than a dword, a single row, leaves of one row

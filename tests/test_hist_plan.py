@@ -16,6 +16,10 @@ SHAPES = [  # n_rows, n_features, n_bins, max_leaves, bin_bytes
     (5000, 36, 100, 31, 1), (30_000, 72, 256, 31, 1), (100_000, 1, 2, 4, 1), (100_000, 2048, 256, 15, 1),
     (20_000, 10, 600, 31, 2), (9000, 33, 1024, 31, 2), (5000, 100, 300, 31, 2), (3000, 1, 700, 7, 2),
     (2_000_000, 40, 600, 63, 2), (160_000_000, 28, 255, 15, 1), (2_400_000, 2000, 63, 7, 1),
+    # edges: very wide rows, many bins of both widths, tile widths around the 128-byte piece, the leaf limit
+    (50_000, 4096, 256, 31, 1), (20_000, 10_000, 64, 15, 1), (3000, 2000, 1024, 7, 2), (1000, 7, 2, 658, 1),
+    (300, 255, 256, 7, 1), (100_000, 16, 256, 15, 1), (100_000, 124, 255, 15, 1), (100_000, 128, 255, 15, 1),
+    (50_000, 132, 200, 15, 1), (8000, 257, 1024, 15, 2),
 ]
 BITS = [(2, 2), (3, 3), (4, 4), (5, 5), (3, 8), (3, 0), (8, 8)]
 
