@@ -1018,6 +1018,7 @@ HistPlan make_hist_plan_for(const qgbdt_shape& s, int bits_g, int bits_h, int ac
             q.lds_bytes = (int32_t)lds;
             q.slot_bytes = (int32_t)((words * 8 + 15) & ~(int64_t)15);
             q.max_groups = 256;
+            q.max_items = 256;  // one build, one group per CU
             q.max_lanes = 256;
             q.single_rows = 0x40000000;  // a group folds its chunks locally: no limit on its length
             return q;

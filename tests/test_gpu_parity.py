@@ -162,6 +162,33 @@ def test_histogram_worst_case_multi_chunk_groups_with_unaligned_head():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("F", [16, 40, 48])
+def test_histogram_two_level_byte_stream_other_row_widths(F):
+    # long contiguous builds of narrow matrices take the byte-stream kernel's two-level form (32-bit working words
+    # folded into 64-bit words in LDS): here for rows of 16, 40 and 48 bytes (64, 60 and 63 lanes per iteration), slices
+    # that start on and off a 16-byte boundary, 4- and 5-bit values with every row at the extremes and one feature
+    # that keeps all rows in one bin -- a fold that came one row late would overflow a field
+    N, nb = 2_600_003, 255
+    from paper_2207_09682_amd.binding import describe_hist_plan
+    gen = torch.Generator(device="cuda").manual_seed(F)
+    dbins = torch.randint(0, 5, (N, F), dtype=torch.uint8, device="cuda", generator=gen)
+    dbins[:, 1] = 3
+    bins = dbins.cpu().numpy()
+    ctx = _ctx(N, F, nb, L=15)
+    rng = np.random.default_rng(F)
+    for bg, bh in ((5, 5), (4, 4)):
+        kg, kh = 2 ** (bg - 1) - 1, 2 ** bh - 2
+        assert describe_hist_plan(N, F, nb, 15, 1, bg, bh, 16, False, rows=N - 3)["two_level"] == 1
+        gq = np.where(rng.random(N) < 0.97, kg, -kg).astype(np.int8); hq = np.full(N, kh, np.uint8)
+        gh = torch.from_numpy(_pack_gh(gq, hq)).cuda()
+        for begin in (0, 1, 3):
+            exp = _pack_hist(oracle.build_histograms(bins, nb, gq, hq, begin=begin, count=N - begin))
+            got = ctx.build_histograms(dbins, gh, begin=begin, count=N - begin, bits_g=bg, bits_h=bh, acc_width=16)
+            assert np.array_equal(got.cpu().numpy().reshape(nb, F), exp), (bg, begin)
+    del ctx, dbins
+    torch.cuda.empty_cache()
+
+
 def test_subtract_bit_exact():
     N, F, nb = 40000, 28, 255
     rng = np.random.default_rng(2)

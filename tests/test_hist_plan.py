@@ -20,6 +20,8 @@ SHAPES = [  # n_rows, n_features, n_bins, max_leaves, bin_bytes
     (50_000, 4096, 256, 31, 1), (20_000, 10_000, 64, 15, 1), (3000, 2000, 1024, 7, 2), (1000, 7, 2, 658, 1),
     (300, 255, 256, 7, 1), (100_000, 16, 256, 15, 1), (100_000, 124, 255, 15, 1), (100_000, 128, 255, 15, 1),
     (50_000, 132, 200, 15, 1), (8000, 257, 1024, 15, 2),
+    # long narrow matrices of other row widths (two-level byte-stream builds)
+    (3_000_000, 16, 255, 15, 1), (3_000_000, 40, 255, 15, 1), (3_000_000, 48, 255, 15, 1), (6_000_000, 20, 100, 15, 1),
 ]
 BITS = [(2, 2), (3, 3), (4, 4), (5, 5), (3, 8), (3, 0), (8, 8)]
 
