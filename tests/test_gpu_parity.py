@@ -366,6 +366,15 @@ def test_grow_tree_cfg5_reduced_ranking():
 # (same context shape, same entry point): whole trees against the oracle, every split, every
 # row position and every leaf.
 
+@pytest.mark.parametrize("F,bits,acc", [(16, (4, 4), 0), (40, (5, 5), 16), (48, (4, 4), 0)])
+def test_grow_tree_long_narrow_matrices_of_other_widths(F, bits, acc):
+    # whole trees whose root build takes the byte-stream kernel's two-level form at row widths other than
+    # configuration 3's 28 bytes (2.6 M rows: every CU's share spans several chunks of 4- or 5-bit values)
+    cfg = workloads.CONFIGS[2]
+    _lockstep(cfg, 2_600_000, F, 2, 31, acc=acc, bits=bits, device="cuda")
+    torch.cuda.empty_cache()
+
+
 def test_full_size_cfg2():
     cfg = workloads.CONFIGS[1]
     _lockstep(cfg, cfg.n_rows, cfg.n_features, 3, cfg.num_leaves, device="cuda")
