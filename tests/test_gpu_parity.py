@@ -768,6 +768,34 @@ def test_boost_iterations_lambdarank_lock_step():
         assert np.array_equal(score.cpu().numpy(), exp)
 
 
+def test_work_runs_on_torchs_current_stream():
+    # the library enqueues on the stream torch considers current: inputs produced by torch kernels on a side
+    # stream (default priority) are consumed without a synchronisation in between, and torch kernels that
+    # follow on that stream see the tree
+    N, F, nb, L = 200_000, 28, 63, 31
+    rng = np.random.default_rng(12)
+    bins = rng.integers(0, nb, (N, F)).astype(np.uint8)
+    y = (rng.random(N) < 1.0 / (1.0 + np.exp(-(bins[:, 3].astype(np.float64) - nb / 2) * 6.0 / nb))).astype(np.float32)
+    dbins = torch.from_numpy(bins).cuda(); dy = torch.from_numpy(y).cuda()
+    ctx = _ctx(N, F, nb, L=L)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        score = torch.zeros(N, device="cuda")
+        for _ in range(20):                                 # a queue of torch work in front of the library's
+            score = score * 0.5 + 0.0
+        p = torch.sigmoid(score)
+        g = (p - dy).contiguous(); h = (p * (1 - p)).contiguous()
+        t = ctx.grow_tree(dbins, g, h, 3, 3, 8, 0, L, min_data_in_leaf=20)
+        n_leaves_dev = t.n_leaves.clone()                   # a torch kernel behind the library's work
+        split_feature = t.split_feature.clone()
+    side.synchronize()
+    e = oracle.grow_tree(bins, nb, g.cpu().numpy(), h.cpu().numpy(), 3, 3, 8, 0, L, min_data=20)
+    _compare_tree(t, e, N)
+    assert int(n_leaves_dev.item()) == e.n_leaves
+    assert np.array_equal(split_feature.cpu().numpy()[: e.n_leaves - 1], e.split_feature)
+
+
 def test_create_rejects_leaf_budgets_beyond_the_bookkeeping():
     from paper_2207_09682_amd import QgbdtError
     with pytest.raises(QgbdtError):
